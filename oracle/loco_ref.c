@@ -1,0 +1,213 @@
+/*
+ * loco_ref.c -- CPU oracle for LoCo's per-step local path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
+ * GPU library must compute.  Only the tests, the smoke check and the
+ * cpu_baseline leg of the benchmark may build, load or call it; the product
+ * library never does, and the two share no code.
+ *
+ * What it follows (LoCo, arXiv 2407.04480):
+ *   Alg. 1 step 1 / Eq. 2   h = g + e~            (error state kept in fp32, so
+ *                                                  decompressor(e) is the identity)
+ *   Eq. 1 / Eq. 3           q = round_p-bit(h * s): nearest integer, clamped to
+ *                           [-2^(p-1), 2^(p-1)-1]
+ *   Alg. 1 step 2 / Eq. 1   d = float(q) / s
+ *   Eq. 4                   delta = h - d
+ *   Eq. 5                   e~' = (1-beta) e~ + beta delta,  e~_0 = 0
+ *   Eq. 7                   periodic reset: the new state is 0
+ *   Alg. 1 step 3 / Eq. 8   g~ = (1/N) sum_n decompressor(q^n)
+ *
+ * Readings taken where the paper is silent (each is listed in the design notes):
+ *   - the scale is chosen per block of `block_size` consecutive elements:
+ *     s_b = qmax / max|h| over the block, stored as the step D_b = max|h| / qmax;
+ *     the compressor multiplies by r_b = 1 / D_b, the decompressor multiplies by D_b
+ *     (the same D_b on the sender and on every receiver);
+ *   - "nearest integer" ties go to the even integer (rintf in the default mode);
+ *   - a block whose step would be zero or subnormal (D_b < FLT_MIN) stores
+ *     D_b = +0 and all-zero codes, so the whole of h goes into the error;
+ *   - 4-bit codes are two's complement nibbles, element 2j in the low nibble of
+ *     byte j and element 2j+1 in the high nibble; a missing last nibble is 0;
+ *     8-bit codes are int8;
+ *   - all arithmetic is IEEE binary32, one rounding per written operation, the
+ *     only fused operation being the fmaf of Eq. 5; the sum of Eq. 8 runs over
+ *     the workers in index order and is multiplied by fl(1/N).
+ * The precision is binary32, not binary64, because the codes are integers that
+ * floating point decides and the error state feeds the next step's codes: both
+ * sides have to take those decisions in the same precision.
+ *
+ * Pins (tests/test_oracle_pins.py): hand-worked dyadic example, exact
+ * reconstruction d + delta = h, rounding bound of Lemma 5, closed form of the
+ * Eq. 5 recurrence, beta = 1 (Eq. 4) and beta = 0, zero-error fixed point,
+ * brute-force nearest level in binary64, the telescoping identity of Lemma 1,
+ * the literal fixed-scale form of Eq. 1 at s = 2^19, reset, and Eq. 8 at N = 1.
+ *
+ * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC (see oracle/__init__.py).
+ */
+#include <float.h>
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+enum { LOCO_REF_OK = 0, LOCO_REF_BAD_ARG = 1 };
+enum { LOCO_REF_F32 = 0, LOCO_REF_BF16 = 1 };
+
+/* bf16 is the upper half of a binary32: widening is exact. */
+static float grad_at(const void *grad, int dtype, size_t i)
+{
+    if (dtype == LOCO_REF_F32)
+        return ((const float *)grad)[i];
+    uint32_t bits = (uint32_t)((const uint16_t *)grad)[i] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return f;
+}
+
+static int args_ok(size_t n, int bits, int block_size)
+{
+    (void)n;
+    return (bits == 4 || bits == 8) && block_size >= 1;
+}
+
+/* e~_0 = 0 (below Eq. 5); also the hard form of the Eq. 7 reset. */
+int loco_ref_error_state_init(float *err_state, size_t n)
+{
+    if (n && !err_state)
+        return LOCO_REF_BAD_ARG;
+    for (size_t i = 0; i < n; ++i)
+        err_state[i] = 0.0f;
+    return LOCO_REF_OK;
+}
+
+/*
+ * Alg. 1 steps 1-2 on the blocks [block_lo, block_hi) of one shard of n elements.
+ * Blocks are independent, so any split into block ranges gives the same bytes;
+ * with 4-bit codes a range must start at an even element index.
+ */
+int loco_ref_compensate_quantize_blocks(const void *grad, int grad_dtype, float *err_state,
+                                        size_t n, int bits, int block_size, float beta, int reset,
+                                        uint8_t *codes_out, float *scales_out,
+                                        size_t block_lo, size_t block_hi)
+{
+    if (!args_ok(n, bits, block_size) || !(beta >= 0.0f && beta <= 1.0f))
+        return LOCO_REF_BAD_ARG;
+    if (grad_dtype != LOCO_REF_F32 && grad_dtype != LOCO_REF_BF16)
+        return LOCO_REF_BAD_ARG;
+    if (n && (!grad || !err_state || !codes_out || !scales_out))
+        return LOCO_REF_BAD_ARG;
+
+    const int qmax = (1 << (bits - 1)) - 1; /* Eq. 1: range -2^(p-1) .. 2^(p-1)-1 */
+    const int qmin = -(1 << (bits - 1));
+    const size_t B = (size_t)block_size;
+    const float one_minus_beta = 1.0f - beta;
+
+    for (size_t b = block_lo; b < block_hi; ++b) {
+        const size_t lo = b * B;
+        const size_t hi = (lo + B < n) ? lo + B : n;
+        if (lo >= n)
+            break;
+
+        /* block max of the compensated gradient h = g + e~ (Eq. 2) */
+        float amax = 0.0f;
+        for (size_t i = lo; i < hi; ++i) {
+            float h = grad_at(grad, grad_dtype, i) + err_state[i];
+            float ah = fabsf(h);
+            if (ah > amax)
+                amax = ah;
+        }
+
+        float D = amax / (float)qmax; /* the step 1/s_b */
+        float r = 0.0f;               /* s_b */
+        int dead = D < FLT_MIN;       /* zero or subnormal step: nothing to encode */
+        if (dead)
+            D = 0.0f;
+        else
+            r = 1.0f / D;
+        scales_out[b] = D;
+
+        for (size_t i = lo; i < hi; ++i) {
+            float e = err_state[i];
+            float h = grad_at(grad, grad_dtype, i) + e; /* Eq. 2 */
+            int q = 0;
+            if (!dead) {
+                q = (int)rintf(h * r); /* Eq. 1, 3: nearest integer ... */
+                if (q > qmax)          /* ... within the p-bit range */
+                    q = qmax;
+                if (q < qmin)
+                    q = qmin;
+            }
+            float d = (float)q * D;   /* decompressor, Eq. 1 */
+            float delta = h - d;      /* Eq. 4 */
+            float bd = beta * delta;
+            err_state[i] = reset ? 0.0f : fmaf(one_minus_beta, e, bd); /* Eq. 5 / Eq. 7 */
+
+            if (bits == 8) {
+                codes_out[i] = (uint8_t)(int8_t)q;
+            } else if ((i & 1) == 0) {
+                codes_out[i >> 1] = (uint8_t)(q & 15);
+            } else {
+                codes_out[i >> 1] = (uint8_t)(codes_out[i >> 1] | ((q & 15) << 4));
+            }
+        }
+    }
+    return LOCO_REF_OK;
+}
+
+/* Alg. 1 steps 1-2 on a whole shard; err_state is read and overwritten. */
+int loco_ref_compensate_quantize(const void *grad, int grad_dtype, float *err_state, size_t n,
+                                 int bits, int block_size, float beta, int reset,
+                                 uint8_t *codes_out, float *scales_out)
+{
+    if (!args_ok(n, bits, block_size))
+        return LOCO_REF_BAD_ARG;
+    size_t nb = (n + (size_t)block_size - 1) / (size_t)block_size;
+    return loco_ref_compensate_quantize_blocks(grad, grad_dtype, err_state, n, bits, block_size,
+                                               beta, reset, codes_out, scales_out, 0, nb);
+}
+
+static int code_at(const uint8_t *codes, int bits, size_t i)
+{
+    if (bits == 8)
+        return (int)(int8_t)codes[i];
+    int nib = (codes[i >> 1] >> (4 * (int)(i & 1))) & 15;
+    return (nib ^ 8) - 8; /* two's complement nibble */
+}
+
+/*
+ * Alg. 1 step 3 / Eq. 8 on the elements [elem_lo, elem_hi): decode every worker's
+ * payload with that worker's block step and average in binary32.  Payload w is
+ * codes + w*code_stride_bytes, scales + w*scale_stride_elems.
+ */
+int loco_ref_dequant_reduce_range(const uint8_t *codes, size_t code_stride_bytes,
+                                  const float *scales, size_t scale_stride_elems,
+                                  int num_workers, size_t n, int bits, int block_size,
+                                  float *grad_out, size_t elem_lo, size_t elem_hi)
+{
+    if (!args_ok(n, bits, block_size) || num_workers < 1)
+        return LOCO_REF_BAD_ARG;
+    if (n && (!codes || !scales || !grad_out))
+        return LOCO_REF_BAD_ARG;
+    if (elem_hi > n)
+        elem_hi = n;
+    const float inv = 1.0f / (float)num_workers;
+    for (size_t i = elem_lo; i < elem_hi; ++i) {
+        size_t b = i / (size_t)block_size;
+        float acc = 0.0f;
+        for (int w = 0; w < num_workers; ++w) {
+            int q = code_at(codes + (size_t)w * code_stride_bytes, bits, i);
+            float D = scales[(size_t)w * scale_stride_elems + b];
+            float d = (float)q * D;
+            acc = acc + d;
+        }
+        grad_out[i] = acc * inv;
+    }
+    return LOCO_REF_OK;
+}
+
+int loco_ref_dequant_reduce(const uint8_t *codes, size_t code_stride_bytes, const float *scales,
+                            size_t scale_stride_elems, int num_workers, size_t n, int bits,
+                            int block_size, float *grad_out)
+{
+    return loco_ref_dequant_reduce_range(codes, code_stride_bytes, scales, scale_stride_elems,
+                                         num_workers, n, bits, block_size, grad_out, 0, n);
+}

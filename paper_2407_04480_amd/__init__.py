@@ -1,0 +1,26 @@
+"""MI355X-native implementation of LoCo's per-step local path (arXiv 2407.04480, Alg. 1).
+
+`binding` wraps the C-ABI library (include/loco.h) built from csrc/*.hip;
+`workloads` makes the seeded synthetic gradients; `build` compiles the library.
+Importing the package loads nothing: the library is opened on first use and a
+missing library is an error, never a fallback.
+"""
+from .binding import (  # noqa: F401
+    LocoError,
+    library_path,
+    loco_code_bytes,
+    loco_num_blocks,
+    loco_error_state_init,
+    loco_compensate_quantize,
+    loco_dequant_reduce,
+)
+
+__all__ = [
+    "LocoError",
+    "library_path",
+    "loco_code_bytes",
+    "loco_num_blocks",
+    "loco_error_state_init",
+    "loco_compensate_quantize",
+    "loco_dequant_reduce",
+]

@@ -1,0 +1,471 @@
+"""Checks that pin the CPU oracle to what the paper and arithmetic fix.
+
+Each check takes a loaded oracle library handle, so the same checks can be run
+on the real oracle (they must pass) and on copies with a planted mistake (at
+least one must fail; see test_oracle_mutants.py).  Nothing here calls the GPU.
+
+Citations are to LoCo, arXiv 2407.04480.
+"""
+from __future__ import annotations
+
+import os
+
+import numpy as np
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+FLT_MIN = np.float32(np.finfo(np.float32).tiny)
+
+
+# ---------------------------------------------------------------- helpers
+def unpack(codes: np.ndarray, n: int, bits: int) -> np.ndarray:
+    """Integer codes from packed bytes (int8, or two's complement nibbles, low first)."""
+    if bits == 8:
+        return codes[:n].view(np.int8).astype(np.int64)
+    nib = np.empty(2 * codes.size, dtype=np.int64)
+    nib[0::2] = codes & 15
+    nib[1::2] = codes >> 4
+    nib = nib[:n]
+    return np.where(nib >= 8, nib - 16, nib)
+
+
+def qrange(bits):
+    return -(1 << (bits - 1)), (1 << (bits - 1)) - 1
+
+
+def block_index(n, B):
+    return np.arange(n) // B
+
+
+def rng_grad(rng, n, kind="normal", scale=1e-3):
+    if kind == "normal":
+        g = rng.standard_normal(n) * scale
+    elif kind == "student":
+        g = rng.standard_t(3, n) * scale
+    elif kind == "uniform":
+        g = rng.uniform(-scale, scale, n)
+    elif kind == "wide":  # magnitudes over many binades
+        g = rng.standard_normal(n) * np.exp2(rng.integers(-40, 10, n))
+    else:
+        raise ValueError(kind)
+    return g.astype(np.float32)
+
+
+def to_bf16_bits(x32: np.ndarray) -> np.ndarray:
+    """float32 -> bf16 bit patterns, round to nearest even (input-making helper)."""
+    u = x32.view(np.uint32).astype(np.uint64)
+    u = u + 0x7FFF + ((u >> 16) & 1)
+    return (u >> 16).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (b.astype(np.uint32) << 16).view(np.float32)
+
+
+def cq(lib, g, e, bits, B, beta, reset=0, threads=1):
+    return oracle.compensate_quantize(g, e, bits, B, beta, reset, threads=threads, lib=lib)
+
+
+def decode1(lib, codes, scales, n, bits, B):
+    return oracle.dequant_reduce(codes, scales, 1, n, bits, B, lib=lib)
+
+
+def ulp32(x):
+    x = np.abs(x.astype(np.float32))
+    return np.spacing(x).astype(np.float64)
+
+
+# ---------------------------------------------------------------- the pins
+def check_worked_example(lib):
+    """Hand-derived dyadic two-step example (Alg. 1 steps 1-2; Eq. 1-5)."""
+    rows = {}
+    with open(os.path.join(GOLDEN, "worked_example_p4_b8.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, *vals = line.split()
+            rows[key] = vals
+    unit = 2.0 ** int(rows["unit_log2"][0])
+    bits, B, beta = int(rows["bits"][0]), int(rows["block"][0]), float(rows["beta"][0])
+    vec = lambda k: (np.array([float(v) for v in rows[k]]) * unit).astype(np.float32)
+    g = vec("g")
+    e = np.zeros_like(g)
+    oracle.error_state_init(e, lib=lib)
+    for step, nxt in ((0, "e1"), (1, "e2")):
+        if step == 1:
+            assert np.array_equal((g + e), vec("h1"))
+        codes, scales = cq(lib, g, e, bits, B, beta)
+        want_bytes = np.array([int(b, 16) for b in rows[f"bytes{step}"]], dtype=np.uint8)
+        assert np.array_equal(codes, want_bytes), (step, codes, want_bytes)
+        assert np.array_equal(unpack(codes, g.size, bits), [int(v) for v in rows[f"q{step}"]])
+        assert scales.tolist() == [float(rows[f"scale{step}"][0]) * unit]
+        assert np.array_equal(e, vec(nxt)), (step, e / unit)
+
+
+def check_exact_reconstruction(lib):
+    """Eq. 4: d + delta = h.  With beta = 1 the new state is delta itself."""
+    rng = np.random.default_rng(101)
+    for bits, B, kind in ((4, 256, "normal"), (8, 64, "student"), (4, 128, "wide"), (8, 32, "uniform")):
+        n = 40 * B + 17
+        g = rng_grad(rng, n, kind)
+        e0 = rng_grad(rng, n, "normal", 2e-4)
+        h = g + e0                                     # Eq. 2 in binary32
+        e = e0.copy()
+        codes, scales = cq(lib, g, e, bits, B, 1.0)
+        delta = e
+        d = decode1(lib, codes, scales, n, bits, B)
+        back = (d + delta).astype(np.float32)
+        # h - d is exact (Sterbenz) when d == 0 or d/2 <= h <= 2d; the only other case is
+        # |q| = 1 with |h| a hair under half a step, where one rounding may remain.
+        with np.errstate(divide="ignore", invalid="ignore"):
+            ratio = np.where(d != 0, h.astype(np.float64) / d.astype(np.float64), 1.0)
+        safe = (d == 0) | ((ratio >= 0.5) & (ratio <= 2.0))
+        assert np.array_equal(back[safe], h[safe])
+        rest = ~safe
+        assert rest.mean() < 1e-3
+        assert np.all(np.abs(unpack(codes, n, bits)[rest]) == 1)
+        assert np.all(np.abs(back[rest].astype(np.float64) - h[rest]) <= ulp32(h[rest]))
+
+
+def check_rounding_bound(lib):
+    """Lemma 5 with 1/s = D_b: |h - C(h)| <= D_b/2 (plus the rounding of r_b and h*r_b);
+    the block's largest element gets code +-qmax; no code reaches -2^(p-1)."""
+    rng = np.random.default_rng(202)
+    for bits, B in ((4, 256), (8, 64), (4, 64), (8, 256)):
+        qmin, qmax = qrange(bits)
+        n = 64 * B + 5
+        g = rng_grad(rng, n, "student")
+        e0 = rng_grad(rng, n, "normal", 1e-4)
+        h = g + e0
+        e = e0.copy()
+        codes, scales = cq(lib, g, e, bits, B, 1.0)
+        q = unpack(codes, n, bits)
+        D = scales[block_index(n, B)].astype(np.float64)
+        assert np.all(np.abs(e) <= D * (0.5 + 4 * qmax * 2.0 ** -24))
+        assert q.min() >= -qmax and q.max() <= qmax
+        nb = oracle.num_blocks(n, B)
+        for b in range(nb):
+            sl = slice(b * B, min(n, (b + 1) * B))
+            i = np.argmax(np.abs(h[sl]))
+            assert abs(q[sl][i]) == qmax
+            assert np.sign(q[sl][i]) == np.sign(h[sl][i])
+            # the stored step is max|h|/qmax, one binary32 division
+            assert scales[b] == np.float32(np.abs(h[sl]).max()) / np.float32(qmax)
+
+
+def check_ema_recurrence(lib):
+    """Eq. 5 unrolled: e~_K = beta * sum_k (1-beta)^(K-1-k) delta_k with e~_0 = 0."""
+    rng = np.random.default_rng(303)
+    for beta in (0.25, 0.5, 0.9):
+        bits, B, n, K = 4, 64, 64 * 30 + 9, 7
+        e = np.ones(n, dtype=np.float32)
+        oracle.error_state_init(e, lib=lib)
+        assert not e.any()
+        deltas = []
+        for k in range(K):
+            g = rng_grad(rng, n, "normal")
+            h = g.astype(np.float64) + e.astype(np.float64)
+            codes, scales = cq(lib, g, e, bits, B, beta)
+            d = decode1(lib, codes, scales, n, bits, B).astype(np.float64)
+            deltas.append(h - d)
+        closed = np.zeros(n)
+        for k, dl in enumerate(deltas):
+            closed += beta * (1.0 - beta) ** (K - 1 - k) * dl
+        tol = K * 2.0 ** -22 * max(np.abs(dl).max() for dl in deltas)
+        assert np.abs(e - closed).max() <= tol
+        assert np.abs(closed).max() > 100 * tol          # the check has teeth
+
+
+def check_beta_special_cases(lib):
+    """beta = 1 is classic error feedback (Eq. 4); beta = 0 keeps e~ = 0 for ever."""
+    rng = np.random.default_rng(404)
+    bits, B, n = 4, 128, 128 * 20 + 3
+    g0, g1 = rng_grad(rng, n), rng_grad(rng, n)
+    # beta = 0: the state stays zero and codes are those of a fresh state
+    e = np.zeros(n, np.float32)
+    c0, s0 = cq(lib, g0, e, bits, B, 0.0)
+    assert not e.any()
+    c1, s1 = cq(lib, g1, e, bits, B, 0.0)
+    assert not e.any()
+    f = np.zeros(n, np.float32)
+    c1f, s1f = cq(lib, g1, f, bits, B, 0.7)
+    assert np.array_equal(c1, c1f) and np.array_equal(s1, s1f)
+    # beta = 1: the state equals h - d exactly
+    e = np.zeros(n, np.float32)
+    cq(lib, g0, e, bits, B, 1.0)
+    h = g1 + e
+    c, s = cq(lib, g1, e, bits, B, 1.0)
+    d = decode1(lib, c, s, n, bits, B)
+    assert np.array_equal(e, (h - d).astype(np.float32))
+    # a general beta: one step from a known state, against Eq. 5 written in binary64
+    e0 = rng_grad(rng, n, "normal", 3e-4)
+    e = e0.copy()
+    beta = 0.3
+    c, s = cq(lib, g0, e, bits, B, beta)
+    d = decode1(lib, c, s, n, bits, B).astype(np.float64)
+    h = (g0 + e0).astype(np.float64)
+    want = (1.0 - np.float64(np.float32(beta))) * e0 + np.float64(np.float32(beta)) * (h - d)
+    assert np.abs(e - want).max() <= 2.0 ** -22 * np.abs(want).max()
+
+
+def check_zero_error_fixed_point(lib):
+    """Eq. 1 on exactly representable input: h = m * 2^-t, |m| <= qmax, some |m| = qmax
+    in every block  =>  D = 2^-t, q = m, delta = 0, the state stays exactly 0."""
+    rng = np.random.default_rng(505)
+    for bits, B, t in ((4, 256, 19), (8, 64, 17), (4, 128, 10), (8, 256, 30)):
+        qmin, qmax = qrange(bits)
+        n = 33 * B
+        e = np.zeros(n, np.float32)
+        for _ in range(3):
+            m = rng.integers(-qmax, qmax + 1, n)
+            pos = np.arange(0, n, B) + rng.integers(0, B, n // B)
+            m[pos] = rng.choice([-qmax, qmax], n // B)
+            g = (m * 2.0 ** -t).astype(np.float32)
+            codes, scales = cq(lib, g, e, bits, B, 0.25)
+            assert np.array_equal(unpack(codes, n, bits), m)
+            assert np.all(scales == np.float32(2.0 ** -t))
+            assert not e.any()
+            assert np.array_equal(decode1(lib, codes, scales, n, bits, B), g)
+
+
+def check_brute_force_levels(lib):
+    """Eq. 1: q is the level of [-2^(p-1), 2^(p-1)-1] nearest to h*s (ties to even),
+    found here by trying every level in binary64."""
+    rng = np.random.default_rng(606)
+    flips = total = 0
+    for trial in range(1500):
+        bits = (4, 8)[trial & 1]
+        qmin, qmax = qrange(bits)
+        B = int(rng.choice([8, 16, 32, 64]))
+        n = int(rng.integers(1, 65))
+        g = rng_grad(rng, n, ("normal", "student", "wide")[trial % 3])
+        e0 = rng_grad(rng, n, "normal", 1e-4) if trial % 5 else np.zeros(n, np.float32)
+        h = g + e0
+        e = e0.copy()
+        codes, scales = cq(lib, g, e, bits, B, 1.0)
+        q = unpack(codes, n, bits)
+        levels = np.arange(qmin, qmax + 1, dtype=np.float64)
+        for b in range(oracle.num_blocks(n, B)):
+            sl = slice(b * B, min(n, (b + 1) * B))
+            D = np.float32(np.abs(h[sl]).max()) / np.float32(qmax)
+            if D < FLT_MIN:
+                assert scales[b] == 0 and not q[sl].any()
+                continue
+            assert scales[b] == D
+            x = h[sl].astype(np.float64) / np.float64(D)
+            dist = np.abs(x[:, None] - levels[None, :])
+            best = dist.min(axis=1)
+            cand = dist <= best[:, None]                       # one level, or two at a tie
+            ok = cand[np.arange(x.size), q[sl] - qmin]
+            tie = cand.sum(axis=1) == 2
+            even_ok = ~tie | (q[sl] % 2 == 0)
+            near_half = np.abs(np.abs(x - np.floor(x)) - 0.5) <= 4 * qmax * 2.0 ** -24
+            bad = ~(ok & even_ok)
+            assert not np.any(bad & ~near_half), (trial, b)
+            # even when the binary32 rounding of s_b moved a near-tie, the code is adjacent
+            assert np.all(np.abs(q[sl] - x) <= 0.5 + 4 * qmax * 2.0 ** -24)
+            flips += int(bad.sum())
+            total += x.size
+    assert flips <= 1e-3 * total
+
+
+def check_telescoping(lib):
+    """Lemma 1 with an uncompressed state: d_k = g_k + (e~_k - e~_{k+1})/beta, hence
+    sum_k d_k = sum_k g_k - e~_K / beta."""
+    rng = np.random.default_rng(707)
+    for bits, B, beta, K in ((4, 256, 0.25, 10), (8, 64, 0.5, 20), (4, 128, 1.0, 10)):
+        n = B * 12 + 1
+        e = np.zeros(n, np.float32)
+        sum_d = np.zeros(n)
+        sum_g = np.zeros(n)
+        gmax = 0.0
+        for _ in range(K):
+            g = rng_grad(rng, n, "normal")
+            codes, scales = cq(lib, g, e, bits, B, beta)
+            sum_d += decode1(lib, codes, scales, n, bits, B)
+            sum_g += g
+            gmax = max(gmax, float(np.abs(g).max()))
+        beta32 = np.float64(np.float32(beta))
+        assert np.abs(sum_d - (sum_g - e / beta32)).max() <= K * 2.0 ** -21 * gmax / beta32
+        assert np.abs(sum_d - sum_g).max() > 20 * K * 2.0 ** -21 * gmax / beta32  # non-trivial
+
+
+def check_fixed_scale_form(lib):
+    """Eq. 1 literally, at the paper's s = 2^19 (4-bit) and s = 2^17: when a block's
+    largest |h| is qmax/s the block scale is s exactly and q = clip(rint(h*s))."""
+    rng = np.random.default_rng(808)
+    for bits, B, log2s in ((4, 256, 19), (4, 64, 17), (8, 64, 19), (8, 128, 17)):
+        qmin, qmax = qrange(bits)
+        s = np.float32(2.0 ** log2s)
+        n = 50 * B
+        top = np.float32(qmax) / s
+        g = rng.uniform(-float(top), float(top), n).astype(np.float32)
+        e0 = np.zeros(n, np.float32)
+        pos = np.arange(0, n, B) + rng.integers(0, B, n // B)
+        g[pos] = top * rng.choice([-1.0, 1.0], n // B).astype(np.float32)
+        e = e0.copy()
+        codes, scales = cq(lib, g, e, bits, B, 1.0)
+        assert np.all(scales == np.float32(1.0) / s)
+        want = np.clip(np.rint(g * s), qmin, qmax).astype(np.int64)   # power-of-two product: exact
+        assert np.array_equal(unpack(codes, n, bits), want)
+        # decompressor: float(q)/s, and Eq. 4
+        d = decode1(lib, codes, scales, n, bits, B)
+        assert np.array_equal(d, (want / float(s)).astype(np.float32))
+        assert np.array_equal(e, g - d)
+
+
+def check_reset(lib):
+    """e~_0 = 0; Eq. 7: on a reset step the payload is that of the old state and the
+    new state is all zeros."""
+    rng = np.random.default_rng(909)
+    bits, B, n = 4, 256, 256 * 9 + 100
+    g = rng_grad(rng, n)
+    e0 = rng_grad(rng, n, "normal", 2e-4)
+    ea, eb = e0.copy(), e0.copy()
+    ca, sa = cq(lib, g, ea, bits, B, 0.25, reset=0)
+    cb, sb = cq(lib, g, eb, bits, B, 0.25, reset=1)
+    assert np.array_equal(ca, cb) and np.array_equal(sa, sb)
+    assert ea.any() and not eb.any()
+    assert np.all(np.signbit(eb) == False)  # noqa: E712
+
+
+def check_dequant_reduce(lib):
+    """Eq. 8: N = 1 returns float(q)/s; N equal payloads return that value again (exactly
+    for N = 2); a general N is the mean of the decoded payloads."""
+    rng = np.random.default_rng(1010)
+    for bits, B in ((4, 256), (8, 64)):
+        n = B * 20 + 7
+        nb, cb = oracle.num_blocks(n, B), oracle.code_bytes(n, bits)
+        payloads = []
+        for w in range(5):
+            e = np.zeros(n, np.float32)
+            payloads.append(cq(lib, rng_grad(rng, n, "student"), e, bits, B, 0.25))
+        dec = [unpack(c, n, bits).astype(np.float32) * s[block_index(n, B)] for c, s in payloads]
+        c0, s0 = payloads[0]
+        assert np.array_equal(decode1(lib, c0, s0, n, bits, B), dec[0])
+        for W in (2, 4, 8, 16):
+            out = oracle.dequant_reduce(np.tile(c0, W), np.tile(s0, W), W, n, bits, B, lib=lib)
+            if W == 2:      # x + x is exact, and so is the halving
+                assert np.array_equal(out, dec[0])
+            else:           # 3x, 5x, ... round: one ulp per addition at most
+                assert np.all(np.abs(out.astype(np.float64) - dec[0]) <= W * ulp32(dec[0]))
+        # strided layout with padding between payloads, W = 3 and 5
+        cstride, sstride = cb + 13, nb + 3
+        for W in (3, 5):
+            codes = np.zeros(W * cstride, np.uint8)
+            scales = np.zeros(W * sstride, np.float32)
+            for w in range(W):
+                codes[w * cstride:w * cstride + cb] = payloads[w][0]
+                scales[w * sstride:w * sstride + nb] = payloads[w][1]
+            out = oracle.dequant_reduce(codes, scales, W, n, bits, B, cstride, sstride, lib=lib)
+            mean = np.mean(np.stack(dec[:W]).astype(np.float64), axis=0)
+            top = np.abs(np.stack(dec[:W])).max(axis=0)
+            assert np.all(np.abs(out - mean) <= (W + 1) * 2.0 ** -24 * top)
+            assert np.abs(mean).max() > 0
+        # order of the workers: at most (W-1) ulp of the largest partial sum
+        W = 5
+        codes = np.concatenate([p[0] for p in payloads])
+        scales = np.concatenate([p[1] for p in payloads])
+        fwd = oracle.dequant_reduce(codes, scales, W, n, bits, B, lib=lib)
+        rcodes = np.concatenate([p[0] for p in payloads[::-1]])
+        rscales = np.concatenate([p[1] for p in payloads[::-1]])
+        rev = oracle.dequant_reduce(rcodes, rscales, W, n, bits, B, lib=lib)
+        bound = (W - 1) * ulp32(np.abs(np.stack(dec)).sum(axis=0).astype(np.float32))
+        assert np.all(np.abs(fwd.astype(np.float64) - rev) <= bound)
+
+
+def check_bf16_widening(lib):
+    """A bf16 gradient is widened exactly: same result as the same values given as fp32."""
+    rng = np.random.default_rng(1111)
+    bits, B, n = 4, 64, 64 * 11 + 3
+    gb = to_bf16_bits(rng_grad(rng, n, "student"))
+    g32 = bf16_bits_to_f32(gb)
+    e0 = rng_grad(rng, n, "normal", 1e-4)
+    ea, eb = e0.copy(), e0.copy()
+    ca, sa = cq(lib, gb, ea, bits, B, 0.25)
+    cb, sb = cq(lib, g32, eb, bits, B, 0.25)
+    assert np.array_equal(ca, cb) and np.array_equal(sa, sb) and np.array_equal(ea, eb)
+    assert sa.any()
+
+
+def check_edges(lib):
+    """Empty input, one element, odd length (last high nibble 0), partial last block,
+    all-zero and subnormal-step blocks (stored step +0, zero codes, error keeps h)."""
+    e = np.zeros(0, np.float32)
+    c, s = cq(lib, np.zeros(0, np.float32), e, 4, 256, 0.25)
+    assert c.size == 0 and s.size == 0
+    assert oracle.dequant_reduce(c, s, 3, 0, 4, 256, lib=lib).size == 0
+    # one element: it is its own block maximum
+    for bits in (4, 8):
+        qmin, qmax = qrange(bits)
+        e = np.zeros(1, np.float32)
+        c, s = cq(lib, np.array([-0.3], np.float32), e, bits, 256, 1.0)
+        assert unpack(c, 1, bits).tolist() == [-qmax] and c.size == 1
+        assert s[0] == np.float32(0.3) / np.float32(qmax)
+    # odd n, 4-bit: the unused high nibble is zero
+    rng = np.random.default_rng(1212)
+    n = 2 * 64 + 37
+    g = rng_grad(rng, n)
+    e = np.zeros(n, np.float32)
+    c, s = cq(lib, g, e, 4, 64, 0.25)
+    assert c.size == (n + 1) // 2 and (c[-1] >> 4) == 0 and s.size == 3
+    # the partial last block sees only its own elements
+    tail = g[128:]
+    et = np.zeros(tail.size, np.float32)
+    ct, st = cq(lib, tail, et, 4, 64, 0.25)
+    assert st[0] == s[2] and np.array_equal(ct, c[64:]) and np.array_equal(et, e[128:])
+    # zero block between live blocks; a block whose step would be subnormal
+    B = 64
+    g = rng_grad(rng, 4 * B)
+    g[B:2 * B] = 0
+    tiny = np.float32(2.0 ** -127)                    # max|h|/7 < FLT_MIN
+    g[2 * B:3 * B] = (rng.uniform(-1, 1, B) * tiny).astype(np.float32)
+    e = np.zeros(4 * B, np.float32)
+    c, s = cq(lib, g, e, 4, B, 1.0)
+    q = unpack(c, 4 * B, 4)
+    assert s[1] == 0 and not np.signbit(s[1]) and s[2] == 0 and s[0] > 0 and s[3] > 0
+    assert not q[B:3 * B].any() and q[:B].any() and q[3 * B:].any()
+    assert np.array_equal(e[B:3 * B], g[B:3 * B])
+    # smallest live step: max|h| = 7 * FLT_MIN
+    g = np.zeros(B, np.float32)
+    g[3] = np.float32(7) * FLT_MIN
+    g[5] = np.float32(-3) * FLT_MIN
+    e = np.zeros(B, np.float32)
+    c, s = cq(lib, g, e, 4, B, 1.0)
+    assert s[0] == FLT_MIN and unpack(c, B, 4)[[3, 5]].tolist() == [7, -3] and not e.any()
+
+
+def check_threads_agree(lib):
+    """The threaded driver only splits ranges: same bytes as one thread."""
+    rng = np.random.default_rng(1313)
+    for bits, B, n in ((4, 256, 256 * 37 + 11), (8, 64, 64 * 101 + 63), (4, 7, 1001)):
+        g = rng_grad(rng, n, "student")
+        e0 = rng_grad(rng, n, "normal", 1e-4)
+        ea, eb = e0.copy(), e0.copy()
+        ca, sa = cq(lib, g, ea, bits, B, 0.25)
+        cb, sb = cq(lib, g, eb, bits, B, 0.25, threads=5)
+        assert np.array_equal(ca, cb) and np.array_equal(sa, sb) and np.array_equal(ea, eb)
+        W = 3
+        out1 = oracle.dequant_reduce(np.tile(ca, W), np.tile(sa, W), W, n, bits, B, lib=lib)
+        out5 = oracle.dequant_reduce(np.tile(ca, W), np.tile(sa, W), W, n, bits, B, threads=5, lib=lib)
+        assert np.array_equal(out1, out5)
+
+
+ALL_CHECKS = [
+    check_worked_example,
+    check_exact_reconstruction,
+    check_rounding_bound,
+    check_ema_recurrence,
+    check_beta_special_cases,
+    check_zero_error_fixed_point,
+    check_brute_force_levels,
+    check_telescoping,
+    check_fixed_scale_form,
+    check_reset,
+    check_dequant_reduce,
+    check_bf16_widening,
+    check_edges,
+    check_threads_agree,
+]

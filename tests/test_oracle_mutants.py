@@ -1,0 +1,61 @@
+"""Do the pins have teeth?  Plant one plausible mistake at a time in a COPY of the
+oracle's source (on the CPU, in a temporary directory), build it, and require that
+at least one pin of tests/pins.py fails.  The real oracle is never modified.
+"""
+import os
+import shutil
+
+import pytest
+
+import oracle
+import pins
+
+SRC = os.path.join(os.path.dirname(oracle.__file__), "loco_ref.c")
+MT = os.path.join(os.path.dirname(oracle.__file__), "loco_ref_mt.c")
+
+# (name, text in loco_ref.c, replacement)
+MUTANTS = [
+    ("compensation_sign", "grad_at(grad, grad_dtype, i) + e; /* Eq. 2 */", "grad_at(grad, grad_dtype, i) - e;"),
+    ("error_sign", "float delta = h - d;", "float delta = d - h;"),
+    ("ema_weights_swapped", "fmaf(one_minus_beta, e, bd)", "fmaf(beta, e, one_minus_beta * delta)"),
+    ("ema_history_dropped", "fmaf(one_minus_beta, e, bd)", "bd"),
+    ("ema_not_weighted", "float bd = beta * delta;", "float bd = delta;"),
+    ("scale_uses_2_pow_p_minus_1", "amax / (float)qmax;", "amax / (float)(qmax + 1);"),
+    ("truncate_instead_of_round", "(int)rintf(h * r);", "(int)truncf(h * r);"),
+    ("round_half_away", "(int)rintf(h * r);", "(int)roundf(h * r);"),
+    ("max_without_abs", "float ah = fabsf(h);", "float ah = h;"),
+    ("nibble_order", "codes_out[i >> 1] = (uint8_t)(codes_out[i >> 1] | ((q & 15) << 4));",
+     "codes_out[i >> 1] = (uint8_t)((codes_out[i >> 1] << 4) | (q & 15));"),
+    ("unsigned_nibble_decode", "return (nib ^ 8) - 8;", "return nib;"),
+    ("no_average", "grad_out[i] = acc * inv;", "grad_out[i] = acc;"),
+    ("reset_ignored", "reset ? 0.0f : fmaf", "0 ? 0.0f : fmaf"),
+    ("bf16_shift", "[i] << 16;", "[i] << 15;"),
+    ("worker_scale_stride", "scales[(size_t)w * scale_stride_elems + b]", "scales[b]"),
+    ("worker_code_stride", "codes + (size_t)w * code_stride_bytes", "codes"),
+    ("subnormal_step_kept", "int dead = D < FLT_MIN;", "int dead = D <= 0.0f;"),
+    ("state_not_compensated_in_max", "float h = grad_at(grad, grad_dtype, i) + err_state[i];",
+     "float h = grad_at(grad, grad_dtype, i);"),
+    ("decode_with_reciprocal", "float d = (float)q * D;   /* decompressor, Eq. 1 */",
+     "float d = (float)q * r;"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(tmp_path, name, old, new):
+    text = open(SRC).read()
+    assert text.count(old) == 1, f"mutation site for {name} not unique"
+    src = tmp_path / "loco_ref.c"
+    src.write_text(text.replace(old, new))
+    shutil.copy(MT, tmp_path / "loco_ref_mt.c")
+    so = oracle.build(force=True, out=str(tmp_path / "libmutant.so"),
+                      srcs=[str(src), str(tmp_path / "loco_ref_mt.c")], extra_flags=["-w"])
+    lib = oracle.load(so)
+    caught = []
+    for check in pins.ALL_CHECKS:
+        try:
+            check(lib)
+        except (AssertionError, ValueError, FloatingPointError):
+            caught.append(check.__name__)
+            break
+    assert caught, f"no pin noticed the planted mistake {name!r}"
+
