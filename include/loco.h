@@ -1,0 +1,132 @@
+/*
+ * loco.h -- C ABI of the MI355X (gfx950) library for LoCo's per-step local path.
+ *
+ * LoCo (arXiv 2407.04480), Algorithm 1: every step each worker adds its error
+ * state to the fresh gradient, compresses the sum to p-bit integers, keeps a
+ * moving average of the compression error, and, after the low-bit payloads have
+ * been exchanged, decodes and averages the N payloads it received.  This
+ * library holds the two element-wise passes of that step and the state's
+ * initialisation; the exchange itself, the optimizer and everything else are
+ * the caller's.
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers on the current HIP device; the caller
+ *     owns every buffer.  The library allocates nothing, frees nothing and never
+ *     synchronises: work is enqueued on `stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and is ordered by it.
+ *   - Sizes are in elements unless a name says bytes; n may exceed 2^31.
+ *   - Buffers must not overlap, except that err_state is updated in place.
+ *   - Inputs must be finite; NaN and infinities are not checked and give
+ *     unspecified codes.
+ *   - Errors are returned, never thrown; on an error nothing has been enqueued.
+ *     n == 0 is LOCO_OK and enqueues nothing.
+ *   - By default each call checks that every device buffer lies inside one
+ *     allocation known to the HIP runtime (loco_set_pointer_checks).
+ *
+ * Payload format (the paper leaves scale granularity and packing open; Eq. 1 is
+ * applied per block of block_size consecutive elements):
+ *   scales[b] = D_b = max|h| / qmax over block b, fp32, qmax = 2^(bits-1) - 1;
+ *               +0 for a block whose D_b would be zero or subnormal
+ *   code q_i  = clamp(rint(h_i * (1/D_b)), -2^(bits-1), qmax), ties to even
+ *   bits = 8:   codes[i] = (int8) q_i
+ *   bits = 4:   codes[i/2] holds q_i as a two's complement nibble, even i in the low
+ *               nibble, odd i in the high nibble; an unused last nibble is 0
+ *   decode:     d_i = (float) q_i * D_b
+ */
+#ifndef LOCO_H
+#define LOCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LOCO_OK = 0,
+    LOCO_ERR_INVALID_ARG = 1, /* NULL pointer, beta outside [0,1] or NaN, W < 1, stride too small */
+    LOCO_ERR_UNSUPPORTED = 2, /* bits, block_size or dtype outside the supported sets */
+    LOCO_ERR_ALIGNMENT = 3,   /* a pointer or stride breaks the alignment rule of the call */
+    LOCO_ERR_LAUNCH = 4,      /* the HIP runtime refused the launch */
+    LOCO_ERR_BAD_POINTER = 5  /* a buffer is not device memory, or too small for the call */
+} loco_status_t;
+
+typedef enum { LOCO_F32 = 0, LOCO_BF16 = 1 } loco_dtype_t;
+
+/* Short text for a status code; static storage. */
+const char *loco_status_string(loco_status_t status);
+
+/* Bytes of packed codes for n elements: ceil(n * bits / 8).  0 if bits is not 4 or 8. */
+size_t loco_code_bytes(size_t n, int bits);
+
+/* Number of blocks (= number of fp32 scales) for n elements: ceil(n / block_size). */
+size_t loco_num_blocks(size_t n, int block_size);
+
+/* 1 (default): validate device buffers against the runtime's allocation table on
+ * every call (a few microseconds of host time).  0: trust the caller.  Returns the
+ * previous setting.  Process-wide. */
+int loco_set_pointer_checks(int enabled);
+
+/*
+ * e~_0 = 0 (stated below Eq. 5); also the hard form of the periodic reset of Eq. 7.
+ *   err_state  [n] fp32, device, 16-byte aligned; overwritten with +0.
+ * Uses a fill kernel, so the call may be captured into a HIP graph.
+ */
+loco_status_t loco_error_state_init(float *err_state, size_t n, void *stream);
+
+/*
+ * Algorithm 1, steps 1 and 2, fused into one pass over the shard:
+ *   h   = g + e~                      (Eq. 2; the state is fp32, so no decompression)
+ *   q   = compressor(h; s_b, bits)    (Eq. 1, Eq. 3; per-block scale, see above)
+ *   d   = decompressor(q; s_b)        (Eq. 1)
+ *   e~' = (1-beta) e~ + beta (h - d)  (Eq. 4, Eq. 5), or 0 when reset != 0 (Eq. 7)
+ *
+ *   grad        [n] device, LOCO_F32 or LOCO_BF16, read only, 16-byte aligned
+ *   err_state   [n] fp32 device, read and overwritten in place, 16-byte aligned
+ *   bits        4 or 8
+ *   block_size  32, 64, 128, 256 or 512
+ *   beta        moving-average coefficient of Eq. 5, 0 <= beta <= 1
+ *   reset       non-zero on a step where Eq. 7 zeroes the state: codes and scales are
+ *               still those of the old state, the state written is +0
+ *   codes_out   [loco_code_bytes(n, bits)] device, 16-byte aligned
+ *   scales_out  [loco_num_blocks(n, block_size)] fp32 device, 4-byte aligned
+ * The arithmetic is IEEE binary32 with one rounding per operation (Eq. 5 is
+ * fmaf(1-beta, e~, beta*(h-d))), so codes, scales and state are reproducible bit
+ * for bit.
+ */
+loco_status_t loco_compensate_quantize(const void *grad, loco_dtype_t grad_dtype,
+                                       float *err_state, size_t n, int bits, int block_size,
+                                       float beta, int reset, uint8_t *codes_out,
+                                       float *scales_out, void *stream);
+
+/*
+ * Algorithm 1, step 3 / Eq. 8: decode the payloads of W workers and average them in
+ * fp32:  out_i = (sum_{w=0}^{W-1} (float) q^w_i * D^w_b) * (1/W), summed in worker order.
+ *
+ * Payload w is at codes + w*code_stride_bytes and scales + w*scale_stride_elems, the
+ * layout of an all-to-all receive buffer (Sec. 3.3).
+ *   codes               device, 16-byte aligned; code_stride_bytes a multiple of 16 and
+ *                       >= loco_code_bytes(n, bits) (ignored when W == 1)
+ *   scales              fp32 device; scale_stride_elems >= loco_num_blocks(n, block_size)
+ *   num_workers         W >= 1 (N of Eq. 8)
+ *   bits, block_size    as for loco_compensate_quantize
+ *   grad_out            [n] fp32 device, overwritten, 16-byte aligned
+ */
+loco_status_t loco_dequant_reduce(const uint8_t *codes, size_t code_stride_bytes,
+                                  const float *scales, size_t scale_stride_elems,
+                                  int num_workers, size_t n, int bits, int block_size,
+                                  float *grad_out, void *stream);
+
+/*
+ * Measurement aid, not part of the method: dst[i] = src[i] for `bytes` bytes
+ * (a multiple of 16, both pointers 16-byte aligned) with the same load/store
+ * shape as the kernels above.  Gives the practical HBM ceiling and the scale
+ * factor for hardware byte counters.
+ */
+loco_status_t loco_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOCO_H */

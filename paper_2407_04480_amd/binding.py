@@ -1,0 +1,174 @@
+"""ctypes binding of the C-ABI library (include/loco.h): argument marshalling only.
+
+The functions carry the names of the C entry points.  Tensors are torch tensors
+on the GPU (torch is used for device memory and streams only); every step of the
+method runs in the library's HIP kernels.  There is no CPU path: a missing
+library, a CPU tensor or a non-zero status raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libloco.so")
+
+LOCO_OK = 0
+LOCO_F32 = 0
+LOCO_BF16 = 1
+
+EXPORTS = (
+    "loco_status_string",
+    "loco_code_bytes",
+    "loco_num_blocks",
+    "loco_set_pointer_checks",
+    "loco_error_state_init",
+    "loco_compensate_quantize",
+    "loco_dequant_reduce",
+    "loco_stream_copy",
+)
+
+_lib = None
+
+
+class LocoError(RuntimeError):
+    def __init__(self, call: str, status: int, text: str):
+        super().__init__(f"{call}: status {status} ({text})")
+        self.call, self.status = call, status
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library(path: Optional[str] = None):
+    """Open libloco.so (built by paper_2407_04480_amd.build); raises if it is not there."""
+    global _lib
+    if path is None and _lib is not None:
+        return _lib
+    p = path or _LIB_PATH
+    if not os.path.exists(p):
+        raise FileNotFoundError(
+            f"{p} not found: build it first (python -m paper_2407_04480_amd.build); there is no fallback path")
+    lib = ctypes.CDLL(p)
+    c = ctypes
+    vp, sz, i, f = c.c_void_p, c.c_size_t, c.c_int, c.c_float
+    lib.loco_status_string.argtypes, lib.loco_status_string.restype = [i], c.c_char_p
+    lib.loco_code_bytes.argtypes, lib.loco_code_bytes.restype = [sz, i], sz
+    lib.loco_num_blocks.argtypes, lib.loco_num_blocks.restype = [sz, i], sz
+    lib.loco_set_pointer_checks.argtypes, lib.loco_set_pointer_checks.restype = [i], i
+    lib.loco_error_state_init.argtypes, lib.loco_error_state_init.restype = [vp, sz, vp], i
+    lib.loco_compensate_quantize.argtypes = [vp, i, vp, sz, i, i, f, i, vp, vp, vp]
+    lib.loco_compensate_quantize.restype = i
+    lib.loco_dequant_reduce.argtypes = [vp, sz, vp, sz, i, sz, i, i, vp, vp]
+    lib.loco_dequant_reduce.restype = i
+    lib.loco_stream_copy.argtypes, lib.loco_stream_copy.restype = [vp, vp, sz, vp], i
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def _check(call: str, status: int):
+    if status != LOCO_OK:
+        raise LocoError(call, status, load_library().loco_status_string(status).decode())
+
+
+def _dev_ptr(t: torch.Tensor, name: str, dtype=None) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a torch tensor on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def loco_code_bytes(n: int, bits: int) -> int:
+    return load_library().loco_code_bytes(n, bits)
+
+
+def loco_num_blocks(n: int, block_size: int) -> int:
+    return load_library().loco_num_blocks(n, block_size)
+
+
+def loco_set_pointer_checks(enabled: bool) -> bool:
+    return bool(load_library().loco_set_pointer_checks(1 if enabled else 0))
+
+
+def loco_error_state_init(err_state: torch.Tensor, stream=None) -> None:
+    """e~_0 = 0 (below Eq. 5 of arXiv 2407.04480); also the hard reset of Eq. 7."""
+    lib = load_library()
+    p = _dev_ptr(err_state, "err_state", torch.float32)
+    _check("loco_error_state_init", lib.loco_error_state_init(p, err_state.numel(), _stream_handle(stream)))
+
+
+def loco_compensate_quantize(grad: torch.Tensor, err_state: torch.Tensor, bits: int, block_size: int,
+                             beta: float, reset: bool, codes_out: torch.Tensor, scales_out: torch.Tensor,
+                             stream=None) -> None:
+    """Algorithm 1 steps 1-2 (Eq. 1-5, 7): err_state is updated in place, codes_out
+    (uint8) and scales_out (float32) receive the payload."""
+    lib = load_library()
+    if grad.dtype == torch.float32:
+        gd = LOCO_F32
+    elif grad.dtype == torch.bfloat16:
+        gd = LOCO_BF16
+    else:
+        raise TypeError(f"grad must be float32 or bfloat16, got {grad.dtype}")
+    n = grad.numel()
+    pg = _dev_ptr(grad, "grad")
+    pe = _dev_ptr(err_state, "err_state", torch.float32)
+    pc = _dev_ptr(codes_out, "codes_out", torch.uint8)
+    ps = _dev_ptr(scales_out, "scales_out", torch.float32)
+    if err_state.numel() != n:
+        raise ValueError("err_state must have as many elements as grad")
+    if bits in (4, 8) and block_size >= 1:
+        if codes_out.numel() < (n * bits + 7) // 8:
+            raise ValueError("codes_out too small")
+        if scales_out.numel() < (n + block_size - 1) // block_size:
+            raise ValueError("scales_out too small")
+    st = lib.loco_compensate_quantize(pg, gd, pe, n, int(bits), int(block_size), float(beta),
+                                      1 if reset else 0, pc, ps, _stream_handle(stream))
+    _check("loco_compensate_quantize", st)
+
+
+def loco_dequant_reduce(codes: torch.Tensor, code_stride_bytes: int, scales: torch.Tensor,
+                        scale_stride_elems: int, num_workers: int, n: int, bits: int, block_size: int,
+                        grad_out: torch.Tensor, stream=None) -> None:
+    """Algorithm 1 step 3 / Eq. 8: decode num_workers payloads and average into grad_out (float32)."""
+    lib = load_library()
+    pc = _dev_ptr(codes, "codes", torch.uint8)
+    ps = _dev_ptr(scales, "scales", torch.float32)
+    po = _dev_ptr(grad_out, "grad_out", torch.float32)
+    if grad_out.numel() < n:
+        raise ValueError("grad_out too small")
+    if bits in (4, 8) and block_size >= 1 and num_workers >= 1 and n > 0:
+        cs = code_stride_bytes if num_workers > 1 else 0
+        ss = scale_stride_elems if num_workers > 1 else 0
+        if codes.numel() < (num_workers - 1) * cs + (n * bits + 7) // 8:
+            raise ValueError("codes too small for num_workers payloads at this stride")
+        if scales.numel() < (num_workers - 1) * ss + (n + block_size - 1) // block_size:
+            raise ValueError("scales too small for num_workers payloads at this stride")
+    st = lib.loco_dequant_reduce(pc, int(code_stride_bytes), ps, int(scale_stride_elems), int(num_workers),
+                                 int(n), int(bits), int(block_size), po, _stream_handle(stream))
+    _check("loco_dequant_reduce", st)
+
+
+def loco_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    """Plain device copy with the kernels' load/store shape (measurement aid)."""
+    lib = load_library()
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < nbytes:
+        raise ValueError("dst too small")
+    st = lib.loco_stream_copy(_dev_ptr(dst, "dst"), _dev_ptr(src, "src"), nbytes, _stream_handle(stream))
+    _check("loco_stream_copy", st)

@@ -1,0 +1,219 @@
+// Host side of the C ABI declared in include/loco.h: argument checks, dispatch on
+// (gradient type, bits, block size), launches on the caller's stream.  No allocation,
+// no synchronisation, no CPU fallback: without a GPU every compute call fails.
+#include "loco.h"
+#include "loco_kernels.h"
+
+#include <atomic>
+#include <cmath>
+
+namespace {
+
+using namespace loco;
+
+// Launch shape chosen by measurement on MI355X (see the design notes): tiles of 2048
+// elements per workgroup and whether loads/stores carry the non-temporal hint.
+constexpr int kCqTiles = LOCO_CQ_TILES;
+constexpr int kDrTiles = LOCO_DR_TILES;
+constexpr int kDrWorkersInFlight = LOCO_DR_WU;
+constexpr bool kNonTemporal = LOCO_NT != 0;
+constexpr int kCopyTiles = 4;
+
+std::atomic<int> g_pointer_checks{1};
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+bool block_size_ok(int b) { return b == 32 || b == 64 || b == 128 || b == 256 || b == 512; }
+
+// Is [p, p+bytes) inside one device allocation known to the runtime?
+loco_status_t check_device_range(const void* p, size_t bytes) {
+    if (!g_pointer_checks.load(std::memory_order_relaxed) || bytes == 0) return LOCO_OK;
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+        (void)hipGetLastError();
+        return LOCO_ERR_BAD_POINTER;
+    }
+    if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged) return LOCO_ERR_BAD_POINTER;
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    if (hipMemGetAddressRange(&base, &size, const_cast<void*>(p)) != hipSuccess) {
+        (void)hipGetLastError();
+        return LOCO_ERR_BAD_POINTER;
+    }
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(base), q = reinterpret_cast<uintptr_t>(p);
+    if (q < lo || bytes > size || q - lo > size - bytes) return LOCO_ERR_BAD_POINTER;
+    return LOCO_OK;
+}
+
+loco_status_t grid_for(size_t units, size_t per_group, unsigned* grid) {
+    const size_t g = (units + per_group - 1) / per_group;
+    if (g == 0 || g > 0x7FFFFFFFull) return LOCO_ERR_UNSUPPORTED;
+    *grid = (unsigned)g;
+    return LOCO_OK;
+}
+
+loco_status_t launched() { return hipGetLastError() == hipSuccess ? LOCO_OK : LOCO_ERR_LAUNCH; }
+
+template <typename G, int BITS, int BLOCK>
+void launch_cq(unsigned grid, hipStream_t s, const void* grad, float* err, size_t n, float beta,
+               int reset, uint8_t* codes, float* scales) {
+    const float one_minus_beta = 1.0f - beta;
+    cq_kernel<G, BITS, BLOCK, kCqTiles, kNonTemporal><<<dim3(grid), dim3(kThreads), 0, s>>>(
+        grad, err, n, beta, one_minus_beta, reset, codes, scales);
+}
+
+template <typename G, int BITS>
+bool dispatch_cq_block(int block, unsigned grid, hipStream_t s, const void* grad, float* err, size_t n,
+                       float beta, int reset, uint8_t* codes, float* scales) {
+    switch (block) {
+        case 32: launch_cq<G, BITS, 32>(grid, s, grad, err, n, beta, reset, codes, scales); return true;
+        case 64: launch_cq<G, BITS, 64>(grid, s, grad, err, n, beta, reset, codes, scales); return true;
+        case 128: launch_cq<G, BITS, 128>(grid, s, grad, err, n, beta, reset, codes, scales); return true;
+        case 256: launch_cq<G, BITS, 256>(grid, s, grad, err, n, beta, reset, codes, scales); return true;
+        case 512: launch_cq<G, BITS, 512>(grid, s, grad, err, n, beta, reset, codes, scales); return true;
+        default: return false;
+    }
+}
+
+template <int BITS, int BLOCK>
+void launch_dr(unsigned grid, hipStream_t s, const uint8_t* codes, size_t cs, const float* scales,
+               size_t ss, int W, size_t n, float* out) {
+    const float inv_w = 1.0f / (float)W;
+    dr_kernel<BITS, BLOCK, kDrTiles, kDrWorkersInFlight, kNonTemporal>
+        <<<dim3(grid), dim3(kThreads), 0, s>>>(codes, cs, scales, ss, W, n, inv_w, out);
+}
+
+template <int BITS>
+bool dispatch_dr_block(int block, unsigned grid, hipStream_t s, const uint8_t* codes, size_t cs,
+                       const float* scales, size_t ss, int W, size_t n, float* out) {
+    switch (block) {
+        case 32: launch_dr<BITS, 32>(grid, s, codes, cs, scales, ss, W, n, out); return true;
+        case 64: launch_dr<BITS, 64>(grid, s, codes, cs, scales, ss, W, n, out); return true;
+        case 128: launch_dr<BITS, 128>(grid, s, codes, cs, scales, ss, W, n, out); return true;
+        case 256: launch_dr<BITS, 256>(grid, s, codes, cs, scales, ss, W, n, out); return true;
+        case 512: launch_dr<BITS, 512>(grid, s, codes, cs, scales, ss, W, n, out); return true;
+        default: return false;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* loco_status_string(loco_status_t status) {
+    switch (status) {
+        case LOCO_OK: return "ok";
+        case LOCO_ERR_INVALID_ARG: return "invalid argument";
+        case LOCO_ERR_UNSUPPORTED: return "unsupported bits, block size, dtype or size";
+        case LOCO_ERR_ALIGNMENT: return "pointer or stride not aligned as required";
+        case LOCO_ERR_LAUNCH: return "kernel launch failed";
+        case LOCO_ERR_BAD_POINTER: return "buffer is not device memory or is too small";
+        default: return "unknown status";
+    }
+}
+
+size_t loco_code_bytes(size_t n, int bits) {
+    if (bits == 8) return n;
+    if (bits == 4) return n / 2 + (n & 1);
+    return 0;
+}
+
+size_t loco_num_blocks(size_t n, int block_size) {
+    if (block_size < 1) return 0;
+    return n / (size_t)block_size + (n % (size_t)block_size != 0);
+}
+
+int loco_set_pointer_checks(int enabled) { return g_pointer_checks.exchange(enabled ? 1 : 0); }
+
+loco_status_t loco_error_state_init(float* err_state, size_t n, void* stream) {
+    if (n == 0) return LOCO_OK;
+    if (!err_state) return LOCO_ERR_INVALID_ARG;
+    if (!aligned(err_state, 16)) return LOCO_ERR_ALIGNMENT;
+    if (loco_status_t st = check_device_range(err_state, n * sizeof(float))) return st;
+    unsigned grid;
+    if (loco_status_t st = grid_for(n, (size_t)kThreads * 4 * kCopyTiles, &grid)) return st;
+    fill_zero_kernel<kCopyTiles, kNonTemporal>
+        <<<dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream)>>>(err_state, n);
+    return launched();
+}
+
+loco_status_t loco_compensate_quantize(const void* grad, loco_dtype_t grad_dtype, float* err_state,
+                                       size_t n, int bits, int block_size, float beta, int reset,
+                                       uint8_t* codes_out, float* scales_out, void* stream) {
+    if (bits != 4 && bits != 8) return LOCO_ERR_UNSUPPORTED;
+    if (!block_size_ok(block_size)) return LOCO_ERR_UNSUPPORTED;
+    if (grad_dtype != LOCO_F32 && grad_dtype != LOCO_BF16) return LOCO_ERR_UNSUPPORTED;
+    if (!(beta >= 0.0f && beta <= 1.0f)) return LOCO_ERR_INVALID_ARG;  // also rejects NaN
+    if (n == 0) return LOCO_OK;
+    if (!grad || !err_state || !codes_out || !scales_out) return LOCO_ERR_INVALID_ARG;
+    if (!aligned(grad, 16) || !aligned(err_state, 16) || !aligned(codes_out, 16) || !aligned(scales_out, 4))
+        return LOCO_ERR_ALIGNMENT;
+    const size_t gsz = grad_dtype == LOCO_BF16 ? 2 : 4;
+    if (loco_status_t st = check_device_range(grad, n * gsz)) return st;
+    if (loco_status_t st = check_device_range(err_state, n * sizeof(float))) return st;
+    if (loco_status_t st = check_device_range(codes_out, loco_code_bytes(n, bits))) return st;
+    if (loco_status_t st = check_device_range(scales_out, loco_num_blocks(n, block_size) * sizeof(float)))
+        return st;
+    unsigned grid;
+    if (loco_status_t st = grid_for(n, (size_t)kTile * kCqTiles, &grid)) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    bool ok;
+    if (grad_dtype == LOCO_BF16) {
+        ok = bits == 4 ? dispatch_cq_block<bf16_t, 4>(block_size, grid, s, grad, err_state, n, beta, reset, codes_out, scales_out)
+                       : dispatch_cq_block<bf16_t, 8>(block_size, grid, s, grad, err_state, n, beta, reset, codes_out, scales_out);
+    } else {
+        ok = bits == 4 ? dispatch_cq_block<float, 4>(block_size, grid, s, grad, err_state, n, beta, reset, codes_out, scales_out)
+                       : dispatch_cq_block<float, 8>(block_size, grid, s, grad, err_state, n, beta, reset, codes_out, scales_out);
+    }
+    if (!ok) return LOCO_ERR_UNSUPPORTED;
+    return launched();
+}
+
+loco_status_t loco_dequant_reduce(const uint8_t* codes, size_t code_stride_bytes, const float* scales,
+                                  size_t scale_stride_elems, int num_workers, size_t n, int bits,
+                                  int block_size, float* grad_out, void* stream) {
+    if (bits != 4 && bits != 8) return LOCO_ERR_UNSUPPORTED;
+    if (!block_size_ok(block_size)) return LOCO_ERR_UNSUPPORTED;
+    if (num_workers < 1) return LOCO_ERR_INVALID_ARG;
+    if (n == 0) return LOCO_OK;
+    if (!codes || !scales || !grad_out) return LOCO_ERR_INVALID_ARG;
+    const size_t cb = loco_code_bytes(n, bits), nb = loco_num_blocks(n, block_size);
+    const size_t W = (size_t)num_workers;
+    if (W == 1) {  // strides are not used
+        code_stride_bytes = 0;
+        scale_stride_elems = 0;
+    } else {
+        if (code_stride_bytes < cb || scale_stride_elems < nb) return LOCO_ERR_INVALID_ARG;
+        if (code_stride_bytes % 16 != 0) return LOCO_ERR_ALIGNMENT;
+    }
+    if (!aligned(codes, 16) || !aligned(scales, 4) || !aligned(grad_out, 16)) return LOCO_ERR_ALIGNMENT;
+    if (loco_status_t st = check_device_range(codes, (W - 1) * code_stride_bytes + cb)) return st;
+    if (loco_status_t st = check_device_range(scales, ((W - 1) * scale_stride_elems + nb) * sizeof(float)))
+        return st;
+    if (loco_status_t st = check_device_range(grad_out, n * sizeof(float))) return st;
+    unsigned grid;
+    if (loco_status_t st = grid_for(n, (size_t)kTile * kDrTiles, &grid)) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool ok = bits == 4 ? dispatch_dr_block<4>(block_size, grid, s, codes, code_stride_bytes, scales,
+                                                    scale_stride_elems, num_workers, n, grad_out)
+                              : dispatch_dr_block<8>(block_size, grid, s, codes, code_stride_bytes, scales,
+                                                    scale_stride_elems, num_workers, n, grad_out);
+    if (!ok) return LOCO_ERR_UNSUPPORTED;
+    return launched();
+}
+
+loco_status_t loco_stream_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (bytes == 0) return LOCO_OK;
+    if (!dst || !src) return LOCO_ERR_INVALID_ARG;
+    if (bytes % 16 != 0 || !aligned(dst, 16) || !aligned(src, 16)) return LOCO_ERR_ALIGNMENT;
+    if (loco_status_t st = check_device_range(dst, bytes)) return st;
+    if (loco_status_t st = check_device_range(src, bytes)) return st;
+    const size_t n16 = bytes / 16;
+    unsigned grid;
+    if (loco_status_t st = grid_for(n16, (size_t)kThreads * kCopyTiles, &grid)) return st;
+    copy_kernel<kCopyTiles, kNonTemporal><<<dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream)>>>(
+        static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n16);
+    return launched();
+}
+
+}  // extern "C"
