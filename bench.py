@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of LoCo's per-step local path on one MI355X.
+
+A step is one pass of the whole path (arXiv 2407.04480, Alg. 1): compensate-quantize
+of this worker's gradient shard (steps 1-2) into slot 0 of a receive buffer, then
+dequant-reduce of the W payloads in that buffer (step 3).  All inputs are synthetic,
+seeded and resident in HBM before the timed region; the error state evolves in place,
+so every timed step is a real step.
+
+Prints ONE JSON line: throughput in algorithmic GB/s over the whole step, the
+roofline of the dominant kernel (HIP events on the launch stream), and the CPU
+oracle timed on this machine's host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "compensate+quantize and dequant-reduce GB/s on one MI355X; % of HBM peak"
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
+# what the same counters read for loco_stream_copy of known size.  Keyed by
+# (workload, kernel); the profiles/ file named holds the run these come from.
+MEASURED_TRAFFIC: dict = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama7b_shard_4bit_b256")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 26,
+                    help="elements of the workload the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-copy-ceiling", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, grads, recv_codes, cstride, recv_scales, nb_full, sample, bytes_cq, bytes_dr):
+    """Time the oracle (as it stands) on the first `sample` elements of the workload and
+    check the GPU's payload of those elements against it."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2407_04480_amd import workloads
+
+    B, bits, W = w.block_size, w.bits, w.num_workers
+    ns = min(w.n, sample) // (2 * B) * (2 * B)
+    if ns == 0:
+        return None
+    cores = max(1, min(16, os.cpu_count() or 1))
+    g_host = workloads.as_numpy_grad(grads[0][:ns])
+    cb, nb = oracle.code_bytes(ns, bits), oracle.num_blocks(ns, B)
+    codes = np.empty((W, cb), np.uint8)
+    scales = np.empty((W, nb), np.float32)
+    for k in range(W):
+        codes[k] = recv_codes[k * cstride:k * cstride + cb].cpu().numpy()
+        scales[k] = recv_scales[k * nb_full:k * nb_full + nb].cpu().numpy()
+
+    def run(threads):
+        e = np.zeros(ns, np.float32)
+        t0 = time.perf_counter()
+        c, s = oracle.compensate_quantize(g_host, e, bits, B, w.beta, 0, threads=threads)
+        t1 = time.perf_counter()
+        out = oracle.dequant_reduce(codes, scales, W, ns, bits, B, cb, nb, threads=threads)
+        t2 = time.perf_counter()
+        return t1 - t0, t2 - t1, c, s, out
+
+    cq1, dr1, _, _, _ = run(1)
+    best = None
+    for _ in range(3):
+        r = run(cores)
+        if best is None or r[0] + r[1] < best[0] + best[1]:
+            best = r
+    cqm, drm = best[0], best[1]
+    step_bytes = (bytes_cq + bytes_dr) * ns
+    return {
+        "value": step_bytes / (cqm + drm) / 1e9,
+        "unit": "GB/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": f"first {ns} elements of the shard, one step (compensate-quantize from a zero state + "
+                  f"dequant-reduce W={W}), best of 3",
+        "seconds": {"compensate_quantize": cqm, "dequant_reduce": drm},
+        "elements_per_s": ns / (cqm + drm),
+        "single_thread": {"value": step_bytes / (cq1 + dr1) / 1e9, "unit": "GB/s",
+                          "seconds": {"compensate_quantize": cq1, "dequant_reduce": dr1}},
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; payloads of the other workers are resident buffers "
+              "on the same device, so --gpus must be 1.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2407_04480_amd import (loco_code_bytes, loco_compensate_quantize, loco_dequant_reduce,
+                                      loco_error_state_init, loco_num_blocks, workloads)
+    from paper_2407_04480_amd.binding import loco_stream_copy
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU path.", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = workloads.by_name(args.workload)
+    n, bits, B, W = w.n, w.bits, w.block_size, w.num_workers
+    bytes_cq, bytes_dr = workloads.algorithmic_bytes(w)
+
+    # ---- resident inputs: two own gradients (used alternately), W-1 peers' payloads ----
+    grads = [workloads.gradient(w, s, device=dev) for s in range(2)]
+    err = torch.empty(n, dtype=torch.float32, device=dev)
+    loco_error_state_init(err)
+    cb, nb = loco_code_bytes(n, bits), loco_num_blocks(n, B)
+    cstride = (cb + 15) // 16 * 16
+    recv_codes = torch.zeros(W * cstride, dtype=torch.uint8, device=dev)
+    recv_scales = torch.zeros(W * nb, dtype=torch.float32, device=dev)
+    tmp_err = torch.empty(n, dtype=torch.float32, device=dev)
+    for k in range(1, W):
+        gk = workloads.gradient(w, 0, worker=k, device=dev)
+        loco_error_state_init(tmp_err)
+        loco_compensate_quantize(gk, tmp_err, bits, B, w.beta, False,
+                                 recv_codes[k * cstride:k * cstride + cb], recv_scales[k * nb:(k + 1) * nb])
+        del gk
+    del tmp_err
+    out = torch.empty(n, dtype=torch.float32, device=dev)
+    own_codes, own_scales = recv_codes[:cb], recv_scales[:nb]
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream()
+
+    def step(i, ev=None):
+        g = grads[i & 1]
+        if ev is not None:
+            ev[0].record(stream)
+        loco_compensate_quantize(g, err, bits, B, w.beta, False, own_codes, own_scales, stream)
+        if ev is not None:
+            ev[1].record(stream)
+        loco_dequant_reduce(recv_codes, cstride, recv_scales, nb, W, n, bits, B, out, stream)
+        if ev is not None:
+            ev[2].record(stream)
+
+    for i in range(args.warmup):
+        step(i)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    total_s = t1 - t0
+    ms_per_step = total_s / args.steps * 1e3
+    cq_ms = sorted(e[0].elapsed_time(e[1]) for e in events)
+    dr_ms = sorted(e[1].elapsed_time(e[2]) for e in events)
+    cq_avg, dr_avg = sum(cq_ms) / len(cq_ms), sum(dr_ms) / len(dr_ms)
+    step_bytes = (bytes_cq + bytes_dr) * n
+    value = step_bytes / (total_s / args.steps) / 1e9
+
+    def kernel_entry(name, per_elem, avg_ms, all_ms):
+        gbps = per_elem * n / (avg_ms * 1e-3) / 1e9
+        tr = MEASURED_TRAFFIC.get((w.name, name))
+        return {"kernel": name, "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": gbps / HBM_PEAK_GBPS, "traffic": tr, "avg_ms": avg_ms,
+                "median_ms": all_ms[len(all_ms) // 2], "min_ms": all_ms[0],
+                "algorithmic_bytes_per_launch": per_elem * n}
+
+    k_cq = kernel_entry("loco_compensate_quantize", bytes_cq, cq_avg, cq_ms)
+    k_dr = kernel_entry("loco_dequant_reduce", bytes_dr, dr_avg, dr_ms)
+    dominant = k_cq if cq_avg >= dr_avg else k_dr
+
+    copy_gbps = None
+    if not args.no_copy_ceiling:
+        nbytes = 1 << 31
+        src = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        src.zero_()
+        for _ in range(2):
+            loco_stream_copy(dst, src, stream)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(10):
+            loco_stream_copy(dst, src, stream)
+        b.record(stream)
+        torch.cuda.synchronize()
+        copy_gbps = 2 * nbytes * 10 / (a.elapsed_time(b) * 1e-3) / 1e9
+        del src, dst
+
+    cpu = None
+    if args.cpu_sample > 0:
+        # own payload for the sample: one compensate-quantize step from a zero state
+        loco_error_state_init(err)
+        loco_compensate_quantize(grads[0], err, bits, B, w.beta, False, own_codes, own_scales, stream)
+        torch.cuda.synchronize()
+        cpu = cpu_baseline(w, grads, recv_codes, cstride, recv_scales, nb, args.cpu_sample, bytes_cq, bytes_dr)
+
+    line = {
+        "metric": METRIC,
+        "value": value,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "n": n, "grad_dtype": str(w.grad_dtype).replace("torch.", ""),
+                   "bits": bits, "block_size": B, "beta": w.beta, "num_workers": W,
+                   "step": "compensate_quantize + dequant_reduce"},
+        "elements_per_s": n / (total_s / args.steps),
+        "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
+        "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
+        | {"kernel": dominant["kernel"]},
+        "kernels": [k_cq, k_dr],
+        "copy_ceiling_GBps": copy_gbps,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
