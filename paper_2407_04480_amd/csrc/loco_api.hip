@@ -11,13 +11,18 @@ namespace {
 
 using namespace loco;
 
-// Launch shape chosen by measurement on MI355X (see the design notes): tiles of 2048
-// elements per workgroup and whether loads/stores carry the non-temporal hint.
-constexpr int kCqTiles = LOCO_CQ_TILES;
-constexpr int kDrTiles = LOCO_DR_TILES;
+// Launch shape chosen by measurement on MI355X: slots of 256 elements per wavefront,
+// threads per workgroup, payloads in flight per lane in the reduce kernel, and the
+// non-temporal hint on the streaming loads/stores.
+constexpr int kCqSlots = LOCO_CQ_SLOTS;
+constexpr int kCqThreads = LOCO_CQ_THREADS;
+constexpr int kDrSlots = LOCO_DR_SLOTS;
+constexpr int kDrThreads = LOCO_DR_THREADS;
 constexpr int kDrWorkersInFlight = LOCO_DR_WU;
 constexpr bool kNonTemporal = LOCO_NT != 0;
-constexpr int kCopyTiles = 4;
+constexpr int kCopySlots = 2;
+constexpr int kCopyThreads = 64;
+static_assert(kCqSlots % 2 == 0 && kDrSlots >= 1, "block size 512 needs an even number of slots");
 
 std::atomic<int> g_pointer_checks{1};
 
@@ -58,7 +63,7 @@ template <typename G, int BITS, int BLOCK>
 void launch_cq(unsigned grid, hipStream_t s, const void* grad, float* err, size_t n, float beta,
                int reset, uint8_t* codes, float* scales) {
     const float one_minus_beta = 1.0f - beta;
-    cq_kernel<G, BITS, BLOCK, kCqTiles, kNonTemporal><<<dim3(grid), dim3(kThreads), 0, s>>>(
+    cq_kernel<G, BITS, BLOCK, kCqSlots, kCqThreads, kNonTemporal><<<dim3(grid), dim3(kCqThreads), 0, s>>>(
         grad, err, n, beta, one_minus_beta, reset, codes, scales);
 }
 
@@ -79,8 +84,8 @@ template <int BITS, int BLOCK>
 void launch_dr(unsigned grid, hipStream_t s, const uint8_t* codes, size_t cs, const float* scales,
                size_t ss, int W, size_t n, float* out) {
     const float inv_w = 1.0f / (float)W;
-    dr_kernel<BITS, BLOCK, kDrTiles, kDrWorkersInFlight, kNonTemporal>
-        <<<dim3(grid), dim3(kThreads), 0, s>>>(codes, cs, scales, ss, W, n, inv_w, out);
+    dr_kernel<BITS, BLOCK, kDrSlots, kDrThreads, kDrWorkersInFlight, kNonTemporal>
+        <<<dim3(grid), dim3(kDrThreads), 0, s>>>(codes, cs, scales, ss, W, n, inv_w, out);
 }
 
 template <int BITS>
@@ -131,9 +136,9 @@ loco_status_t loco_error_state_init(float* err_state, size_t n, void* stream) {
     if (!aligned(err_state, 16)) return LOCO_ERR_ALIGNMENT;
     if (loco_status_t st = check_device_range(err_state, n * sizeof(float))) return st;
     unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kThreads * 4 * kCopyTiles, &grid)) return st;
-    fill_zero_kernel<kCopyTiles, kNonTemporal>
-        <<<dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream)>>>(err_state, n);
+    if (loco_status_t st = grid_for(n, (size_t)kCopyThreads * 4 * kCopySlots, &grid)) return st;
+    fill_zero_kernel<kCopySlots, kCopyThreads, kNonTemporal>
+        <<<dim3(grid), dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream)>>>(err_state, n);
     return launched();
 }
 
@@ -155,7 +160,7 @@ loco_status_t loco_compensate_quantize(const void* grad, loco_dtype_t grad_dtype
     if (loco_status_t st = check_device_range(scales_out, loco_num_blocks(n, block_size) * sizeof(float)))
         return st;
     unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kTile * kCqTiles, &grid)) return st;
+    if (loco_status_t st = grid_for(n, (size_t)kSlot * kCqSlots * (kCqThreads / kWave), &grid)) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     bool ok;
     if (grad_dtype == LOCO_BF16) {
@@ -192,7 +197,7 @@ loco_status_t loco_dequant_reduce(const uint8_t* codes, size_t code_stride_bytes
         return st;
     if (loco_status_t st = check_device_range(grad_out, n * sizeof(float))) return st;
     unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kTile * kDrTiles, &grid)) return st;
+    if (loco_status_t st = grid_for(n, (size_t)kSlot * kDrSlots * (kDrThreads / kWave), &grid)) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool ok = bits == 4 ? dispatch_dr_block<4>(block_size, grid, s, codes, code_stride_bytes, scales,
                                                     scale_stride_elems, num_workers, n, grad_out)
@@ -210,8 +215,8 @@ loco_status_t loco_stream_copy(void* dst, const void* src, size_t bytes, void* s
     if (loco_status_t st = check_device_range(src, bytes)) return st;
     const size_t n16 = bytes / 16;
     unsigned grid;
-    if (loco_status_t st = grid_for(n16, (size_t)kThreads * kCopyTiles, &grid)) return st;
-    copy_kernel<kCopyTiles, kNonTemporal><<<dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream)>>>(
+    if (loco_status_t st = grid_for(n16, (size_t)kCopyThreads * kCopySlots, &grid)) return st;
+    copy_kernel<kCopySlots, kCopyThreads, kNonTemporal><<<dim3(grid), dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream)>>>(
         static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n16);
     return launched();
 }

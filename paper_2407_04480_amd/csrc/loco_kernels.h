@@ -5,15 +5,17 @@
 //              quantise, self-decode, fold the error into the moving average; one pass.
 //   dr_kernel  Algorithm 1 step 3 (Eq. 8): decode W payloads and average in fp32.
 //
-// Work decomposition shared by both: a lane owns 8 consecutive elements ("octet"), a
-// 256-thread workgroup owns TILES_PER_WG consecutive tiles of 2048 elements.  A
-// quantisation block of 32..512 elements is therefore 4..64 consecutive lanes of one
-// wavefront, and its max-abs is an all-reduce over those lanes with DPP / swizzle
-// cross-lane moves; no LDS memory and no barrier is needed.  One lane's 8 codes are one
-// dword (4-bit) or two (8-bit), so a wavefront writes 256 or 512 contiguous bytes.
+// Work decomposition shared by both: a lane owns 4 consecutive elements (a "quad"), so
+// one wavefront instruction moves 256 consecutive elements (a "slot": 1 KB of fp32 state,
+// 512 B of bf16 gradient) with every lane's 16 bytes adjacent to its neighbour's.  A
+// wavefront owns SLOTS consecutive slots and is scheduled on its own (one-wave
+// workgroups): measured on MI355X this shape, with the non-temporal hint on every
+// streaming access, carries the most bytes per second.  A quantisation block of 32..512
+// elements lies inside one wavefront's tile, so its max-abs is an all-reduce over 8..64
+// lanes (and at most two slots) with DPP moves and lane reads; no LDS, no barrier.
 //
-// Floating point: every operation below is one IEEE binary32 operation in the order
-// the method states; the file must be compiled with -ffp-contract=off and without any
+// Floating point: every operation below is one IEEE binary32 operation in the order the
+// method states; the file must be compiled with -ffp-contract=off and without any
 // fast-math flag.  The only fused operation is the fmaf of Eq. 5.
 #pragma once
 
@@ -29,9 +31,9 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 struct bf16_t { uint16_t bits; };  // storage tag only; widened with integer shifts
 
-constexpr int kThreads = 256;             // 4 wavefronts
-constexpr int kOctet = 8;                 // elements per lane per tile
-constexpr int kTile = kThreads * kOctet;  // 2048 elements
+constexpr int kWave = 64;
+constexpr int kQuad = 4;               // elements per lane per slot
+constexpr int kSlot = kWave * kQuad;   // 256 elements per wavefront instruction
 
 template <bool NT, typename V>
 __device__ __forceinline__ V vload(const V* p) {
@@ -44,6 +46,8 @@ __device__ __forceinline__ void vstore(V* p, V v) {
     else *p = v;
 }
 
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
 // ---- cross-lane all-reduce (max) over aligned groups of LANES consecutive lanes ----
 // Operands are bit patterns of non-negative floats, which order like unsigned ints.
 template <int CTRL>
@@ -51,27 +55,32 @@ __device__ __forceinline__ uint32_t dpp_move(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
 }
 template <int LANES>
-__device__ __forceinline__ uint32_t group_max_u32(uint32_t v) {
-    static_assert(LANES == 4 || LANES == 8 || LANES == 16 || LANES == 32 || LANES == 64, "group size");
-    v = max(v, dpp_move<0xB1>(v));                       // quad_perm [1,0,3,2]: lane ^ 1
-    v = max(v, dpp_move<0x4E>(v));                       // quad_perm [2,3,0,1]: lane ^ 2
-    if constexpr (LANES >= 8) v = max(v, dpp_move<0x141>(v));   // row_half_mirror: other quad of 8
-    if constexpr (LANES >= 16) v = max(v, dpp_move<0x140>(v));  // row_mirror: other half of 16
-    if constexpr (LANES >= 32)                                   // ds_swizzle bit mode, lane ^ 16
-        v = max(v, (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x401F));
-    if constexpr (LANES >= 64) v = max(v, (uint32_t)__shfl_xor((int)v, 32, 64));
+__device__ __forceinline__ uint32_t group_max_u32(uint32_t v, int lane) {
+    static_assert(LANES == 8 || LANES == 16 || LANES == 32 || LANES == 64, "group size");
+    v = umax(v, dpp_move<0xB1>(v));                          // quad_perm [1,0,3,2]: lane ^ 1
+    v = umax(v, dpp_move<0x4E>(v));                          // quad_perm [2,3,0,1]: lane ^ 2
+    v = umax(v, dpp_move<0x141>(v));                         // row_half_mirror: other quad of 8
+    if constexpr (LANES >= 16) v = umax(v, dpp_move<0x140>(v));  // row_mirror: other half of 16
+    if constexpr (LANES >= 32) {
+        // every lane of a 16-lane row now holds the row's maximum: combine rows through SGPRs
+        const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
+        const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+        const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
+        const uint32_t r3 = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+        const uint32_t lo = umax(r0, r1), hi = umax(r2, r3);
+        if constexpr (LANES == 32) v = lane < 32 ? lo : hi;
+        else v = umax(lo, hi);
+    }
     return v;
 }
 
-// ---- gradient loads: 8 elements widened to fp32 ----
+// ---- gradient loads: one quad widened to fp32 ----
 template <typename G> struct Grad;
 template <> struct Grad<float> {
     template <bool NT>
-    static __device__ __forceinline__ void load8(const void* base, size_t i, float (&g)[8]) {
-        const f32x4* p = reinterpret_cast<const f32x4*>(static_cast<const float*>(base) + i);
-        f32x4 a = vload<NT>(p), b = vload<NT>(p + 1);
+    static __device__ __forceinline__ void load4(const void* base, size_t i, float (&g)[4]) {
+        f32x4 a = vload<NT>(reinterpret_cast<const f32x4*>(static_cast<const float*>(base) + i));
         g[0] = a.x; g[1] = a.y; g[2] = a.z; g[3] = a.w;
-        g[4] = b.x; g[5] = b.y; g[6] = b.z; g[7] = b.w;
     }
     static __device__ __forceinline__ float load1(const void* base, size_t i) {
         return static_cast<const float*>(base)[i];
@@ -79,229 +88,266 @@ template <> struct Grad<float> {
 };
 template <> struct Grad<bf16_t> {
     template <bool NT>
-    static __device__ __forceinline__ void load8(const void* base, size_t i, float (&g)[8]) {
-        const u32x4* p = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(base) + i);
-        u32x4 a = vload<NT>(p);
-        uint32_t w[4] = {a.x, a.y, a.z, a.w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {  // bf16 is the high half of a binary32: exact
-            g[2 * k] = __uint_as_float(w[k] << 16);
-            g[2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
-        }
+    static __device__ __forceinline__ void load4(const void* base, size_t i, float (&g)[4]) {
+        u32x2 a = vload<NT>(reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(base) + i));
+        // bf16 is the high half of a binary32: widening is exact
+        g[0] = __uint_as_float(a.x << 16); g[1] = __uint_as_float(a.x & 0xFFFF0000u);
+        g[2] = __uint_as_float(a.y << 16); g[3] = __uint_as_float(a.y & 0xFFFF0000u);
     }
     static __device__ __forceinline__ float load1(const void* base, size_t i) {
         return __uint_as_float((uint32_t)static_cast<const uint16_t*>(base)[i] << 16);
     }
 };
 
-// ---- Algorithm 1 steps 1-2 on one octet held in registers ----
-// h: compensated gradient (Eq. 2), e: old state.  Writes the new state, the packed codes
-// and the block's step D.  All lanes of a quantisation block call this together.
-template <int BITS, int BLOCK>
-__device__ __forceinline__ void cq_octet(const float (&h)[8], const float (&e)[8], float beta,
-                                         float one_minus_beta, bool reset, float (&e_new)[8],
-                                         uint32_t (&packed)[BITS / 4], float& step) {
+// ---- Algorithm 1 steps 1-2 on a wavefront's tile held in registers ----
+// h: compensated gradient (Eq. 2), e: old state; on return e holds the new state, packed
+// the codes of each quad (16 or 32 bits) and step the quad's block step D.
+template <int BITS, int BLOCK, int SLOTS>
+__device__ __forceinline__ void cq_tile(const float (&h)[SLOTS][4], float (&e)[SLOTS][4], float beta,
+                                        float one_minus_beta, bool reset, int lane,
+                                        uint32_t (&packed)[SLOTS], float (&step)[SLOTS]) {
     constexpr int QMAX = (1 << (BITS - 1)) - 1;
     constexpr int QMIN = -(1 << (BITS - 1));
-    float a = 0.0f;
+    static_assert(BLOCK <= kSlot || SLOTS % (BLOCK / kSlot) == 0, "a block must lie inside the tile");
+    float a[SLOTS];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(h[j]));
-    a = __uint_as_float(group_max_u32<BLOCK / kOctet>(__float_as_uint(a)));
-
-    float D = a / (float)QMAX;           // step of the block: 1/s_b, correctly rounded
-    const bool live = !(D < FLT_MIN);    // zero or subnormal step: encode nothing
-    const float r = live ? 1.0f / D : 0.0f;
-    D = live ? D : 0.0f;
-    step = D;
-
-    packed[0] = 0;
-    if constexpr (BITS == 8) packed[1] = 0;
+    for (int s = 0; s < SLOTS; ++s)
+        a[s] = fmaxf(fmaxf(fabsf(h[s][0]), fabsf(h[s][1])), fmaxf(fabsf(h[s][2]), fabsf(h[s][3])));
+    if constexpr (BLOCK > kSlot) {  // a block spans BLOCK/256 adjacent slots of this wavefront
+        constexpr int SPAN = BLOCK / kSlot;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        int q = (int)rintf(h[j] * r);                 // Eq. 1: nearest integer, ties to even
-        q = min(max(q, QMIN), QMAX);                  // ... within the p-bit range
-        const float d = (float)q * D;                 // decompressor
-        const float delta = h[j] - d;                 // Eq. 4
-        const float bd = beta * delta;
-        e_new[j] = reset ? 0.0f : __builtin_fmaf(one_minus_beta, e[j], bd);  // Eq. 5 / Eq. 7
-        if constexpr (BITS == 4) packed[0] |= ((uint32_t)q & 15u) << (4 * j);
-        else packed[j >> 2] |= ((uint32_t)q & 255u) << (8 * (j & 3));
+        for (int s = 0; s < SLOTS; s += SPAN) {
+            float m = a[s];
+#pragma unroll
+            for (int k = 1; k < SPAN; ++k) m = fmaxf(m, a[s + k]);
+            m = __uint_as_float(group_max_u32<kWave>(__float_as_uint(m), lane));
+#pragma unroll
+            for (int k = 0; k < SPAN; ++k) a[s + k] = m;
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s)
+            a[s] = __uint_as_float(group_max_u32<BLOCK / kQuad>(__float_as_uint(a[s]), lane));
+    }
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s) {
+        float D = a[s] / (float)QMAX;        // step of the block: 1/s_b, correctly rounded
+        const bool live = !(D < FLT_MIN);    // zero or subnormal step: encode nothing
+        const float r = live ? 1.0f / D : 0.0f;
+        D = live ? D : 0.0f;
+        step[s] = D;
+        uint32_t pk = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int q = (int)rintf(h[s][j] * r);              // Eq. 1: nearest integer, ties to even
+            q = min(max(q, QMIN), QMAX);                  // ... within the p-bit range
+            const float d = (float)q * D;                 // decompressor
+            const float delta = h[s][j] - d;              // Eq. 4
+            const float bd = beta * delta;
+            e[s][j] = reset ? 0.0f : __builtin_fmaf(one_minus_beta, e[s][j], bd);  // Eq. 5 / Eq. 7
+            pk |= ((uint32_t)q & (BITS == 4 ? 15u : 255u)) << (BITS * j);
+        }
+        packed[s] = pk;
     }
 }
 
-// grid: ceil(n / (kTile * TILES)) workgroups of kThreads.  Workgroups whose chunk lies
-// wholly inside [0, n) take the vector path; the last one may take the guarded path,
-// which touches memory element by element and never beyond n.
-template <typename G, int BITS, int BLOCK, int TILES, bool NT>
-__global__ void __launch_bounds__(kThreads)
+// One wavefront per SLOTS*256 elements; THREADS/64 wavefronts per workgroup, each with its
+// own contiguous tile.  grid = ceil(n / (SLOTS*256*THREADS/64)).  A wavefront whose tile
+// lies inside [0, n) takes the vector path; the last one may take the guarded path, which
+// touches memory element by element and never at or beyond n.
+template <typename G, int BITS, int BLOCK, int SLOTS, int THREADS, bool NT>
+__global__ void __launch_bounds__(THREADS)
 cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, float beta,
           float one_minus_beta, int reset, uint8_t* __restrict__ codes, float* __restrict__ scales) {
-    constexpr int GROUP = BLOCK / kOctet;  // lanes per quantisation block
-    const size_t chunk0 = (size_t)blockIdx.x * (size_t)(kTile * TILES);
+    constexpr int GROUP = BLOCK >= kSlot ? kWave : BLOCK / kQuad;  // lanes per block within a slot
+    constexpr size_t TILE = (size_t)kSlot * SLOTS;
+    const int lane = threadIdx.x & (kWave - 1);
+    const size_t wave = (size_t)blockIdx.x * (THREADS / kWave) + (threadIdx.x >> 6);
+    const size_t tile0 = wave * TILE;
     const bool rst = reset != 0;
+    if (tile0 >= n) return;  // whole wavefront
 
-    if (chunk0 + (size_t)(kTile * TILES) <= n) {
-        float g[TILES][8], e[TILES][8];
+    float h[SLOTS][4], e[SLOTS][4], step[SLOTS];
+    uint32_t pk[SLOTS];
+    if (tile0 + TILE <= n) {
 #pragma unroll
-        for (int t = 0; t < TILES; ++t) {
-            const size_t i = chunk0 + (size_t)t * kTile + (size_t)threadIdx.x * kOctet;
-            Grad<G>::template load8<NT>(grad, i, g[t]);
-            const f32x4* pe = reinterpret_cast<const f32x4*>(err + i);
-            f32x4 a = vload<NT>(pe), b = vload<NT>(pe + 1);
-            e[t][0] = a.x; e[t][1] = a.y; e[t][2] = a.z; e[t][3] = a.w;
-            e[t][4] = b.x; e[t][5] = b.y; e[t][6] = b.z; e[t][7] = b.w;
+        for (int s = 0; s < SLOTS; ++s) {
+            const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
+            Grad<G>::template load4<NT>(grad, i, h[s]);
+            const f32x4 v = vload<NT>(reinterpret_cast<const f32x4*>(err + i));
+            e[s][0] = v.x; e[s][1] = v.y; e[s][2] = v.z; e[s][3] = v.w;
         }
 #pragma unroll
-        for (int t = 0; t < TILES; ++t) {
-            const size_t i = chunk0 + (size_t)t * kTile + (size_t)threadIdx.x * kOctet;
-            float h[8], en[8], step;
-            uint32_t pk[BITS / 4];
+        for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
-            for (int j = 0; j < 8; ++j) h[j] = g[t][j] + e[t][j];  // Eq. 2
-            cq_octet<BITS, BLOCK>(h, e[t], beta, one_minus_beta, rst, en, pk, step);
-            f32x4* pe = reinterpret_cast<f32x4*>(err + i);
-            vstore<NT>(pe, f32x4{en[0], en[1], en[2], en[3]});
-            vstore<NT>(pe + 1, f32x4{en[4], en[5], en[6], en[7]});
+            for (int j = 0; j < 4; ++j) h[s][j] = h[s][j] + e[s][j];  // Eq. 2
+        cq_tile<BITS, BLOCK, SLOTS>(h, e, beta, one_minus_beta, rst, lane, pk, step);
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
+            vstore<NT>(reinterpret_cast<f32x4*>(err + i), f32x4{e[s][0], e[s][1], e[s][2], e[s][3]});
             if constexpr (BITS == 4) {
-                vstore<NT>(reinterpret_cast<uint32_t*>(codes + (i >> 1)), pk[0]);
+                vstore<NT>(reinterpret_cast<uint16_t*>(codes + (i >> 1)), (uint16_t)pk[s]);
             } else {
-                vstore<NT>(reinterpret_cast<u32x2*>(codes + i), u32x2{pk[0], pk[1]});
+                vstore<NT>(reinterpret_cast<uint32_t*>(codes + i), pk[s]);
             }
-            if ((threadIdx.x & (GROUP - 1)) == 0) scales[i / BLOCK] = step;
+            if constexpr (BLOCK > kSlot) {
+                if (lane == 0 && s % (BLOCK / kSlot) == 0) scales[i / BLOCK] = step[s];
+            } else {
+                if ((lane & (GROUP - 1)) == 0) scales[i / BLOCK] = step[s];
+            }
         }
     } else {
-#pragma unroll 1
-        for (int t = 0; t < TILES; ++t) {
-            const size_t i = chunk0 + (size_t)t * kTile + (size_t)threadIdx.x * kOctet;
-            if (chunk0 + (size_t)t * kTile >= n) break;  // uniform over the workgroup
-            float h[8], e[8], en[8], step;
-            uint32_t pk[BITS / 4];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+        for (int s = 0; s < SLOTS; ++s) {
+            const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
                 const bool in = i + j < n;
-                e[j] = in ? err[i + j] : 0.0f;
+                e[s][j] = in ? err[i + j] : 0.0f;
                 const float gj = in ? Grad<G>::load1(grad, i + j) : 0.0f;
-                h[j] = gj + e[j];  // elements past n read as h = 0: neutral for the max, code 0
+                h[s][j] = gj + e[s][j];  // past n: h = 0, neutral for the max, code 0
             }
-            cq_octet<BITS, BLOCK>(h, e, beta, one_minus_beta, rst, en, pk, step);
+        }
+        cq_tile<BITS, BLOCK, SLOTS>(h, e, beta, one_minus_beta, rst, lane, pk, step);
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (i + j < n) err[i + j] = en[j];
+        for (int s = 0; s < SLOTS; ++s) {
+            const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (i + j < n) err[i + j] = e[s][j];
             if constexpr (BITS == 4) {
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    if (i + 2 * k < n) codes[(i >> 1) + k] = (uint8_t)(pk[0] >> (8 * k));
+                if (i < n) codes[i >> 1] = (uint8_t)pk[s];
+                if (i + 2 < n) codes[(i >> 1) + 1] = (uint8_t)(pk[s] >> 8);
             } else {
 #pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (i + j < n) codes[i + j] = (uint8_t)(pk[j >> 2] >> (8 * (j & 3)));
+                for (int j = 0; j < 4; ++j)
+                    if (i + j < n) codes[i + j] = (uint8_t)(pk[s] >> (8 * j));
             }
-            if ((threadIdx.x & (GROUP - 1)) == 0 && i < n) scales[i / BLOCK] = step;
+            if constexpr (BLOCK > kSlot) {
+                if (lane == 0 && s % (BLOCK / kSlot) == 0 && i < n) scales[i / BLOCK] = step[s];
+            } else {
+                if ((lane & (GROUP - 1)) == 0 && i < n) scales[i / BLOCK] = step[s];
+            }
         }
     }
 }
 
 // ---- Algorithm 1 step 3 / Eq. 8 ----
+// c holds one quad's codes in its low 16 (4-bit) or 32 (8-bit) bits.
 template <int BITS>
-__device__ __forceinline__ void dr_accumulate(const uint32_t (&c)[BITS / 4], float D, float (&acc)[8]) {
+__device__ __forceinline__ void dr_accumulate(uint32_t c, float D, float (&acc)[4]) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        int q;
-        if constexpr (BITS == 4) q = ((int)(c[0] << (28 - 4 * j))) >> 28;          // signed nibble j
-        else q = ((int)(c[j >> 2] << (24 - 8 * (j & 3)))) >> 24;                   // signed byte j
+    for (int j = 0; j < 4; ++j) {
+        const int q = ((int)(c << (32 - BITS * (j + 1)))) >> (32 - BITS);  // signed field j
         const float d = (float)q * D;   // decompressor of Eq. 1
         acc[j] = acc[j] + d;            // sum of Eq. 8, in worker order
     }
 }
 
-// grid: ceil(n / (kTile * TILES)) workgroups of kThreads; WU payloads are in flight per lane.
-template <int BITS, int BLOCK, int TILES, int WU, bool NT>
-__global__ void __launch_bounds__(kThreads)
+template <int BITS, bool NT>
+__device__ __forceinline__ uint32_t load_quad_codes(const uint8_t* p) {
+    if constexpr (BITS == 4) return vload<NT>(reinterpret_cast<const uint16_t*>(p));
+    else return vload<NT>(reinterpret_cast<const uint32_t*>(p));
+}
+
+// Same decomposition as cq_kernel; WU payloads are in flight per lane and slot.
+template <int BITS, int BLOCK, int SLOTS, int THREADS, int WU, bool NT>
+__global__ void __launch_bounds__(THREADS)
 dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const float* __restrict__ scales,
           size_t scale_stride, int W, size_t n, float inv_w, float* __restrict__ out) {
-    constexpr int CW = BITS / 4;  // dwords of codes per octet
-    const size_t chunk0 = (size_t)blockIdx.x * (size_t)(kTile * TILES);
+    constexpr size_t TILE = (size_t)kSlot * SLOTS;
+    const int lane = threadIdx.x & (kWave - 1);
+    const size_t wave = (size_t)blockIdx.x * (THREADS / kWave) + (threadIdx.x >> 6);
+    const size_t tile0 = wave * TILE;
+    if (tile0 >= n) return;
 
-    if (chunk0 + (size_t)(kTile * TILES) <= n) {
+    if (tile0 + TILE <= n) {
+        float acc[SLOTS][4];
+        const uint8_t* pc[SLOTS];
+        const float* ps[SLOTS];
 #pragma unroll
-        for (int t = 0; t < TILES; ++t) {
-            const size_t i = chunk0 + (size_t)t * kTile + (size_t)threadIdx.x * kOctet;
-            const uint8_t* pc = codes + (i * BITS) / 8;
-            const float* ps = scales + i / BLOCK;
-            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            int w = 0;
-            for (; w + WU <= W; w += WU) {
-                uint32_t c[WU][CW];
-                float D[WU];
+        for (int s = 0; s < SLOTS; ++s) {
+            const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
+            pc[s] = codes + (i * BITS) / 8;
+            ps[s] = scales + i / BLOCK;
 #pragma unroll
-                for (int u = 0; u < WU; ++u) {
-                    if constexpr (BITS == 4) {
-                        c[u][0] = vload<NT>(reinterpret_cast<const uint32_t*>(pc));
-                    } else {
-                        u32x2 v = vload<NT>(reinterpret_cast<const u32x2*>(pc));
-                        c[u][0] = v.x; c[u][1] = v.y;
-                    }
-                    D[u] = *ps;
-                    pc += code_stride;
-                    ps += scale_stride;
+            for (int j = 0; j < 4; ++j) acc[s][j] = 0.0f;
+        }
+        int w = 0;
+        for (; w + WU <= W; w += WU) {
+            uint32_t c[WU][SLOTS];
+            float D[WU][SLOTS];
+#pragma unroll
+            for (int u = 0; u < WU; ++u)
+#pragma unroll
+                for (int s = 0; s < SLOTS; ++s) {
+                    c[u][s] = load_quad_codes<BITS, NT>(pc[s] + (size_t)u * code_stride);
+                    D[u][s] = ps[s][(size_t)u * scale_stride];
                 }
 #pragma unroll
-                for (int u = 0; u < WU; ++u) dr_accumulate<BITS>(c[u], D[u], acc);
+            for (int s = 0; s < SLOTS; ++s) {
+                pc[s] += (size_t)WU * code_stride;
+                ps[s] += (size_t)WU * scale_stride;
             }
-            for (; w < W; ++w) {
-                uint32_t c[CW];
-                if constexpr (BITS == 4) {
-                    c[0] = vload<NT>(reinterpret_cast<const uint32_t*>(pc));
-                } else {
-                    u32x2 v = vload<NT>(reinterpret_cast<const u32x2*>(pc));
-                    c[0] = v.x; c[1] = v.y;
-                }
-                const float D = *ps;
-                pc += code_stride;
-                ps += scale_stride;
-                dr_accumulate<BITS>(c, D, acc);
+#pragma unroll
+            for (int u = 0; u < WU; ++u)
+#pragma unroll
+                for (int s = 0; s < SLOTS; ++s) dr_accumulate<BITS>(c[u][s], D[u][s], acc[s]);
+        }
+        for (; w < W; ++w) {
+#pragma unroll
+            for (int s = 0; s < SLOTS; ++s) {
+                const uint32_t c = load_quad_codes<BITS, NT>(pc[s]);
+                const float D = *ps[s];
+                pc[s] += code_stride;
+                ps[s] += scale_stride;
+                dr_accumulate<BITS>(c, D, acc[s]);
             }
-            f32x4* po = reinterpret_cast<f32x4*>(out + i);
-            vstore<NT>(po, f32x4{acc[0] * inv_w, acc[1] * inv_w, acc[2] * inv_w, acc[3] * inv_w});
-            vstore<NT>(po + 1, f32x4{acc[4] * inv_w, acc[5] * inv_w, acc[6] * inv_w, acc[7] * inv_w});
+        }
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
+            vstore<NT>(reinterpret_cast<f32x4*>(out + i),
+                       f32x4{acc[s][0] * inv_w, acc[s][1] * inv_w, acc[s][2] * inv_w, acc[s][3] * inv_w});
         }
     } else {
 #pragma unroll 1
-        for (int t = 0; t < TILES; ++t) {
-            const size_t i = chunk0 + (size_t)t * kTile + (size_t)threadIdx.x * kOctet;
+        for (int s = 0; s < SLOTS; ++s) {
+            const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
             if (i >= n) continue;
-            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            float acc[4] = {0.f, 0.f, 0.f, 0.f};
             for (int w = 0; w < W; ++w) {
-                const uint8_t* pc = codes + (size_t)w * code_stride;
-                uint32_t c[CW] = {};
+                const uint8_t* p = codes + (size_t)w * code_stride;
+                uint32_t c = 0;
                 if constexpr (BITS == 4) {
-#pragma unroll
-                    for (int k = 0; k < 4; ++k)
-                        if (i + 2 * k < n) c[0] |= (uint32_t)pc[(i >> 1) + k] << (8 * k);
+                    c = p[i >> 1];
+                    if (i + 2 < n) c |= (uint32_t)p[(i >> 1) + 1] << 8;
                 } else {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (i + j < n) c[j >> 2] |= (uint32_t)pc[i + j] << (8 * (j & 3));
+                    for (int j = 0; j < 4; ++j)
+                        if (i + j < n) c |= (uint32_t)p[i + j] << (8 * j);
                 }
                 const float D = scales[(size_t)w * scale_stride + i / BLOCK];
                 dr_accumulate<BITS>(c, D, acc);
             }
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
+            for (int j = 0; j < 4; ++j)
                 if (i + j < n) out[i + j] = acc[j] * inv_w;
         }
     }
 }
 
-// ---- helpers: zero fill and plain copy, same launch shape ----
-// grid: ceil(n16 / (kThreads * TILES)) workgroups; n16 = number of 16-byte units.
-template <int TILES, bool NT>
-__global__ void __launch_bounds__(kThreads)
+// ---- helpers: zero fill and plain copy in the same shape (16 bytes per lane and slot) ----
+template <int SLOTS, int THREADS, bool NT>
+__global__ void __launch_bounds__(THREADS)
 fill_zero_kernel(float* __restrict__ dst, size_t n) {
-    const size_t chunk0 = (size_t)blockIdx.x * (size_t)(kThreads * 4 * TILES);
+    const int lane = threadIdx.x & (kWave - 1);
+    const size_t wave = (size_t)blockIdx.x * (THREADS / kWave) + (threadIdx.x >> 6);
+    const size_t tile0 = wave * ((size_t)kSlot * SLOTS);
 #pragma unroll
-    for (int t = 0; t < TILES; ++t) {
-        const size_t i = chunk0 + (size_t)t * (kThreads * 4) + (size_t)threadIdx.x * 4;
+    for (int s = 0; s < SLOTS; ++s) {
+        const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
         if (i + 4 <= n) {
             vstore<NT>(reinterpret_cast<f32x4*>(dst + i), f32x4{0.f, 0.f, 0.f, 0.f});
         } else {
@@ -310,20 +356,22 @@ fill_zero_kernel(float* __restrict__ dst, size_t n) {
     }
 }
 
-template <int TILES, bool NT>
-__global__ void __launch_bounds__(kThreads)
+template <int SLOTS, int THREADS, bool NT>
+__global__ void __launch_bounds__(THREADS)
 copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n16) {
-    const size_t chunk0 = (size_t)blockIdx.x * (size_t)(kThreads * TILES);
-    u32x4 v[TILES];
+    const int lane = threadIdx.x & (kWave - 1);
+    const size_t wave = (size_t)blockIdx.x * (THREADS / kWave) + (threadIdx.x >> 6);
+    const size_t tile0 = wave * ((size_t)kWave * SLOTS);
+    u32x4 v[SLOTS];
 #pragma unroll
-    for (int t = 0; t < TILES; ++t) {
-        const size_t i = chunk0 + (size_t)t * kThreads + threadIdx.x;
-        if (i < n16) v[t] = vload<NT>(src + i);
+    for (int s = 0; s < SLOTS; ++s) {
+        const size_t i = tile0 + (size_t)s * kWave + lane;
+        if (i < n16) v[s] = vload<NT>(src + i);
     }
 #pragma unroll
-    for (int t = 0; t < TILES; ++t) {
-        const size_t i = chunk0 + (size_t)t * kThreads + threadIdx.x;
-        if (i < n16) vstore<NT>(dst + i, v[t]);
+    for (int s = 0; s < SLOTS; ++s) {
+        const size_t i = tile0 + (size_t)s * kWave + lane;
+        if (i < n16) vstore<NT>(dst + i, v[s]);
     }
 }
 
