@@ -26,10 +26,16 @@ if ROOT not in sys.path:
 METRIC = "compensate+quantize and dequant-reduce GB/s on one MI355X; % of HBM peak"
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by
-# what the same counters read for loco_stream_copy of known size.  Keyed by
-# (workload, kernel); the profiles/ file named holds the run these come from.
-MEASURED_TRAFFIC: dict = {}
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE, KiB per
+# dispatch), each scaled by what the same counter reads for loco_stream_copy of 2 GiB
+# (factor 2.0 for FETCH_SIZE, 1.0 for WRITE_SIZE on this machine).  The profiles/ file of
+# the same kernel and workload holds the counters and the commands.
+MEASURED_TRAFFIC = {
+    ("llama7b_shard_4bit_b256", "loco_compensate_quantize"): 8.8752e9,
+    ("llama7b_shard_4bit_b256", "loco_dequant_reduce"): 6.9720e9,
+    ("llama7b_shard_8bit_b64", "loco_compensate_quantize"): 9.3179e9,
+    ("llama7b_shard_8bit_b64", "loco_dequant_reduce"): 1.05485e10,
+}
 
 
 def parse_args():
@@ -38,7 +44,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b_shard_4bit_b256")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 26,
+    ap.add_argument("--cpu-sample", type=int, default=1 << 30,
                     help="elements of the workload the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-copy-ceiling", action="store_true")
     return ap.parse_args()

@@ -17,10 +17,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libloco.so")
 
-# Launch shape: slots of 256 elements per wavefront, threads per workgroup, payloads in
-# flight per lane in the reduce kernel, non-temporal hint on the streaming loads/stores.
-TUNING = {"LOCO_CQ_SLOTS": 2, "LOCO_CQ_THREADS": 64, "LOCO_DR_SLOTS": 2, "LOCO_DR_THREADS": 64,
-          "LOCO_DR_WU": 4, "LOCO_NT": 1}
+# Extra -D definitions (none by default; the launch shapes live in csrc/loco_api.hip).
+TUNING: dict = {}
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",

@@ -11,18 +11,26 @@ namespace {
 
 using namespace loco;
 
-// Launch shape chosen by measurement on MI355X: slots of 256 elements per wavefront,
-// threads per workgroup, payloads in flight per lane in the reduce kernel, and the
-// non-temporal hint on the streaming loads/stores.
-constexpr int kCqSlots = LOCO_CQ_SLOTS;
-constexpr int kCqThreads = LOCO_CQ_THREADS;
-constexpr int kDrSlots = LOCO_DR_SLOTS;
-constexpr int kDrThreads = LOCO_DR_THREADS;
-constexpr int kDrWorkersInFlight = LOCO_DR_WU;
-constexpr bool kNonTemporal = LOCO_NT != 0;
+// Launch shapes chosen by measurement on MI355X (sweeps at the 7B-shard size): slots of
+// 256 elements per wavefront, threads per workgroup, payloads in flight per lane in the
+// reduce kernel, the non-temporal hint on the streaming accesses, XCD-aware tile order.
+template <int BITS> struct CqShape;
+template <> struct CqShape<4> { static constexpr int kSlots = 2, kThreads = 128; };
+template <> struct CqShape<8> { static constexpr int kSlots = 2, kThreads = 64; };
+template <int BITS> struct DrShape;
+template <> struct DrShape<4> { static constexpr int kSlots = 2, kThreads = 128, kInFlight = 4; };
+template <> struct DrShape<8> { static constexpr int kSlots = 1, kThreads = 256, kInFlight = 4; };
+constexpr bool kNonTemporal = true;
+// Consecutive workgroups' tiles per XCD (see wave_tile_index).  Measured: compensate-
+// quantize is fastest with the hardware's own round robin (0); dequant-reduce loses
+// nothing with runs of 32, which keeps each cache line of block steps in one L2 instead
+// of fetching it into all eight.
+constexpr int kCqXcdRun = 0;
+constexpr int kDrXcdRun = 32;
 constexpr int kCopySlots = 2;
 constexpr int kCopyThreads = 64;
-static_assert(kCqSlots % 2 == 0 && kDrSlots >= 1, "block size 512 needs an even number of slots");
+static_assert(CqShape<4>::kSlots % 2 == 0 && CqShape<8>::kSlots % 2 == 0,
+              "block size 512 spans two slots of one wavefront");
 
 std::atomic<int> g_pointer_checks{1};
 
@@ -50,8 +58,11 @@ loco_status_t check_device_range(const void* p, size_t bytes) {
     return LOCO_OK;
 }
 
-loco_status_t grid_for(size_t units, size_t per_group, unsigned* grid) {
-    const size_t g = (units + per_group - 1) / per_group;
+// Workgroups needed for `units` at `per_group` each, rounded up to a multiple of `round`
+// (8 where the kernel spreads tiles over the XCDs itself).
+loco_status_t grid_for(size_t units, size_t per_group, unsigned* grid, size_t round = 1) {
+    size_t g = (units + per_group - 1) / per_group;
+    g = (g + round - 1) / round * round;
     if (g == 0 || g > 0x7FFFFFFFull) return LOCO_ERR_UNSUPPORTED;
     *grid = (unsigned)g;
     return LOCO_OK;
@@ -63,7 +74,9 @@ template <typename G, int BITS, int BLOCK>
 void launch_cq(unsigned grid, hipStream_t s, const void* grad, float* err, size_t n, float beta,
                int reset, uint8_t* codes, float* scales) {
     const float one_minus_beta = 1.0f - beta;
-    cq_kernel<G, BITS, BLOCK, kCqSlots, kCqThreads, kNonTemporal><<<dim3(grid), dim3(kCqThreads), 0, s>>>(
+    using Shape = CqShape<BITS>;
+    cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun>
+        <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(
         grad, err, n, beta, one_minus_beta, reset, codes, scales);
 }
 
@@ -84,8 +97,9 @@ template <int BITS, int BLOCK>
 void launch_dr(unsigned grid, hipStream_t s, const uint8_t* codes, size_t cs, const float* scales,
                size_t ss, int W, size_t n, float* out) {
     const float inv_w = 1.0f / (float)W;
-    dr_kernel<BITS, BLOCK, kDrSlots, kDrThreads, kDrWorkersInFlight, kNonTemporal>
-        <<<dim3(grid), dim3(kDrThreads), 0, s>>>(codes, cs, scales, ss, W, n, inv_w, out);
+    using Shape = DrShape<BITS>;
+    dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun>
+        <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(codes, cs, scales, ss, W, n, inv_w, out);
 }
 
 template <int BITS>
@@ -160,7 +174,9 @@ loco_status_t loco_compensate_quantize(const void* grad, loco_dtype_t grad_dtype
     if (loco_status_t st = check_device_range(scales_out, loco_num_blocks(n, block_size) * sizeof(float)))
         return st;
     unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kSlot * kCqSlots * (kCqThreads / kWave), &grid)) return st;
+    const size_t per_group = bits == 4 ? (size_t)kSlot * CqShape<4>::kSlots * (CqShape<4>::kThreads / kWave)
+                                       : (size_t)kSlot * CqShape<8>::kSlots * (CqShape<8>::kThreads / kWave);
+    if (loco_status_t st = grid_for(n, per_group, &grid, kCqXcdRun ? 8 * kCqXcdRun : 1)) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     bool ok;
     if (grad_dtype == LOCO_BF16) {
@@ -197,7 +213,9 @@ loco_status_t loco_dequant_reduce(const uint8_t* codes, size_t code_stride_bytes
         return st;
     if (loco_status_t st = check_device_range(grad_out, n * sizeof(float))) return st;
     unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kSlot * kDrSlots * (kDrThreads / kWave), &grid)) return st;
+    const size_t per_group = bits == 4 ? (size_t)kSlot * DrShape<4>::kSlots * (DrShape<4>::kThreads / kWave)
+                                       : (size_t)kSlot * DrShape<8>::kSlots * (DrShape<8>::kThreads / kWave);
+    if (loco_status_t st = grid_for(n, per_group, &grid, kDrXcdRun ? 8 * kDrXcdRun : 1)) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool ok = bits == 4 ? dispatch_dr_block<4>(block_size, grid, s, codes, code_stride_bytes, scales,
                                                     scale_stride_elems, num_workers, n, grad_out)

@@ -178,6 +178,32 @@ def test_dequant_reduce_worker_counts(bits, B, W):
     assert_f32_close(f"reduce bits={bits} B={B} W={W}", out_t.cpu().numpy(), ref)
 
 
+@pytest.mark.parametrize("bits,B", [(4, 256), (4, 64), (8, 64), (4, 512), (8, 32)])
+def test_dequant_reduce_arbitrary_payloads(bits, B):
+    """Payloads that compensate-quantize would never emit: every code value including
+    -2^(p-1), steps that are huge (16*D overflows), tiny, zero or negative."""
+    n, W = 7 * 2048 + 129, 6
+    rs = np.random.default_rng(99 + bits + B)
+    cb, nb = oracle.code_bytes(n, bits), oracle.num_blocks(n, B)
+    cstride = (cb + 15) // 16 * 16
+    codes = rs.integers(0, 256, W * cstride, dtype=np.uint8)
+    pool = np.array([0.0, 1e-4, -3e-5, 2.0 ** -126, 2.0 ** -140, 2.0 ** 119, 2.0 ** 120, 2.0 ** 121, 2.0 ** 124,
+                     3.0e38 / 127, -(2.0 ** 122), 1.0, 7.25e-3], dtype=np.float32)
+    scales = pool[rs.integers(0, pool.size, W * nb)]
+    scales[rs.random(W * nb) < 0.7] = np.float32(1e-4)      # most blocks ordinary
+    out_t = torch.empty(n, dtype=torch.float32, device=DEV)
+    loco_dequant_reduce(torch.from_numpy(codes).to(DEV), cstride, torch.from_numpy(scales).to(DEV), nb,
+                        W, n, bits, B, out_t)
+    torch.cuda.synchronize()
+    with np.errstate(over="ignore", invalid="ignore"):
+        ref = oracle.dequant_reduce(codes, scales, W, n, bits, B, cstride, nb)
+    got = out_t.cpu().numpy()
+    fin = np.isfinite(ref)
+    assert np.array_equal(np.isnan(got), np.isnan(ref)) and np.array_equal(np.isinf(got), np.isinf(ref))
+    assert np.array_equal(got[fin], ref[fin]), f"{np.count_nonzero(got[fin] != ref[fin])} values differ"
+    assert fin.mean() > 0.3
+
+
 @pytest.mark.parametrize("n", [1, 7, 9, 255, 2047, 2049, 100_003])
 def test_dequant_reduce_ragged(n):
     for bits, B in ((4, 64), (8, 128)):
