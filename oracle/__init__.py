@@ -55,7 +55,15 @@ def _bind(lib):
     lib.loco_ref_compensate_quantize_mt.argtypes = [vp, i, vp, sz, i, i, f, i, vp, vp, i]
     lib.loco_ref_dequant_reduce.argtypes = [vp, sz, vp, sz, i, sz, i, i, vp]
     lib.loco_ref_dequant_reduce_mt.argtypes = [vp, sz, vp, sz, i, sz, i, i, vp, i]
+    lib.loco_ref_fixed_compensate_quantize.argtypes = [vp, i, vp, sz, i, i, i, f, i, vp]
+    lib.loco_ref_fixed_compensate_quantize_mt.argtypes = [vp, i, vp, sz, i, i, i, f, i, vp, i]
+    lib.loco_ref_fixed_dequant_reduce.argtypes = [vp, sz, i, sz, i, i, vp]
+    lib.loco_ref_fixed_dequant_reduce_mt.argtypes = [vp, sz, i, sz, i, i, vp, i]
     for name in (
+        "loco_ref_fixed_compensate_quantize",
+        "loco_ref_fixed_compensate_quantize_mt",
+        "loco_ref_fixed_dequant_reduce",
+        "loco_ref_fixed_dequant_reduce_mt",
         "loco_ref_error_state_init",
         "loco_ref_compensate_quantize",
         "loco_ref_compensate_quantize_blocks",
@@ -155,4 +163,43 @@ def dequant_reduce(codes, scales, num_workers, n, bits, block_size,
         rc = lib.loco_ref_dequant_reduce(*args)
     if rc:
         raise ValueError("loco_ref_dequant_reduce: status %d" % rc)
+    return out
+
+
+def fixed_compensate_quantize(grad, err_state8, bits, log2_s, se_mult, beta, reset=0, threads=1, lib=None):
+    """Alg. 1 steps 1-2 as printed: global scale s = 2^log2_s, 8-bit error state with scale
+    s_e = se_mult * s (Eq. 1-3, 5, 7).  err_state8 (int8) is updated in place; returns codes."""
+    lib = lib or load()
+    grad = np.ascontiguousarray(grad)
+    assert err_state8.dtype == np.int8 and err_state8.flags.c_contiguous and err_state8.size == grad.size
+    n = grad.size
+    codes = np.zeros(code_bytes(n, bits), dtype=np.uint8)
+    args = [_ptr(grad), _grad_dtype(grad), _ptr(err_state8), n, bits, int(log2_s), int(se_mult),
+            float(beta), int(reset), _ptr(codes)]
+    if threads > 1:
+        rc = lib.loco_ref_fixed_compensate_quantize_mt(*args, int(threads))
+    else:
+        rc = lib.loco_ref_fixed_compensate_quantize(*args)
+    if rc:
+        raise ValueError("loco_ref_fixed_compensate_quantize: status %d" % rc)
+    return codes
+
+
+def fixed_dequant_reduce(codes, num_workers, n, bits, log2_s, code_stride_bytes=None, threads=1, lib=None):
+    """Eq. 8 with the global scale; returns float32[n]."""
+    lib = lib or load()
+    codes = np.ascontiguousarray(codes).reshape(-1)
+    assert codes.dtype == np.uint8
+    if code_stride_bytes is None:
+        code_stride_bytes = code_bytes(n, bits)
+    if num_workers >= 1 and n > 0:
+        assert codes.size >= (num_workers - 1) * code_stride_bytes + code_bytes(n, bits)
+    out = np.zeros(n, dtype=np.float32)
+    args = [_ptr(codes), code_stride_bytes, int(num_workers), n, bits, int(log2_s), _ptr(out)]
+    if threads > 1:
+        rc = lib.loco_ref_fixed_dequant_reduce_mt(*args, int(threads))
+    else:
+        rc = lib.loco_ref_fixed_dequant_reduce(*args)
+    if rc:
+        raise ValueError("loco_ref_fixed_dequant_reduce: status %d" % rc)
     return out

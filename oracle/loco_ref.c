@@ -211,3 +211,113 @@ int loco_ref_dequant_reduce(const uint8_t *codes, size_t code_stride_bytes, cons
     return loco_ref_dequant_reduce_range(codes, code_stride_bytes, scales, scale_stride_elems,
                                          num_workers, n, bits, block_size, grad_out, 0, n);
 }
+
+/* ------------------------------------------------------------------------------------
+ * The paper's literal form: one global scale s for the gradient codes and the error
+ * state itself kept as 8-bit codes with scale s_e (Alg. 1 as printed; Eq. 1, 2, 3, 5, 7;
+ * s = 2^19 or 2^17 and s_e = 4s or 6s in Sec. 3.1-3.2).
+ *
+ *   e^   = decompressor(e; s_e) = float(e) / s_e
+ *   h    = g + e^                                              (Eq. 2)
+ *   q    = round_p-bit(h * s), clamped to [-2^(p-1), 2^(p-1)-1] (Eq. 1, 3)
+ *   d    = float(q) / s                                        (Alg. 1 step 2)
+ *   e~'  = (1-beta) e^ + beta (h - d)                          (Eq. 5)
+ *   e'   = 0 on a reset step, else round_8-bit(e~' * s_e)      (Eq. 7)
+ *
+ * Readings: s = 2^log2_s (the paper's values are powers of two, which makes h*s and
+ * q/s exact); s_e = se_mult * s; only the 8-bit e is stored, so the "previous e~" of
+ * Eq. 5 is its decoded value e^; the clamp is applied to the rounded float before the
+ * conversion to an integer; ties to even; binary32 with one rounding per operation.
+ * ---------------------------------------------------------------------------------- */
+static int fixed_args_ok(int bits, int log2_s, int se_mult)
+{
+    return (bits == 4 || bits == 8) && log2_s >= -64 && log2_s <= 64 && se_mult >= 1 && se_mult <= 64;
+}
+
+static float clamp_round(float x, int lo, int hi)
+{
+    float t = rintf(x);
+    if (t > (float)hi)
+        t = (float)hi;
+    if (t < (float)lo)
+        t = (float)lo;
+    return t;
+}
+
+int loco_ref_fixed_compensate_quantize_range(const void *grad, int grad_dtype, int8_t *err_state8,
+                                             size_t n, int bits, int log2_s, int se_mult, float beta,
+                                             int reset, uint8_t *codes_out, size_t elem_lo, size_t elem_hi)
+{
+    if (!fixed_args_ok(bits, log2_s, se_mult) || !(beta >= 0.0f && beta <= 1.0f))
+        return LOCO_REF_BAD_ARG;
+    if (grad_dtype != LOCO_REF_F32 && grad_dtype != LOCO_REF_BF16)
+        return LOCO_REF_BAD_ARG;
+    if (n && (!grad || !err_state8 || !codes_out))
+        return LOCO_REF_BAD_ARG;
+    if (elem_hi > n)
+        elem_hi = n;
+    const int qmax = (1 << (bits - 1)) - 1;
+    const int qmin = -(1 << (bits - 1));
+    const float s = ldexpf(1.0f, log2_s);
+    const float s_e = (float)se_mult * s;
+    const float one_minus_beta = 1.0f - beta;
+    for (size_t i = elem_lo; i < elem_hi; ++i) {
+        float e_hat = (float)err_state8[i] / s_e;            /* decompressor(e; s_e) */
+        float h = grad_at(grad, grad_dtype, i) + e_hat;      /* Eq. 2 */
+        int q = (int)clamp_round(h * s, qmin, qmax);         /* Eq. 1, 3 */
+        float d = (float)q / s;                              /* decompressor(q; s) */
+        float delta = h - d;                                 /* Eq. 4 */
+        float bd = beta * delta;
+        float e_new = fmaf(one_minus_beta, e_hat, bd);       /* Eq. 5 */
+        int e8 = reset ? 0 : (int)clamp_round(e_new * s_e, -128, 127); /* Eq. 7 */
+        err_state8[i] = (int8_t)e8;
+        if (bits == 8) {
+            codes_out[i] = (uint8_t)(int8_t)q;
+        } else if ((i & 1) == 0) {
+            codes_out[i >> 1] = (uint8_t)(q & 15);
+        } else {
+            codes_out[i >> 1] = (uint8_t)(codes_out[i >> 1] | ((q & 15) << 4));
+        }
+    }
+    return LOCO_REF_OK;
+}
+
+int loco_ref_fixed_compensate_quantize(const void *grad, int grad_dtype, int8_t *err_state8, size_t n,
+                                       int bits, int log2_s, int se_mult, float beta, int reset,
+                                       uint8_t *codes_out)
+{
+    return loco_ref_fixed_compensate_quantize_range(grad, grad_dtype, err_state8, n, bits, log2_s,
+                                                    se_mult, beta, reset, codes_out, 0, n);
+}
+
+/* Eq. 8 with the global scale: out = (sum_w float(q^w) / s) * (1/W), in worker order. */
+int loco_ref_fixed_dequant_reduce_range(const uint8_t *codes, size_t code_stride_bytes, int num_workers,
+                                        size_t n, int bits, int log2_s, float *grad_out,
+                                        size_t elem_lo, size_t elem_hi)
+{
+    if (!fixed_args_ok(bits, log2_s, 1) || num_workers < 1)
+        return LOCO_REF_BAD_ARG;
+    if (n && (!codes || !grad_out))
+        return LOCO_REF_BAD_ARG;
+    if (elem_hi > n)
+        elem_hi = n;
+    const float s = ldexpf(1.0f, log2_s);
+    const float inv = 1.0f / (float)num_workers;
+    for (size_t i = elem_lo; i < elem_hi; ++i) {
+        float acc = 0.0f;
+        for (int w = 0; w < num_workers; ++w) {
+            int q = code_at(codes + (size_t)w * code_stride_bytes, bits, i);
+            float d = (float)q / s;
+            acc = acc + d;
+        }
+        grad_out[i] = acc * inv;
+    }
+    return LOCO_REF_OK;
+}
+
+int loco_ref_fixed_dequant_reduce(const uint8_t *codes, size_t code_stride_bytes, int num_workers,
+                                  size_t n, int bits, int log2_s, float *grad_out)
+{
+    return loco_ref_fixed_dequant_reduce_range(codes, code_stride_bytes, num_workers, n, bits, log2_s,
+                                               grad_out, 0, n);
+}

@@ -14,11 +14,17 @@ int loco_ref_compensate_quantize_blocks(const void *, int, float *, size_t, int,
                                         uint8_t *, float *, size_t, size_t);
 int loco_ref_dequant_reduce_range(const uint8_t *, size_t, const float *, size_t, int, size_t, int,
                                   int, float *, size_t, size_t);
+int loco_ref_fixed_compensate_quantize_range(const void *, int, int8_t *, size_t, int, int, int, float,
+                                             int, uint8_t *, size_t, size_t);
+int loco_ref_fixed_dequant_reduce_range(const uint8_t *, size_t, int, size_t, int, int, float *, size_t,
+                                        size_t);
 
 #define LOCO_REF_MAX_THREADS 256
 
 typedef struct {
-    int kind; /* 0 = compensate_quantize, 1 = dequant_reduce */
+    int kind; /* 0 = compensate_quantize, 1 = dequant_reduce, 2 and 3 = their fixed-scale forms */
+    int8_t *err_state8;
+    int log2_s, se_mult;
     const void *grad;
     int grad_dtype;
     float *err_state;
@@ -45,10 +51,17 @@ static void *run_job(void *p)
         j->status = loco_ref_compensate_quantize_blocks(j->grad, j->grad_dtype, j->err_state, j->n,
                                                         j->bits, j->block_size, j->beta, j->reset,
                                                         j->codes_out, j->scales_out, j->lo, j->hi);
-    else
+    else if (j->kind == 1)
         j->status = loco_ref_dequant_reduce_range(j->codes, j->code_stride, j->scales,
                                                   j->scale_stride, j->num_workers, j->n, j->bits,
                                                   j->block_size, j->grad_out, j->lo, j->hi);
+    else if (j->kind == 2)
+        j->status = loco_ref_fixed_compensate_quantize_range(j->grad, j->grad_dtype, j->err_state8, j->n,
+                                                             j->bits, j->log2_s, j->se_mult, j->beta,
+                                                             j->reset, j->codes_out, j->lo, j->hi);
+    else
+        j->status = loco_ref_fixed_dequant_reduce_range(j->codes, j->code_stride, j->num_workers, j->n,
+                                                        j->bits, j->log2_s, j->grad_out, j->lo, j->hi);
     return 0;
 }
 
@@ -126,6 +139,40 @@ int loco_ref_dequant_reduce_mt(const uint8_t *codes, size_t code_stride_bytes, c
     j.n = n;
     j.bits = bits;
     j.block_size = block_size;
+    j.grad_out = grad_out;
+    return run_split(&j, n, 64, threads);
+}
+
+int loco_ref_fixed_compensate_quantize_mt(const void *grad, int grad_dtype, int8_t *err_state8, size_t n,
+                                          int bits, int log2_s, int se_mult, float beta, int reset,
+                                          uint8_t *codes_out, int threads)
+{
+    job_t j = {0};
+    j.kind = 2;
+    j.grad = grad;
+    j.grad_dtype = grad_dtype;
+    j.err_state8 = err_state8;
+    j.n = n;
+    j.bits = bits;
+    j.log2_s = log2_s;
+    j.se_mult = se_mult;
+    j.beta = beta;
+    j.reset = reset;
+    j.codes_out = codes_out;
+    return run_split(&j, n, 64, threads);
+}
+
+int loco_ref_fixed_dequant_reduce_mt(const uint8_t *codes, size_t code_stride_bytes, int num_workers,
+                                     size_t n, int bits, int log2_s, float *grad_out, int threads)
+{
+    job_t j = {0};
+    j.kind = 3;
+    j.codes = codes;
+    j.code_stride = code_stride_bytes;
+    j.num_workers = num_workers;
+    j.n = n;
+    j.bits = bits;
+    j.log2_s = log2_s;
     j.grad_out = grad_out;
     return run_split(&j, n, 64, threads);
 }

@@ -469,3 +469,225 @@ ALL_CHECKS = [
     check_edges,
     check_threads_agree,
 ]
+
+
+# ======================================================================================
+# The paper's literal form: global scale s, 8-bit error state with scale s_e (Alg. 1 as
+# printed; Eq. 1-3, 5, 7, 8).  Oracle: loco_ref_fixed_*.
+# ======================================================================================
+def fcq(lib, g, e8, bits, log2_s, se_mult, beta, reset=0, threads=1):
+    return oracle.fixed_compensate_quantize(g, e8, bits, log2_s, se_mult, beta, reset, threads=threads, lib=lib)
+
+
+def near_tie(x, rel=2.0 ** -21, tiny=1e-30):
+    """x (float64 shadow of a binary32 product) so close to k + 1/2 that binary32 may round it either way."""
+    return np.abs(np.abs(x - np.floor(x)) - 0.5) <= np.abs(x) * rel + tiny
+
+
+def check_fixed_worked_example(lib):
+    """Hand-derived dyadic example of Alg. 1 as printed (Eq. 1-3, 5, 7, 8)."""
+    rows = {}
+    with open(os.path.join(GOLDEN, "worked_example_fixed_scale_p4.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                key, *vals = line.split()
+                rows[key] = vals
+    bits, log2_s, mult, beta = int(rows["bits"][0]), int(rows["log2_s"][0]), int(rows["se_mult"][0]), float(rows["beta"][0])
+    g = np.array([float(v) for v in rows["g"]], np.float32)
+    ints = lambda k: [int(v) for v in rows[k]]
+    e8 = np.zeros(g.size, np.int8)
+    payloads = []
+    for step in (0, 1):
+        codes = fcq(lib, g, e8, bits, log2_s, mult, beta)
+        want = np.array([int(b, 16) for b in rows[f"bytes{step}"]], np.uint8)
+        assert np.array_equal(codes, want), (step, codes, want)
+        assert unpack(codes, g.size, bits).tolist() == ints(f"q{step}")
+        assert e8.tolist() == ints(f"e{step + 1}"), (step, e8)
+        payloads.append(codes)
+    out = oracle.fixed_dequant_reduce(np.concatenate(payloads), 2, g.size, bits, log2_s, lib=lib)
+    assert out.tolist() == [float(v) for v in rows["mean"]]
+
+
+def check_fixed_nearest_levels(lib):
+    """Eq. 1 for the gradient codes and Eq. 7 for the state codes: each is the level of its
+    p-bit range nearest to x*s resp. e~'*s_e (binary64 shadow; near-ties whitelisted), and
+    the compression error obeys Lemma 5: at most 1/(2s) unless the clamp fired."""
+    rng = np.random.default_rng(2024)
+    odd = tot = 0
+    for trial in range(300):
+        bits = (4, 8)[trial & 1]
+        qmin, qmax = qrange(bits)
+        log2_s = int(rng.choice([19, 17, 10, 3]))
+        mult = int(rng.choice([4, 6]))
+        beta = float(rng.choice([0.25, 0.5, 1.0, 0.3, 0.9]))
+        s, se = 2.0 ** log2_s, mult * 2.0 ** log2_s
+        n = int(rng.integers(1, 200))
+        g = (rng.standard_normal(n) * rng.choice([0.3, 1, 3, 30]) * qmax / s).astype(np.float32)
+        e0 = rng.integers(-128, 128, n).astype(np.int8) if trial % 3 else np.zeros(n, np.int8)
+        e8 = e0.copy()
+        codes = fcq(lib, g, e8, bits, log2_s, mult, beta)
+        q = unpack(codes, n, bits)
+        e_hat = e0.astype(np.float64) / se
+        h = g.astype(np.float64) + e_hat
+        x = h * s
+        want_q = np.clip(np.rint(x), qmin, qmax)
+        bad = (q != want_q) & ~near_tie(x)
+        assert not bad.any(), (trial, x[bad], q[bad])
+        assert np.all(np.abs(q - np.clip(x, qmin, qmax)) <= 0.5 + np.abs(x) * 2.0 ** -21)
+        unsat = np.abs(x) <= qmax + 0.5
+        d = q / s
+        assert np.all(np.abs(h - d)[unsat] <= (0.5 + np.abs(x[unsat]) * 2.0 ** -21) / s)      # Lemma 5
+        sat = ~unsat & (np.abs(x) > qmax + 1)
+        assert np.all(q[sat & (x > 0)] == qmax) and np.all(q[sat & (x < 0)] == qmin)
+        b32 = np.float64(np.float32(beta))
+        e_new = (1.0 - b32) * e_hat + b32 * (h - d)                                              # Eq. 5
+        y = e_new * se
+        want_e = np.clip(np.rint(y), -128, 127)
+        # the binary32 rounding of e~' moves y by up to |y| 2^-22: near-ties may go either way
+        bad_e = (e8 != want_e) & ~near_tie(y, rel=2.0 ** -20)
+        assert not bad_e.any(), (trial, y[bad_e], e8[bad_e])
+        odd += int(((q != want_q) | (e8 != want_e)).sum())
+        tot += 2 * n
+    assert odd <= 2e-3 * tot
+
+
+def check_fixed_zero_error_fixed_point(lib):
+    """g = m/s with integer m in range: q = m, delta = 0, the state stays 0 (Eq. 1, 5)."""
+    rng = np.random.default_rng(31)
+    for bits, log2_s, mult in ((4, 19, 4), (4, 17, 6), (8, 19, 6)):
+        qmin, qmax = qrange(bits)
+        n = 1001
+        e8 = np.zeros(n, np.int8)
+        for _ in range(3):
+            m = rng.integers(qmin, qmax + 1, n)
+            g = (m * 2.0 ** -log2_s).astype(np.float32)
+            codes = fcq(lib, g, e8, bits, log2_s, mult, 0.25)
+            assert np.array_equal(unpack(codes, n, bits), m)
+            assert not e8.any()
+            assert np.array_equal(oracle.fixed_dequant_reduce(codes, 1, n, bits, log2_s, lib=lib), g)
+
+
+def check_fixed_telescoping(lib):
+    """Lemma 1 with the compressed state: d_k = g_k + (e^_k - e~_{k+1})/beta, so summed over K
+    steps |sum d - sum g + e^_K/beta| <= K/(2 s_e beta): only the state's own rounding is left."""
+    rng = np.random.default_rng(47)
+    for bits, log2_s, mult, beta, K in ((4, 19, 4, 0.5, 12), (4, 17, 6, 0.25, 20), (8, 19, 6, 1.0, 8)):
+        qmin, qmax = qrange(bits)
+        s, se = 2.0 ** log2_s, mult * 2.0 ** log2_s
+        n = 4000
+        e8 = np.zeros(n, np.int8)
+        sum_d, sum_g = np.zeros(n), np.zeros(n)
+        for _ in range(K):
+            g = (rng.uniform(-(qmax - 1), qmax - 1, n) / s).astype(np.float32)   # never clamps
+            codes = fcq(lib, g, e8, bits, log2_s, mult, beta)
+            sum_d += unpack(codes, n, bits) / s
+            sum_g += g
+        assert np.abs(e8).max() < 127
+        resid = np.abs(sum_d - sum_g + (e8 / se) / beta)
+        assert resid.max() <= K / (2 * se * beta) * (1 + 1e-3)
+        # and the uncompensated error of one step, 1/(2s), would have added up to far more
+        assert np.abs(sum_d - sum_g).max() <= (0.5 / s + 0.5 / se) / beta + K / (2 * se * beta)
+
+
+def check_fixed_beta_and_reset(lib):
+    """beta = 0: re-compressing the decoded state gives the same codes back (the state is
+    constant); beta = 1: e' = compressor(h - d; s_e); reset (Eq. 7): same payload, state 0."""
+    rng = np.random.default_rng(53)
+    bits, log2_s = 4, 19
+    s = 2.0 ** log2_s
+    n = 3001
+    g = (rng.standard_normal(n) * 5 / s).astype(np.float32)
+    for mult in (4, 6):
+        e0 = rng.integers(-128, 128, n).astype(np.int8)
+        e8 = e0.copy()
+        c0 = fcq(lib, g, e8, bits, log2_s, mult, 0.0)
+        assert np.array_equal(e8, e0)
+        ea, eb = e0.copy(), e0.copy()
+        ca = fcq(lib, g, ea, bits, log2_s, mult, 0.25, reset=0)
+        cb = fcq(lib, g, eb, bits, log2_s, mult, 0.25, reset=1)
+        assert np.array_equal(ca, cb) and np.array_equal(ca, c0) and ea.any() and not eb.any()
+        e1 = e0.copy()
+        c1 = fcq(lib, g, e1, bits, log2_s, mult, 1.0)
+        h = g.astype(np.float64) + e0 / (mult * s)
+        y = (h - unpack(c1, n, bits) / s) * mult * s
+        ok = (e1 == np.clip(np.rint(y), -128, 127)) | near_tie(y, rel=2.0 ** -20)
+        assert ok.all()
+
+
+def check_fixed_matches_block_form(lib):
+    """With a zero state and every block's largest |g| equal to qmax/s, the block-scaled
+    compressor has scale s exactly, so both forms of Eq. 1 must emit the same codes."""
+    rng = np.random.default_rng(59)
+    for bits, log2_s, B in ((4, 19, 256), (8, 17, 64)):
+        qmin, qmax = qrange(bits)
+        s = 2.0 ** log2_s
+        n = 20 * B
+        g = (rng.uniform(-qmax, qmax, n) / s).astype(np.float32)
+        g[np.arange(0, n, B) + rng.integers(0, B, n // B)] = np.float32(qmax / s)
+        c_fixed = fcq(lib, g, np.zeros(n, np.int8), bits, log2_s, 4, 0.25)
+        c_block, scales = cq(lib, g, np.zeros(n, np.float32), bits, B, 0.25)
+        assert np.all(scales == np.float32(1.0 / s))
+        assert np.array_equal(c_fixed, c_block)
+
+
+def check_fixed_dequant_reduce(lib):
+    """Eq. 8 with the global scale: every partial sum is an integer over s, hence exact, and
+    the result is (sum q) / s times fl(1/N) with one rounding."""
+    rng = np.random.default_rng(61)
+    for bits, log2_s in ((4, 19), (8, 17)):
+        n = 2001
+        cb = oracle.code_bytes(n, bits)
+        stride = cb + 7
+        for W in (1, 2, 3, 8, 16, 17):
+            codes = rng.integers(0, 256, W * stride, dtype=np.uint8)
+            out = oracle.fixed_dequant_reduce(codes, W, n, bits, log2_s, code_stride_bytes=stride, lib=lib)
+            tot = np.zeros(n)
+            for w in range(W):
+                tot += unpack(codes[w * stride:w * stride + cb], n, bits)
+            d_sum = (tot * 2.0 ** -log2_s).astype(np.float32)          # exact: |sum q| < 2^24
+            assert np.array_equal(out, d_sum * (np.float32(1.0) / np.float32(W)))
+            ref = tot * 2.0 ** -log2_s / W
+            if W in (1, 2, 8, 16):                                      # 1/W exact too
+                assert np.array_equal(out, ref.astype(np.float32))
+            else:
+                assert np.all(np.abs(out - ref) <= np.abs(ref) * 2.0 ** -22)
+        assert np.abs(tot).max() > 0
+
+
+def check_fixed_edges(lib):
+    """bf16 widening, empty input, odd length (last high nibble 0), threads agree, the state
+    saturates at +-127/-128 instead of wrapping."""
+    rng = np.random.default_rng(67)
+    assert fcq(lib, np.zeros(0, np.float32), np.zeros(0, np.int8), 4, 19, 4, 0.25).size == 0
+    n = 777
+    s = 2.0 ** 19
+    gb = to_bf16_bits((rng.standard_normal(n) * 4 / s).astype(np.float32))
+    e0 = rng.integers(-128, 128, n).astype(np.int8)
+    ea, eb, ec = e0.copy(), e0.copy(), e0.copy()
+    ca = fcq(lib, gb, ea, 4, 19, 6, 0.25)
+    cb = fcq(lib, bf16_bits_to_f32(gb), eb, 4, 19, 6, 0.25)
+    cc = fcq(lib, gb, ec, 4, 19, 6, 0.25, threads=4)
+    assert np.array_equal(ca, cb) and np.array_equal(ea, eb) and np.array_equal(ca, cc) and np.array_equal(ea, ec)
+    assert ca.size == (n + 1) // 2 and (ca[-1] >> 4) == 0
+    big = np.full(8, 1.0, np.float32)
+    big[4:] = -1.0
+    e8 = np.zeros(8, np.int8)
+    c = fcq(lib, big, e8, 4, 19, 4, 1.0)
+    assert unpack(c, 8, 4).tolist() == [7] * 4 + [-8] * 4 and e8.tolist() == [127] * 4 + [-128] * 4
+    o1 = oracle.fixed_dequant_reduce(np.tile(ca, 3), 3, n, 4, 19, lib=lib)
+    o4 = oracle.fixed_dequant_reduce(np.tile(ca, 3), 3, n, 4, 19, threads=4, lib=lib)
+    assert np.array_equal(o1, o4)
+
+
+FIXED_CHECKS = [
+    check_fixed_worked_example,
+    check_fixed_nearest_levels,
+    check_fixed_zero_error_fixed_point,
+    check_fixed_telescoping,
+    check_fixed_beta_and_reset,
+    check_fixed_matches_block_form,
+    check_fixed_dequant_reduce,
+    check_fixed_edges,
+]
+ALL_CHECKS = ALL_CHECKS + FIXED_CHECKS

@@ -13,7 +13,7 @@ import pins
 SRC = os.path.join(os.path.dirname(oracle.__file__), "loco_ref.c")
 MT = os.path.join(os.path.dirname(oracle.__file__), "loco_ref_mt.c")
 
-# (name, text in loco_ref.c, replacement)
+# (name, text in loco_ref.c, replacement[, which occurrence: 0 = block-scaled form, 1 = fixed-scale form])
 MUTANTS = [
     ("compensation_sign", "grad_at(grad, grad_dtype, i) + e; /* Eq. 2 */", "grad_at(grad, grad_dtype, i) - e;"),
     ("error_sign", "float delta = h - d;", "float delta = d - h;"),
@@ -37,15 +37,41 @@ MUTANTS = [
      "float h = grad_at(grad, grad_dtype, i);"),
     ("decode_with_reciprocal", "float d = (float)q * D;   /* decompressor, Eq. 1 */",
      "float d = (float)q * r;"),
+    # the paper's literal form (global scale, 8-bit state)
+    ("fixed_ema_not_weighted", "float bd = beta * delta;", "float bd = delta;", 1),
+    ("fixed_error_sign", "float delta = h - d;", "float delta = d - h;", 1),
+    ("fixed_state_not_decoded", "float e_hat = (float)err_state8[i] / s_e;", "float e_hat = (float)err_state8[i];"),
+    ("fixed_state_scale_is_s", "const float s_e = (float)se_mult * s;", "const float s_e = s;"),
+    ("fixed_ema_weights_swapped", "fmaf(one_minus_beta, e_hat, bd)", "fmaf(beta, e_hat, one_minus_beta * delta)"),
+    ("fixed_ema_history_dropped", "fmaf(one_minus_beta, e_hat, bd)", "bd"),
+    ("fixed_state_not_rescaled", "clamp_round(e_new * s_e, -128, 127)", "clamp_round(e_new, -128, 127)"),
+    ("fixed_state_wraps", "(int)clamp_round(e_new * s_e, -128, 127)", "(int)(int8_t)(int)rintf(e_new * s_e)"),
+    ("fixed_no_clamp_low", "if (t < (float)lo)", "if (0)"),
+    ("fixed_truncates", "float t = rintf(x);", "float t = truncf(x);"),
+    ("fixed_compensation_dropped", "grad_at(grad, grad_dtype, i) + e_hat;", "grad_at(grad, grad_dtype, i);"),
+    ("fixed_decode_scale", "float d = (float)q / s;                              /* decompressor(q; s) */",
+     "float d = (float)q / s_e;"),
+    ("fixed_reset_ignored", "int e8 = reset ? 0 :", "int e8 = 0 ? 0 :"),
+    ("fixed_reduce_no_average", "grad_out[i] = acc * inv;", "grad_out[i] = acc;", 1),
+    ("fixed_reduce_stride", "int q = code_at(codes + (size_t)w * code_stride_bytes, bits, i);\n            float d = (float)q / s;",
+     "int q = code_at(codes, bits, i);\n            float d = (float)q / s;"),
 ]
 
 
-@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
-def test_planted_mistake_is_caught(tmp_path, name, old, new):
+def plant(text, old, new, which):
+    parts = text.split(old)
+    assert len(parts) - 1 > which, "mutation site not found"
+    return old.join(parts[:which + 1]) + new + old.join(parts[which + 1:])
+
+
+@pytest.mark.parametrize("mutant", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(tmp_path, mutant):
+    name, old, new = mutant[:3]
+    which = mutant[3] if len(mutant) > 3 else 0
     text = open(SRC).read()
-    assert text.count(old) == 1, f"mutation site for {name} not unique"
+    assert text.count(old) > which, f"mutation site for {name} not found"
     src = tmp_path / "loco_ref.c"
-    src.write_text(text.replace(old, new))
+    src.write_text(plant(text, old, new, which))
     shutil.copy(MT, tmp_path / "loco_ref_mt.c")
     so = oracle.build(force=True, out=str(tmp_path / "libmutant.so"),
                       srcs=[str(src), str(tmp_path / "loco_ref_mt.c")], extra_flags=["-w"])
