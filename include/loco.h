@@ -118,6 +118,49 @@ loco_status_t loco_dequant_reduce(const uint8_t *codes, size_t code_stride_bytes
                                   int num_workers, size_t n, int bits, int block_size,
                                   float *grad_out, void *stream);
 
+/* ------------------------------------------------------------------------------------
+ * Algorithm 1 exactly as printed: one global scale s for the gradient codes and the error
+ * state itself kept as 8-bit codes (Eq. 1-3, 5, 7; s = 2^19 or 2^17, s_e = 4s or 6s in
+ * Sec. 3.1-3.2).  No scales array; 4.5 bytes per element with a bf16 gradient and p = 4.
+ *   s   = 2^log2_s, -64 <= log2_s <= 64 (the paper's values are powers of two)
+ *   s_e = se_mult * s, 1 <= se_mult <= 64
+ * Same conventions as above (device pointers, caller-owned buffers, stream order, status).
+ * ---------------------------------------------------------------------------------- */
+
+/* 1 when step k is a reset step of Eq. 7 (k % reset_period == 0, reset_period > 0), else 0. */
+int loco_reset_due(long long step_index, long long reset_period);
+
+/* e_0 = 0 for the 8-bit error state.  err_state8: [n] int8 device, 16-byte aligned. */
+loco_status_t loco_error_state8_init(int8_t *err_state8, size_t n, void *stream);
+
+/*
+ * Algorithm 1, steps 1 and 2 with the global scale:
+ *   e^  = decompressor(e; s_e) = float(e) / s_e
+ *   h   = g + e^                                        (Eq. 2)
+ *   q   = round_p-bit(h * s), clamped to the p-bit range (Eq. 1, 3), packed as above
+ *   d   = float(q) / s
+ *   e~' = (1-beta) e^ + beta (h - d)                     (Eq. 5 on the decoded state)
+ *   e'  = round_8-bit(e~' * s_e), or 0 when reset != 0   (Eq. 7)
+ *
+ *   grad         [n] device, LOCO_F32 or LOCO_BF16, read only, 16-byte aligned
+ *   err_state8   [n] int8 device, read and overwritten in place, 16-byte aligned
+ *   bits         4 or 8
+ *   codes_out    [loco_code_bytes(n, bits)] device, 16-byte aligned
+ */
+loco_status_t loco_compensate_quantize_fixed(const void *grad, loco_dtype_t grad_dtype,
+                                             int8_t *err_state8, size_t n, int bits, int log2_s,
+                                             int se_mult, float beta, int reset, uint8_t *codes_out,
+                                             void *stream);
+
+/*
+ * Algorithm 1, step 3 / Eq. 8 with the global scale:
+ *   out_i = (sum_{w=0}^{W-1} float(q^w_i) / s) * (1/W)
+ * Payload w is at codes + w*code_stride_bytes (a multiple of 16, >= loco_code_bytes(n, bits);
+ * ignored when W == 1).  grad_out: [n] fp32 device, 16-byte aligned.
+ */
+loco_status_t loco_dequant_reduce_fixed(const uint8_t *codes, size_t code_stride_bytes, int num_workers,
+                                        size_t n, int bits, int log2_s, float *grad_out, void *stream);
+
 /*
  * Measurement aid, not part of the method: dst[i] = src[i] for `bytes` bytes
  * (a multiple of 16, both pointers 16-byte aligned) with the same load/store

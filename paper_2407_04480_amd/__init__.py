@@ -13,6 +13,10 @@ from .binding import (  # noqa: F401
     loco_error_state_init,
     loco_compensate_quantize,
     loco_dequant_reduce,
+    loco_reset_due,
+    loco_error_state8_init,
+    loco_compensate_quantize_fixed,
+    loco_dequant_reduce_fixed,
 )
 
 __all__ = [
@@ -23,4 +27,8 @@ __all__ = [
     "loco_error_state_init",
     "loco_compensate_quantize",
     "loco_dequant_reduce",
+    "loco_reset_due",
+    "loco_error_state8_init",
+    "loco_compensate_quantize_fixed",
+    "loco_dequant_reduce_fixed",
 ]

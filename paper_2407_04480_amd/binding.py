@@ -29,6 +29,10 @@ EXPORTS = (
     "loco_compensate_quantize",
     "loco_dequant_reduce",
     "loco_stream_copy",
+    "loco_reset_due",
+    "loco_error_state8_init",
+    "loco_compensate_quantize_fixed",
+    "loco_dequant_reduce_fixed",
 )
 
 _lib = None
@@ -66,6 +70,12 @@ def load_library(path: Optional[str] = None):
     lib.loco_dequant_reduce.argtypes = [vp, sz, vp, sz, i, sz, i, i, vp, vp]
     lib.loco_dequant_reduce.restype = i
     lib.loco_stream_copy.argtypes, lib.loco_stream_copy.restype = [vp, vp, sz, vp], i
+    lib.loco_reset_due.argtypes, lib.loco_reset_due.restype = [c.c_longlong, c.c_longlong], i
+    lib.loco_error_state8_init.argtypes, lib.loco_error_state8_init.restype = [vp, sz, vp], i
+    lib.loco_compensate_quantize_fixed.argtypes = [vp, i, vp, sz, i, i, i, f, i, vp, vp]
+    lib.loco_compensate_quantize_fixed.restype = i
+    lib.loco_dequant_reduce_fixed.argtypes = [vp, sz, i, sz, i, i, vp, vp]
+    lib.loco_dequant_reduce_fixed.restype = i
     if path is None:
         _lib = lib
     return lib
@@ -172,3 +182,57 @@ def loco_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
         raise ValueError("dst too small")
     st = lib.loco_stream_copy(_dev_ptr(dst, "dst"), _dev_ptr(src, "src"), nbytes, _stream_handle(stream))
     _check("loco_stream_copy", st)
+
+
+def loco_reset_due(step_index: int, reset_period: int) -> bool:
+    """Eq. 7 of arXiv 2407.04480: is step k a reset step (k % T_c == 0)?"""
+    return bool(load_library().loco_reset_due(int(step_index), int(reset_period)))
+
+
+def loco_error_state8_init(err_state8: torch.Tensor, stream=None) -> None:
+    """e_0 = 0 for the 8-bit error state of Algorithm 1 as printed."""
+    lib = load_library()
+    p = _dev_ptr(err_state8, "err_state8", torch.int8)
+    _check("loco_error_state8_init", lib.loco_error_state8_init(p, err_state8.numel(), _stream_handle(stream)))
+
+
+def loco_compensate_quantize_fixed(grad: torch.Tensor, err_state8: torch.Tensor, bits: int, log2_s: int,
+                                   se_mult: int, beta: float, reset: bool, codes_out: torch.Tensor,
+                                   stream=None) -> None:
+    """Algorithm 1 steps 1-2 with the global scale s = 2^log2_s and the 8-bit error state
+    (scale se_mult * s), Eq. 1-3, 5, 7: err_state8 (int8) is updated in place."""
+    lib = load_library()
+    if grad.dtype == torch.float32:
+        gd = LOCO_F32
+    elif grad.dtype == torch.bfloat16:
+        gd = LOCO_BF16
+    else:
+        raise TypeError(f"grad must be float32 or bfloat16, got {grad.dtype}")
+    n = grad.numel()
+    pg = _dev_ptr(grad, "grad")
+    pe = _dev_ptr(err_state8, "err_state8", torch.int8)
+    pc = _dev_ptr(codes_out, "codes_out", torch.uint8)
+    if err_state8.numel() != n:
+        raise ValueError("err_state8 must have as many elements as grad")
+    if bits in (4, 8) and codes_out.numel() < (n * bits + 7) // 8:
+        raise ValueError("codes_out too small")
+    st = lib.loco_compensate_quantize_fixed(pg, gd, pe, n, int(bits), int(log2_s), int(se_mult), float(beta),
+                                            1 if reset else 0, pc, _stream_handle(stream))
+    _check("loco_compensate_quantize_fixed", st)
+
+
+def loco_dequant_reduce_fixed(codes: torch.Tensor, code_stride_bytes: int, num_workers: int, n: int, bits: int,
+                              log2_s: int, grad_out: torch.Tensor, stream=None) -> None:
+    """Algorithm 1 step 3 / Eq. 8 with the global scale."""
+    lib = load_library()
+    pc = _dev_ptr(codes, "codes", torch.uint8)
+    po = _dev_ptr(grad_out, "grad_out", torch.float32)
+    if grad_out.numel() < n:
+        raise ValueError("grad_out too small")
+    if bits in (4, 8) and num_workers >= 1 and n > 0:
+        cs = code_stride_bytes if num_workers > 1 else 0
+        if codes.numel() < (num_workers - 1) * cs + (n * bits + 7) // 8:
+            raise ValueError("codes too small for num_workers payloads at this stride")
+    st = lib.loco_dequant_reduce_fixed(pc, int(code_stride_bytes), int(num_workers), int(n), int(bits),
+                                       int(log2_s), po, _stream_handle(stream))
+    _check("loco_dequant_reduce_fixed", st)

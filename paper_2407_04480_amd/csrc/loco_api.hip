@@ -3,6 +3,7 @@
 // no synchronisation, no CPU fallback: without a GPU every compute call fails.
 #include "loco.h"
 #include "loco_kernels.h"
+#include "loco_fixed_kernels.h"
 
 #include <atomic>
 #include <cmath>
@@ -112,6 +113,33 @@ bool dispatch_dr_block(int block, unsigned grid, hipStream_t s, const uint8_t* c
         case 256: launch_dr<BITS, 256>(grid, s, codes, cs, scales, ss, W, n, out); return true;
         case 512: launch_dr<BITS, 512>(grid, s, codes, cs, scales, ss, W, n, out); return true;
         default: return false;
+    }
+}
+
+// Launch shapes of the fixed-scale kernels (units of 512 elements per wavefront).
+struct FixedCqShape { static constexpr int kUnits = 2, kThreads = 128; };
+struct FixedDrShape { static constexpr int kSlots = 2, kThreads = 128, kInFlight = 4; };
+
+bool fixed_args_ok(int bits, int log2_s, int se_mult) {
+    return (bits == 4 || bits == 8) && log2_s >= -64 && log2_s <= 64 && se_mult >= 1 && se_mult <= 64;
+}
+
+template <typename G, int BITS, bool POW2>
+void launch_fixed_cq(unsigned grid, hipStream_t s, const void* grad, int8_t* err8, size_t n,
+                     const FixedScales& k, int reset, uint8_t* codes) {
+    fixed_cq_kernel<G, BITS, POW2, FixedCqShape::kUnits, FixedCqShape::kThreads, kNonTemporal>
+        <<<dim3(grid), dim3(FixedCqShape::kThreads), 0, s>>>(grad, err8, n, k, reset, codes);
+}
+
+template <typename G>
+void dispatch_fixed_cq(int bits, bool pow2, unsigned grid, hipStream_t s, const void* grad, int8_t* err8,
+                       size_t n, const FixedScales& k, int reset, uint8_t* codes) {
+    if (bits == 4) {
+        if (pow2) launch_fixed_cq<G, 4, true>(grid, s, grad, err8, n, k, reset, codes);
+        else launch_fixed_cq<G, 4, false>(grid, s, grad, err8, n, k, reset, codes);
+    } else {
+        if (pow2) launch_fixed_cq<G, 8, true>(grid, s, grad, err8, n, k, reset, codes);
+        else launch_fixed_cq<G, 8, false>(grid, s, grad, err8, n, k, reset, codes);
     }
 }
 
@@ -236,6 +264,86 @@ loco_status_t loco_stream_copy(void* dst, const void* src, size_t bytes, void* s
     if (loco_status_t st = grid_for(n16, (size_t)kCopyThreads * kCopySlots, &grid)) return st;
     copy_kernel<kCopySlots, kCopyThreads, kNonTemporal><<<dim3(grid), dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream)>>>(
         static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n16);
+    return launched();
+}
+
+int loco_reset_due(long long step_index, long long reset_period) {
+    return reset_period > 0 && step_index % reset_period == 0;
+}
+
+loco_status_t loco_error_state8_init(int8_t* err_state8, size_t n, void* stream) {
+    if (n == 0) return LOCO_OK;
+    if (!err_state8) return LOCO_ERR_INVALID_ARG;
+    if (!aligned(err_state8, 16)) return LOCO_ERR_ALIGNMENT;
+    if (loco_status_t st = check_device_range(err_state8, n)) return st;
+    unsigned grid;
+    if (loco_status_t st = grid_for(n, (size_t)kCopyThreads * 16 * kCopySlots, &grid)) return st;
+    fill_zero_bytes_kernel<kCopySlots, kCopyThreads, kNonTemporal>
+        <<<dim3(grid), dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream)>>>(
+            reinterpret_cast<uint8_t*>(err_state8), n);
+    return launched();
+}
+
+loco_status_t loco_compensate_quantize_fixed(const void* grad, loco_dtype_t grad_dtype, int8_t* err_state8,
+                                             size_t n, int bits, int log2_s, int se_mult, float beta,
+                                             int reset, uint8_t* codes_out, void* stream) {
+    if (!fixed_args_ok(bits, log2_s, se_mult)) return LOCO_ERR_UNSUPPORTED;
+    if (grad_dtype != LOCO_F32 && grad_dtype != LOCO_BF16) return LOCO_ERR_UNSUPPORTED;
+    if (!(beta >= 0.0f && beta <= 1.0f)) return LOCO_ERR_INVALID_ARG;
+    if (n == 0) return LOCO_OK;
+    if (!grad || !err_state8 || !codes_out) return LOCO_ERR_INVALID_ARG;
+    if (!aligned(grad, 16) || !aligned(err_state8, 16) || !aligned(codes_out, 16)) return LOCO_ERR_ALIGNMENT;
+    const size_t gsz = grad_dtype == LOCO_BF16 ? 2 : 4;
+    if (loco_status_t st = check_device_range(grad, n * gsz)) return st;
+    if (loco_status_t st = check_device_range(err_state8, n)) return st;
+    if (loco_status_t st = check_device_range(codes_out, loco_code_bytes(n, bits))) return st;
+    unsigned grid;
+    if (loco_status_t st = grid_for(n, (size_t)kUnit * FixedCqShape::kUnits * (FixedCqShape::kThreads / kWave), &grid))
+        return st;
+    FixedScales k;
+    k.s = std::ldexp(1.0f, log2_s);
+    k.inv_s = std::ldexp(1.0f, -log2_s);
+    k.s_e = (float)se_mult * k.s;
+    k.inv_se = 1.0f / k.s_e;
+    k.beta = beta;
+    k.one_minus_beta = 1.0f - beta;
+    const bool pow2 = (se_mult & (se_mult - 1)) == 0;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (grad_dtype == LOCO_BF16) dispatch_fixed_cq<bf16_t>(bits, pow2, grid, s, grad, err_state8, n, k, reset, codes_out);
+    else dispatch_fixed_cq<float>(bits, pow2, grid, s, grad, err_state8, n, k, reset, codes_out);
+    return launched();
+}
+
+loco_status_t loco_dequant_reduce_fixed(const uint8_t* codes, size_t code_stride_bytes, int num_workers,
+                                        size_t n, int bits, int log2_s, float* grad_out, void* stream) {
+    if (!fixed_args_ok(bits, log2_s, 1)) return LOCO_ERR_UNSUPPORTED;
+    if (num_workers < 1) return LOCO_ERR_INVALID_ARG;
+    if (n == 0) return LOCO_OK;
+    if (!codes || !grad_out) return LOCO_ERR_INVALID_ARG;
+    const size_t cb = loco_code_bytes(n, bits);
+    const size_t W = (size_t)num_workers;
+    if (W == 1) {
+        code_stride_bytes = 0;
+    } else {
+        if (code_stride_bytes < cb) return LOCO_ERR_INVALID_ARG;
+        if (code_stride_bytes % 16 != 0) return LOCO_ERR_ALIGNMENT;
+    }
+    if (!aligned(codes, 16) || !aligned(grad_out, 16)) return LOCO_ERR_ALIGNMENT;
+    if (loco_status_t st = check_device_range(codes, (W - 1) * code_stride_bytes + cb)) return st;
+    if (loco_status_t st = check_device_range(grad_out, n * sizeof(float))) return st;
+    unsigned grid;
+    if (loco_status_t st = grid_for(n, (size_t)kSlot * FixedDrShape::kSlots * (FixedDrShape::kThreads / kWave), &grid))
+        return st;
+    const float inv_s = std::ldexp(1.0f, -log2_s), inv_w = 1.0f / (float)num_workers;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (bits == 4)
+        fixed_dr_kernel<4, FixedDrShape::kSlots, FixedDrShape::kThreads, FixedDrShape::kInFlight, kNonTemporal>
+            <<<dim3(grid), dim3(FixedDrShape::kThreads), 0, s>>>(codes, code_stride_bytes, num_workers, n, inv_s,
+                                                                  inv_w, grad_out);
+    else
+        fixed_dr_kernel<8, FixedDrShape::kSlots, FixedDrShape::kThreads, FixedDrShape::kInFlight, kNonTemporal>
+            <<<dim3(grid), dim3(FixedDrShape::kThreads), 0, s>>>(codes, code_stride_bytes, num_workers, n, inv_s,
+                                                                  inv_w, grad_out);
     return launched();
 }
 
