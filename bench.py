@@ -46,15 +46,20 @@ def parse_args():
     ap.add_argument("--workload", default="llama7b_shard_4bit_b256")
     ap.add_argument("--cpu-sample", type=int, default=1 << 30,
                     help="elements of the workload the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--form", choices=["block", "fixed"], default="block",
+                    help="block: per-block scales, fp32 error state (the headline path); fixed: Algorithm 1 as "
+                         "printed, global scale s = 2^19 and 8-bit error state with s_e = 4s")
     ap.add_argument("--no-copy-ceiling", action="store_true")
     return ap.parse_args()
 
 
-def cpu_baseline(w, grads, recv_codes, cstride, recv_scales, nb_full, sample, bytes_cq, bytes_dr):
-    """Time the oracle (as it stands) on the first `sample` elements of the workload and
-    check the GPU's payload of those elements against it."""
+FIXED_LOG2_S, FIXED_SE_MULT = 19, 4   # the paper's s = 2^19 and s_e = 4s (Sec. 3.1, 3.2)
+
+
+def cpu_baseline(form, w, grads, recv_codes, cstride, recv_scales, nb_full, sample, bytes_cq, bytes_dr):
+    """Time the oracle (as it stands) on the first `sample` elements of the workload: one
+    compensate-quantize step from a zero state, then the reduce over the W resident payloads."""
     import numpy as np
-    import torch
 
     import oracle
     from paper_2407_04480_amd import workloads
@@ -70,18 +75,25 @@ def cpu_baseline(w, grads, recv_codes, cstride, recv_scales, nb_full, sample, by
     scales = np.empty((W, nb), np.float32)
     for k in range(W):
         codes[k] = recv_codes[k * cstride:k * cstride + cb].cpu().numpy()
-        scales[k] = recv_scales[k * nb_full:k * nb_full + nb].cpu().numpy()
+        if form == "block":
+            scales[k] = recv_scales[k * nb_full:k * nb_full + nb].cpu().numpy()
 
     def run(threads):
-        e = np.zeros(ns, np.float32)
         t0 = time.perf_counter()
-        c, s = oracle.compensate_quantize(g_host, e, bits, B, w.beta, 0, threads=threads)
+        if form == "block":
+            oracle.compensate_quantize(g_host, np.zeros(ns, np.float32), bits, B, w.beta, 0, threads=threads)
+        else:
+            oracle.fixed_compensate_quantize(g_host, np.zeros(ns, np.int8), bits, FIXED_LOG2_S, FIXED_SE_MULT,
+                                             w.beta, 0, threads=threads)
         t1 = time.perf_counter()
-        out = oracle.dequant_reduce(codes, scales, W, ns, bits, B, cb, nb, threads=threads)
+        if form == "block":
+            oracle.dequant_reduce(codes, scales, W, ns, bits, B, cb, nb, threads=threads)
+        else:
+            oracle.fixed_dequant_reduce(codes, W, ns, bits, FIXED_LOG2_S, code_stride_bytes=cb, threads=threads)
         t2 = time.perf_counter()
-        return t1 - t0, t2 - t1, c, s, out
+        return t1 - t0, t2 - t1
 
-    cq1, dr1, _, _, _ = run(1)
+    cq1, dr1 = run(1)
     best = None
     for _ in range(3):
         r = run(cores)
@@ -112,7 +124,8 @@ def main():
 
     import torch
 
-    from paper_2407_04480_amd import (loco_code_bytes, loco_compensate_quantize, loco_dequant_reduce,
+    from paper_2407_04480_amd import (loco_code_bytes, loco_compensate_quantize, loco_compensate_quantize_fixed,
+                                      loco_dequant_reduce, loco_dequant_reduce_fixed, loco_error_state8_init,
                                       loco_error_state_init, loco_num_blocks, workloads)
     from paper_2407_04480_amd.binding import loco_stream_copy
 
@@ -123,38 +136,63 @@ def main():
     torch.cuda.set_device(dev)
     w = workloads.by_name(args.workload)
     n, bits, B, W = w.n, w.bits, w.block_size, w.num_workers
-    bytes_cq, bytes_dr = workloads.algorithmic_bytes(w)
+    form = args.form
+    gsz = 2 if w.grad_dtype == torch.bfloat16 else 4
+    if form == "block":
+        bytes_cq, bytes_dr = workloads.algorithmic_bytes(w)
+        names = ("loco_compensate_quantize", "loco_dequant_reduce")
+    else:  # gradient + 8-bit state in and out + codes; W payloads of codes + fp32 out
+        bytes_cq, bytes_dr = gsz + 1 + 1 + bits / 8.0, W * bits / 8.0 + 4
+        names = ("loco_compensate_quantize_fixed", "loco_dequant_reduce_fixed")
 
     # ---- resident inputs: two own gradients (used alternately), W-1 peers' payloads ----
     grads = [workloads.gradient(w, s, device=dev) for s in range(2)]
-    err = torch.empty(n, dtype=torch.float32, device=dev)
-    loco_error_state_init(err)
     cb, nb = loco_code_bytes(n, bits), loco_num_blocks(n, B)
     cstride = (cb + 15) // 16 * 16
     recv_codes = torch.zeros(W * cstride, dtype=torch.uint8, device=dev)
     recv_scales = torch.zeros(W * nb, dtype=torch.float32, device=dev)
-    tmp_err = torch.empty(n, dtype=torch.float32, device=dev)
+    own_codes, own_scales = recv_codes[:cb], recv_scales[:nb]
+    out = torch.empty(n, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    if form == "block":
+        def state_init(e):
+            loco_error_state_init(e, stream)
+
+        def cq(g, e, codes, scales):
+            loco_compensate_quantize(g, e, bits, B, w.beta, False, codes, scales, stream)
+
+        def dr():
+            loco_dequant_reduce(recv_codes, cstride, recv_scales, nb, W, n, bits, B, out, stream)
+        err = torch.empty(n, dtype=torch.float32, device=dev)
+    else:
+        def state_init(e):
+            loco_error_state8_init(e, stream)
+
+        def cq(g, e, codes, scales):
+            loco_compensate_quantize_fixed(g, e, bits, FIXED_LOG2_S, FIXED_SE_MULT, w.beta, False, codes, stream)
+
+        def dr():
+            loco_dequant_reduce_fixed(recv_codes, cstride, W, n, bits, FIXED_LOG2_S, out, stream)
+        err = torch.empty(n, dtype=torch.int8, device=dev)
+    state_init(err)
+    tmp_err = torch.empty_like(err)
     for k in range(1, W):
         gk = workloads.gradient(w, 0, worker=k, device=dev)
-        loco_error_state_init(tmp_err)
-        loco_compensate_quantize(gk, tmp_err, bits, B, w.beta, False,
-                                 recv_codes[k * cstride:k * cstride + cb], recv_scales[k * nb:(k + 1) * nb])
+        state_init(tmp_err)
+        cq(gk, tmp_err, recv_codes[k * cstride:k * cstride + cb], recv_scales[k * nb:(k + 1) * nb])
         del gk
     del tmp_err
-    out = torch.empty(n, dtype=torch.float32, device=dev)
-    own_codes, own_scales = recv_codes[:cb], recv_scales[:nb]
     torch.cuda.synchronize()
-
-    stream = torch.cuda.current_stream()
 
     def step(i, ev=None):
         g = grads[i & 1]
         if ev is not None:
             ev[0].record(stream)
-        loco_compensate_quantize(g, err, bits, B, w.beta, False, own_codes, own_scales, stream)
+        cq(g, err, own_codes, own_scales)
         if ev is not None:
             ev[1].record(stream)
-        loco_dequant_reduce(recv_codes, cstride, recv_scales, nb, W, n, bits, B, out, stream)
+        dr()
         if ev is not None:
             ev[2].record(stream)
 
@@ -184,8 +222,8 @@ def main():
                 "median_ms": all_ms[len(all_ms) // 2], "min_ms": all_ms[0],
                 "algorithmic_bytes_per_launch": per_elem * n}
 
-    k_cq = kernel_entry("loco_compensate_quantize", bytes_cq, cq_avg, cq_ms)
-    k_dr = kernel_entry("loco_dequant_reduce", bytes_dr, dr_avg, dr_ms)
+    k_cq = kernel_entry(names[0], bytes_cq, cq_avg, cq_ms)
+    k_dr = kernel_entry(names[1], bytes_dr, dr_avg, dr_ms)
     dominant = k_cq if cq_avg >= dr_avg else k_dr
 
     copy_gbps = None
@@ -208,10 +246,10 @@ def main():
     cpu = None
     if args.cpu_sample > 0:
         # own payload for the sample: one compensate-quantize step from a zero state
-        loco_error_state_init(err)
-        loco_compensate_quantize(grads[0], err, bits, B, w.beta, False, own_codes, own_scales, stream)
+        state_init(err)
+        cq(grads[0], err, own_codes, own_scales)
         torch.cuda.synchronize()
-        cpu = cpu_baseline(w, grads, recv_codes, cstride, recv_scales, nb, args.cpu_sample, bytes_cq, bytes_dr)
+        cpu = cpu_baseline(form, w, grads, recv_codes, cstride, recv_scales, nb, args.cpu_sample, bytes_cq, bytes_dr)
 
     line = {
         "metric": METRIC,
@@ -227,8 +265,10 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "n": n, "grad_dtype": str(w.grad_dtype).replace("torch.", ""),
-                   "bits": bits, "block_size": B, "beta": w.beta, "num_workers": W,
-                   "step": "compensate_quantize + dequant_reduce"},
+                   "bits": bits, "beta": w.beta, "num_workers": W, "form": form,
+                   **({"block_size": B} if form == "block" else
+                      {"log2_s": FIXED_LOG2_S, "se_mult": FIXED_SE_MULT, "state": "int8"}),
+                   "step": " + ".join(n_[5:] for n_ in names)},
         "elements_per_s": n / (total_s / args.steps),
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
