@@ -35,6 +35,8 @@ MEASURED_TRAFFIC = {
     ("llama7b_shard_4bit_b256", "loco_dequant_reduce"): 6.9720e9,
     ("llama7b_shard_8bit_b64", "loco_compensate_quantize"): 9.3179e9,
     ("llama7b_shard_8bit_b64", "loco_dequant_reduce"): 1.05485e10,
+    ("llama7b_shard_4bit_b256", "loco_compensate_quantize_fixed"): 3.7904e9,
+    ("llama7b_shard_4bit_b256", "loco_dequant_reduce_fixed"): 6.7384e9,
 }
 
 
