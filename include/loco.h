@@ -162,6 +162,21 @@ loco_status_t loco_dequant_reduce_fixed(const uint8_t *codes, size_t code_stride
                                         size_t n, int bits, int log2_s, float *grad_out, void *stream);
 
 /*
+ * Element-wise clipping of the local gradient fused in front of step 1 (the paper's
+ * MoE-from-scratch runs clip g "to reduce sensitivity to s", Sec. 5.2; no threshold is given):
+ *   g' = min(max(g, -clip_abs), clip_abs), then exactly as the call without _clip.
+ * clip_abs > 0; +infinity means no clipping and is what the plain calls pass.
+ */
+loco_status_t loco_compensate_quantize_clip(const void *grad, loco_dtype_t grad_dtype, float clip_abs,
+                                            float *err_state, size_t n, int bits, int block_size,
+                                            float beta, int reset, uint8_t *codes_out, float *scales_out,
+                                            void *stream);
+loco_status_t loco_compensate_quantize_fixed_clip(const void *grad, loco_dtype_t grad_dtype, float clip_abs,
+                                                  int8_t *err_state8, size_t n, int bits, int log2_s,
+                                                  int se_mult, float beta, int reset, uint8_t *codes_out,
+                                                  void *stream);
+
+/*
  * Measurement aid, not part of the method: dst[i] = src[i] for `bytes` bytes
  * (a multiple of 16, both pointers 16-byte aligned) with the same load/store
  * shape as the kernels above.  Gives the practical HBM ceiling and the scale

@@ -59,7 +59,9 @@ def _bind(lib):
     lib.loco_ref_fixed_compensate_quantize_mt.argtypes = [vp, i, vp, sz, i, i, i, f, i, vp, i]
     lib.loco_ref_fixed_dequant_reduce.argtypes = [vp, sz, i, sz, i, i, vp]
     lib.loco_ref_fixed_dequant_reduce_mt.argtypes = [vp, sz, i, sz, i, i, vp, i]
+    lib.loco_ref_clip_gradient.argtypes = [vp, i, sz, f, vp]
     for name in (
+        "loco_ref_clip_gradient",
         "loco_ref_fixed_compensate_quantize",
         "loco_ref_fixed_compensate_quantize_mt",
         "loco_ref_fixed_dequant_reduce",
@@ -202,4 +204,15 @@ def fixed_dequant_reduce(codes, num_workers, n, bits, log2_s, code_stride_bytes=
         rc = lib.loco_ref_fixed_dequant_reduce(*args)
     if rc:
         raise ValueError("loco_ref_fixed_dequant_reduce: status %d" % rc)
+    return out
+
+
+def clip_gradient(grad, clip_abs, lib=None):
+    """Element-wise clipping of the local gradient to [-clip_abs, clip_abs] (Sec. 5.2); float32 out."""
+    lib = lib or load()
+    grad = np.ascontiguousarray(grad)
+    out = np.empty(grad.size, dtype=np.float32)
+    rc = lib.loco_ref_clip_gradient(_ptr(grad), _grad_dtype(grad), grad.size, float(clip_abs), _ptr(out))
+    if rc:
+        raise ValueError("loco_ref_clip_gradient: status %d" % rc)
     return out

@@ -321,3 +321,27 @@ int loco_ref_fixed_dequant_reduce(const uint8_t *codes, size_t code_stride_bytes
     return loco_ref_fixed_dequant_reduce_range(codes, code_stride_bytes, num_workers, n, bits, log2_s,
                                                grad_out, 0, n);
 }
+
+/* ------------------------------------------------------------------------------------
+ * Element-wise clipping of the local gradient before step 1 (Sec. 5.2, MoE runs trained
+ * from scratch; the threshold is the caller's, the paper states none):
+ *   out_i = min(max(float(g_i), -c), c),  c > 0 (c = +inf leaves g unchanged).
+ * The clipped gradient is fp32 (c need not be a bf16 value); feed it to the functions
+ * above as an fp32 gradient.
+ * ---------------------------------------------------------------------------------- */
+int loco_ref_clip_gradient(const void *grad, int grad_dtype, size_t n, float clip_abs, float *out)
+{
+    if (grad_dtype != LOCO_REF_F32 && grad_dtype != LOCO_REF_BF16)
+        return LOCO_REF_BAD_ARG;
+    if (!(clip_abs > 0.0f) || (n && (!grad || !out)))
+        return LOCO_REF_BAD_ARG;
+    for (size_t i = 0; i < n; ++i) {
+        float g = grad_at(grad, grad_dtype, i);
+        if (g > clip_abs)
+            g = clip_abs;
+        if (g < -clip_abs)
+            g = -clip_abs;
+        out[i] = g;
+    }
+    return LOCO_REF_OK;
+}

@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     loco_error_state8_init,
     loco_compensate_quantize_fixed,
     loco_dequant_reduce_fixed,
+    loco_compensate_quantize_clip,
+    loco_compensate_quantize_fixed_clip,
 )
 
 __all__ = [
@@ -31,4 +33,6 @@ __all__ = [
     "loco_error_state8_init",
     "loco_compensate_quantize_fixed",
     "loco_dequant_reduce_fixed",
+    "loco_compensate_quantize_clip",
+    "loco_compensate_quantize_fixed_clip",
 ]

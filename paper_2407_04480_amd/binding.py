@@ -33,6 +33,8 @@ EXPORTS = (
     "loco_error_state8_init",
     "loco_compensate_quantize_fixed",
     "loco_dequant_reduce_fixed",
+    "loco_compensate_quantize_clip",
+    "loco_compensate_quantize_fixed_clip",
 )
 
 _lib = None
@@ -76,6 +78,10 @@ def load_library(path: Optional[str] = None):
     lib.loco_compensate_quantize_fixed.restype = i
     lib.loco_dequant_reduce_fixed.argtypes = [vp, sz, i, sz, i, i, vp, vp]
     lib.loco_dequant_reduce_fixed.restype = i
+    lib.loco_compensate_quantize_clip.argtypes = [vp, i, f, vp, sz, i, i, f, i, vp, vp, vp]
+    lib.loco_compensate_quantize_clip.restype = i
+    lib.loco_compensate_quantize_fixed_clip.argtypes = [vp, i, f, vp, sz, i, i, i, f, i, vp, vp]
+    lib.loco_compensate_quantize_fixed_clip.restype = i
     if path is None:
         _lib = lib
     return lib
@@ -123,9 +129,23 @@ def loco_error_state_init(err_state: torch.Tensor, stream=None) -> None:
     _check("loco_error_state_init", lib.loco_error_state_init(p, err_state.numel(), _stream_handle(stream)))
 
 
+def loco_compensate_quantize_clip(grad, clip_abs: float, err_state, bits, block_size, beta, reset, codes_out,
+                                  scales_out, stream=None) -> None:
+    """loco_compensate_quantize with the gradient clipped element-wise to [-clip_abs, clip_abs] first."""
+    loco_compensate_quantize(grad, err_state, bits, block_size, beta, reset, codes_out, scales_out, stream,
+                             _clip_abs=float(clip_abs))
+
+
+def loco_compensate_quantize_fixed_clip(grad, clip_abs: float, err_state8, bits, log2_s, se_mult, beta, reset,
+                                        codes_out, stream=None) -> None:
+    """loco_compensate_quantize_fixed with the gradient clipped to [-clip_abs, clip_abs] first."""
+    loco_compensate_quantize_fixed(grad, err_state8, bits, log2_s, se_mult, beta, reset, codes_out, stream,
+                                   _clip_abs=float(clip_abs))
+
+
 def loco_compensate_quantize(grad: torch.Tensor, err_state: torch.Tensor, bits: int, block_size: int,
                              beta: float, reset: bool, codes_out: torch.Tensor, scales_out: torch.Tensor,
-                             stream=None) -> None:
+                             stream=None, _clip_abs=None) -> None:
     """Algorithm 1 steps 1-2 (Eq. 1-5, 7): err_state is updated in place, codes_out
     (uint8) and scales_out (float32) receive the payload."""
     lib = load_library()
@@ -147,9 +167,14 @@ def loco_compensate_quantize(grad: torch.Tensor, err_state: torch.Tensor, bits: 
             raise ValueError("codes_out too small")
         if scales_out.numel() < (n + block_size - 1) // block_size:
             raise ValueError("scales_out too small")
-    st = lib.loco_compensate_quantize(pg, gd, pe, n, int(bits), int(block_size), float(beta),
-                                      1 if reset else 0, pc, ps, _stream_handle(stream))
-    _check("loco_compensate_quantize", st)
+    if _clip_abs is None:
+        st = lib.loco_compensate_quantize(pg, gd, pe, n, int(bits), int(block_size), float(beta),
+                                          1 if reset else 0, pc, ps, _stream_handle(stream))
+        _check("loco_compensate_quantize", st)
+    else:
+        st = lib.loco_compensate_quantize_clip(pg, gd, _clip_abs, pe, n, int(bits), int(block_size), float(beta),
+                                               1 if reset else 0, pc, ps, _stream_handle(stream))
+        _check("loco_compensate_quantize_clip", st)
 
 
 def loco_dequant_reduce(codes: torch.Tensor, code_stride_bytes: int, scales: torch.Tensor,
@@ -198,7 +223,7 @@ def loco_error_state8_init(err_state8: torch.Tensor, stream=None) -> None:
 
 def loco_compensate_quantize_fixed(grad: torch.Tensor, err_state8: torch.Tensor, bits: int, log2_s: int,
                                    se_mult: int, beta: float, reset: bool, codes_out: torch.Tensor,
-                                   stream=None) -> None:
+                                   stream=None, _clip_abs=None) -> None:
     """Algorithm 1 steps 1-2 with the global scale s = 2^log2_s and the 8-bit error state
     (scale se_mult * s), Eq. 1-3, 5, 7: err_state8 (int8) is updated in place."""
     lib = load_library()
@@ -216,9 +241,14 @@ def loco_compensate_quantize_fixed(grad: torch.Tensor, err_state8: torch.Tensor,
         raise ValueError("err_state8 must have as many elements as grad")
     if bits in (4, 8) and codes_out.numel() < (n * bits + 7) // 8:
         raise ValueError("codes_out too small")
-    st = lib.loco_compensate_quantize_fixed(pg, gd, pe, n, int(bits), int(log2_s), int(se_mult), float(beta),
-                                            1 if reset else 0, pc, _stream_handle(stream))
-    _check("loco_compensate_quantize_fixed", st)
+    if _clip_abs is None:
+        st = lib.loco_compensate_quantize_fixed(pg, gd, pe, n, int(bits), int(log2_s), int(se_mult), float(beta),
+                                                1 if reset else 0, pc, _stream_handle(stream))
+        _check("loco_compensate_quantize_fixed", st)
+    else:
+        st = lib.loco_compensate_quantize_fixed_clip(pg, gd, _clip_abs, pe, n, int(bits), int(log2_s), int(se_mult),
+                                                     float(beta), 1 if reset else 0, pc, _stream_handle(stream))
+        _check("loco_compensate_quantize_fixed_clip", st)
 
 
 def loco_dequant_reduce_fixed(codes: torch.Tensor, code_stride_bytes: int, num_workers: int, n: int, bits: int,

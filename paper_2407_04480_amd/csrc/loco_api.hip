@@ -71,25 +71,39 @@ loco_status_t grid_for(size_t units, size_t per_group, unsigned* grid, size_t ro
 
 loco_status_t launched() { return hipGetLastError() == hipSuccess ? LOCO_OK : LOCO_ERR_LAUNCH; }
 
+struct CqArgs {
+    const void* grad;
+    float* err;
+    size_t n;
+    float beta;
+    int reset;
+    float clip;   // +inf: no clipping
+    uint8_t* codes;
+    float* scales;
+};
+
 template <typename G, int BITS, int BLOCK>
-void launch_cq(unsigned grid, hipStream_t s, const void* grad, float* err, size_t n, float beta,
-               int reset, uint8_t* codes, float* scales) {
-    const float one_minus_beta = 1.0f - beta;
+void launch_cq(unsigned grid, hipStream_t s, const CqArgs& a) {
+    const float one_minus_beta = 1.0f - a.beta;
     using Shape = CqShape<BITS>;
-    cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun>
-        <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(
-        grad, err, n, beta, one_minus_beta, reset, codes, scales);
+    if (std::isinf(a.clip))
+        cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false>
+            <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset,
+                                                          a.clip, a.codes, a.scales);
+    else
+        cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, true>
+            <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset,
+                                                          a.clip, a.codes, a.scales);
 }
 
 template <typename G, int BITS>
-bool dispatch_cq_block(int block, unsigned grid, hipStream_t s, const void* grad, float* err, size_t n,
-                       float beta, int reset, uint8_t* codes, float* scales) {
+bool dispatch_cq_block(int block, unsigned grid, hipStream_t s, const CqArgs& a) {
     switch (block) {
-        case 32: launch_cq<G, BITS, 32>(grid, s, grad, err, n, beta, reset, codes, scales); return true;
-        case 64: launch_cq<G, BITS, 64>(grid, s, grad, err, n, beta, reset, codes, scales); return true;
-        case 128: launch_cq<G, BITS, 128>(grid, s, grad, err, n, beta, reset, codes, scales); return true;
-        case 256: launch_cq<G, BITS, 256>(grid, s, grad, err, n, beta, reset, codes, scales); return true;
-        case 512: launch_cq<G, BITS, 512>(grid, s, grad, err, n, beta, reset, codes, scales); return true;
+        case 32: launch_cq<G, BITS, 32>(grid, s, a); return true;
+        case 64: launch_cq<G, BITS, 64>(grid, s, a); return true;
+        case 128: launch_cq<G, BITS, 128>(grid, s, a); return true;
+        case 256: launch_cq<G, BITS, 256>(grid, s, a); return true;
+        case 512: launch_cq<G, BITS, 512>(grid, s, a); return true;
         default: return false;
     }
 }
@@ -126,20 +140,24 @@ bool fixed_args_ok(int bits, int log2_s, int se_mult) {
 
 template <typename G, int BITS, bool POW2>
 void launch_fixed_cq(unsigned grid, hipStream_t s, const void* grad, int8_t* err8, size_t n,
-                     const FixedScales& k, int reset, uint8_t* codes) {
-    fixed_cq_kernel<G, BITS, POW2, FixedCqShape::kUnits, FixedCqShape::kThreads, kNonTemporal>
-        <<<dim3(grid), dim3(FixedCqShape::kThreads), 0, s>>>(grad, err8, n, k, reset, codes);
+                     const FixedScales& k, int reset, float clip, uint8_t* codes) {
+    if (std::isinf(clip))
+        fixed_cq_kernel<G, BITS, POW2, FixedCqShape::kUnits, FixedCqShape::kThreads, kNonTemporal, false>
+            <<<dim3(grid), dim3(FixedCqShape::kThreads), 0, s>>>(grad, err8, n, k, reset, clip, codes);
+    else
+        fixed_cq_kernel<G, BITS, POW2, FixedCqShape::kUnits, FixedCqShape::kThreads, kNonTemporal, true>
+            <<<dim3(grid), dim3(FixedCqShape::kThreads), 0, s>>>(grad, err8, n, k, reset, clip, codes);
 }
 
 template <typename G>
 void dispatch_fixed_cq(int bits, bool pow2, unsigned grid, hipStream_t s, const void* grad, int8_t* err8,
-                       size_t n, const FixedScales& k, int reset, uint8_t* codes) {
+                       size_t n, const FixedScales& k, int reset, float clip, uint8_t* codes) {
     if (bits == 4) {
-        if (pow2) launch_fixed_cq<G, 4, true>(grid, s, grad, err8, n, k, reset, codes);
-        else launch_fixed_cq<G, 4, false>(grid, s, grad, err8, n, k, reset, codes);
+        if (pow2) launch_fixed_cq<G, 4, true>(grid, s, grad, err8, n, k, reset, clip, codes);
+        else launch_fixed_cq<G, 4, false>(grid, s, grad, err8, n, k, reset, clip, codes);
     } else {
-        if (pow2) launch_fixed_cq<G, 8, true>(grid, s, grad, err8, n, k, reset, codes);
-        else launch_fixed_cq<G, 8, false>(grid, s, grad, err8, n, k, reset, codes);
+        if (pow2) launch_fixed_cq<G, 8, true>(grid, s, grad, err8, n, k, reset, clip, codes);
+        else launch_fixed_cq<G, 8, false>(grid, s, grad, err8, n, k, reset, clip, codes);
     }
 }
 
@@ -184,13 +202,14 @@ loco_status_t loco_error_state_init(float* err_state, size_t n, void* stream) {
     return launched();
 }
 
-loco_status_t loco_compensate_quantize(const void* grad, loco_dtype_t grad_dtype, float* err_state,
-                                       size_t n, int bits, int block_size, float beta, int reset,
-                                       uint8_t* codes_out, float* scales_out, void* stream) {
+loco_status_t loco_compensate_quantize_clip(const void* grad, loco_dtype_t grad_dtype, float clip_abs,
+                                            float* err_state, size_t n, int bits, int block_size, float beta,
+                                            int reset, uint8_t* codes_out, float* scales_out, void* stream) {
     if (bits != 4 && bits != 8) return LOCO_ERR_UNSUPPORTED;
     if (!block_size_ok(block_size)) return LOCO_ERR_UNSUPPORTED;
     if (grad_dtype != LOCO_F32 && grad_dtype != LOCO_BF16) return LOCO_ERR_UNSUPPORTED;
     if (!(beta >= 0.0f && beta <= 1.0f)) return LOCO_ERR_INVALID_ARG;  // also rejects NaN
+    if (!(clip_abs > 0.0f)) return LOCO_ERR_INVALID_ARG;               // NaN, zero, negative
     if (n == 0) return LOCO_OK;
     if (!grad || !err_state || !codes_out || !scales_out) return LOCO_ERR_INVALID_ARG;
     if (!aligned(grad, 16) || !aligned(err_state, 16) || !aligned(codes_out, 16) || !aligned(scales_out, 4))
@@ -206,16 +225,24 @@ loco_status_t loco_compensate_quantize(const void* grad, loco_dtype_t grad_dtype
                                        : (size_t)kSlot * CqShape<8>::kSlots * (CqShape<8>::kThreads / kWave);
     if (loco_status_t st = grid_for(n, per_group, &grid, kCqXcdRun ? 8 * kCqXcdRun : 1)) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const CqArgs a{grad, err_state, n, beta, reset, clip_abs, codes_out, scales_out};
     bool ok;
     if (grad_dtype == LOCO_BF16) {
-        ok = bits == 4 ? dispatch_cq_block<bf16_t, 4>(block_size, grid, s, grad, err_state, n, beta, reset, codes_out, scales_out)
-                       : dispatch_cq_block<bf16_t, 8>(block_size, grid, s, grad, err_state, n, beta, reset, codes_out, scales_out);
+        ok = bits == 4 ? dispatch_cq_block<bf16_t, 4>(block_size, grid, s, a)
+                       : dispatch_cq_block<bf16_t, 8>(block_size, grid, s, a);
     } else {
-        ok = bits == 4 ? dispatch_cq_block<float, 4>(block_size, grid, s, grad, err_state, n, beta, reset, codes_out, scales_out)
-                       : dispatch_cq_block<float, 8>(block_size, grid, s, grad, err_state, n, beta, reset, codes_out, scales_out);
+        ok = bits == 4 ? dispatch_cq_block<float, 4>(block_size, grid, s, a)
+                       : dispatch_cq_block<float, 8>(block_size, grid, s, a);
     }
     if (!ok) return LOCO_ERR_UNSUPPORTED;
     return launched();
+}
+
+loco_status_t loco_compensate_quantize(const void* grad, loco_dtype_t grad_dtype, float* err_state,
+                                       size_t n, int bits, int block_size, float beta, int reset,
+                                       uint8_t* codes_out, float* scales_out, void* stream) {
+    return loco_compensate_quantize_clip(grad, grad_dtype, INFINITY, err_state, n, bits, block_size, beta, reset,
+                                         codes_out, scales_out, stream);
 }
 
 loco_status_t loco_dequant_reduce(const uint8_t* codes, size_t code_stride_bytes, const float* scales,
@@ -287,7 +314,16 @@ loco_status_t loco_error_state8_init(int8_t* err_state8, size_t n, void* stream)
 loco_status_t loco_compensate_quantize_fixed(const void* grad, loco_dtype_t grad_dtype, int8_t* err_state8,
                                              size_t n, int bits, int log2_s, int se_mult, float beta,
                                              int reset, uint8_t* codes_out, void* stream) {
+    return loco_compensate_quantize_fixed_clip(grad, grad_dtype, INFINITY, err_state8, n, bits, log2_s, se_mult,
+                                               beta, reset, codes_out, stream);
+}
+
+loco_status_t loco_compensate_quantize_fixed_clip(const void* grad, loco_dtype_t grad_dtype, float clip_abs,
+                                                  int8_t* err_state8, size_t n, int bits, int log2_s,
+                                                  int se_mult, float beta, int reset, uint8_t* codes_out,
+                                                  void* stream) {
     if (!fixed_args_ok(bits, log2_s, se_mult)) return LOCO_ERR_UNSUPPORTED;
+    if (!(clip_abs > 0.0f)) return LOCO_ERR_INVALID_ARG;
     if (grad_dtype != LOCO_F32 && grad_dtype != LOCO_BF16) return LOCO_ERR_UNSUPPORTED;
     if (!(beta >= 0.0f && beta <= 1.0f)) return LOCO_ERR_INVALID_ARG;
     if (n == 0) return LOCO_OK;
@@ -309,8 +345,8 @@ loco_status_t loco_compensate_quantize_fixed(const void* grad, loco_dtype_t grad
     k.one_minus_beta = 1.0f - beta;
     const bool pow2 = (se_mult & (se_mult - 1)) == 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (grad_dtype == LOCO_BF16) dispatch_fixed_cq<bf16_t>(bits, pow2, grid, s, grad, err_state8, n, k, reset, codes_out);
-    else dispatch_fixed_cq<float>(bits, pow2, grid, s, grad, err_state8, n, k, reset, codes_out);
+    if (grad_dtype == LOCO_BF16) dispatch_fixed_cq<bf16_t>(bits, pow2, grid, s, grad, err_state8, n, k, reset, clip_abs, codes_out);
+    else dispatch_fixed_cq<float>(bits, pow2, grid, s, grad, err_state8, n, k, reset, clip_abs, codes_out);
     return launched();
 }
 

@@ -96,10 +96,10 @@ __device__ __forceinline__ void fixed_cq_octet(const float (&g)[8], const uint32
 
 // One wavefront per UNITS*512 elements, THREADS/64 wavefronts per workgroup;
 // grid = ceil(n / (UNITS*512*THREADS/64)).  The last wavefront may take the guarded path.
-template <typename G, int BITS, bool POW2, int UNITS, int THREADS, bool NT>
+template <typename G, int BITS, bool POW2, int UNITS, int THREADS, bool NT, bool CLIP>
 __global__ void __launch_bounds__(THREADS)
 fixed_cq_kernel(const void* __restrict__ grad, int8_t* __restrict__ err8, size_t n, FixedScales k,
-                int reset, uint8_t* __restrict__ codes) {
+                int reset, float clip, uint8_t* __restrict__ codes) {
     constexpr size_t TILE = (size_t)kUnit * UNITS;
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const size_t tile0 = wave_tile_index<THREADS, 0>() * TILE;
@@ -113,6 +113,8 @@ fixed_cq_kernel(const void* __restrict__ grad, int8_t* __restrict__ err8, size_t
         for (int u = 0; u < UNITS; ++u) {
             const size_t i = tile0 + (size_t)u * kUnit + (size_t)lane * kOctet;
             GradOctet<G>::template load8<NT>(grad, i, g[u]);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) g[u][j] = clip_grad<CLIP>(g[u][j], clip);
             const u32x2 v = vload<NT>(reinterpret_cast<const u32x2*>(err8 + i));
             e8[u][0] = v.x; e8[u][1] = v.y;
         }
@@ -135,7 +137,7 @@ fixed_cq_kernel(const void* __restrict__ grad, int8_t* __restrict__ err8, size_t
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const bool in = i + j < n;
-                g[j] = in ? Grad<G>::load1(grad, i + j) : 0.0f;
+                g[j] = in ? clip_grad<CLIP>(Grad<G>::load1(grad, i + j), clip) : 0.0f;
                 if (in) e8[j >> 2] |= (uint32_t)(uint8_t)err8[i + j] << (8 * (j & 3));
             }
             fixed_cq_octet<BITS, POW2>(g, e8, k, rst, c, en);

@@ -48,6 +48,14 @@ __device__ __forceinline__ void vstore(V* p, V v) {
 
 __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
 
+// Element-wise clipping of the local gradient to [-c, c] before compensation (used by the
+// paper's MoE-from-scratch runs, Sec. 5.2, to reduce sensitivity to s); one v_med3_f32.
+template <bool CLIP>
+__device__ __forceinline__ float clip_grad(float g, float c) {
+    if constexpr (CLIP) return fminf(fmaxf(g, -c), c);
+    else return g;
+}
+
 // ---- cross-lane all-reduce (max) over aligned groups of LANES consecutive lanes ----
 // Operands are bit patterns of non-negative floats, which order like unsigned ints.
 template <int CTRL>
@@ -173,10 +181,11 @@ __device__ __forceinline__ void cq_tile(const float (&h)[SLOTS][4], float (&e)[S
 // own contiguous tile.  grid = ceil(n / (SLOTS*256*THREADS/64)), rounded up to a multiple of 8*XCDK.  A wavefront whose tile
 // lies inside [0, n) takes the vector path; the last one may take the guarded path, which
 // touches memory element by element and never at or beyond n.
-template <typename G, int BITS, int BLOCK, int SLOTS, int THREADS, bool NT, int XCDK>
+template <typename G, int BITS, int BLOCK, int SLOTS, int THREADS, bool NT, int XCDK, bool CLIP>
 __global__ void __launch_bounds__(THREADS)
 cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, float beta,
-          float one_minus_beta, int reset, uint8_t* __restrict__ codes, float* __restrict__ scales) {
+          float one_minus_beta, int reset, float clip, uint8_t* __restrict__ codes,
+          float* __restrict__ scales) {
     constexpr int GROUP = BLOCK >= kSlot ? kWave : BLOCK / kQuad;  // lanes per block within a slot
     constexpr size_t TILE = (size_t)kSlot * SLOTS;
     const int lane = threadIdx.x & (kWave - 1);
@@ -198,7 +207,7 @@ cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, floa
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) h[s][j] = h[s][j] + e[s][j];  // Eq. 2
+            for (int j = 0; j < 4; ++j) h[s][j] = clip_grad<CLIP>(h[s][j], clip) + e[s][j];  // Eq. 2
         cq_tile<BITS, BLOCK, SLOTS>(h, e, beta, one_minus_beta, rst, lane, pk, step);
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
@@ -229,7 +238,7 @@ cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, floa
                 const bool in = i + j < n;
                 e[s][j] = in ? err[i + j] : 0.0f;
                 const float gj = in ? Grad<G>::load1(grad, i + j) : 0.0f;
-                h[s][j] = gj + e[s][j];  // past n: h = 0, neutral for the max, code 0
+                h[s][j] = clip_grad<CLIP>(gj, clip) + e[s][j];  // past n: h = 0, neutral for the max, code 0
             }
         }
         cq_tile<BITS, BLOCK, SLOTS>(h, e, beta, one_minus_beta, rst, lane, pk, step);

@@ -680,7 +680,28 @@ def check_fixed_edges(lib):
     assert np.array_equal(o1, o4)
 
 
+def check_clip(lib):
+    """Clipping to [-c, c]: values inside are untouched, values outside land on +-c with their
+    sign, c = inf is the identity, the map is idempotent, and bf16 input is widened first."""
+    rng = np.random.default_rng(71)
+    g = rng_grad(rng, 5000, "student", 1e-3)
+    g[:4] = [0.0, -0.0, 1e30, -1e30]
+    for c in (np.float32(1e-3), np.float32(3.3e-4), np.float32(2.0 ** -12)):
+        out = oracle.clip_gradient(g, c, lib=lib)
+        inside = np.abs(g) <= c
+        assert inside.any() and (~inside).any()
+        assert np.array_equal(out[inside], g[inside])
+        assert np.all(out[~inside] == np.sign(g[~inside]) * c)
+        assert np.array_equal(oracle.clip_gradient(out, c, lib=lib), out)
+    assert np.array_equal(oracle.clip_gradient(g, np.inf, lib=lib), g)
+    gb = to_bf16_bits(g)
+    c = np.float32(7.7e-4)                              # not a bf16 value
+    out = oracle.clip_gradient(gb, c, lib=lib)
+    assert np.array_equal(out, np.clip(bf16_bits_to_f32(gb), -c, c)) and (out == c).any()
+
+
 FIXED_CHECKS = [
+    check_clip,
     check_fixed_worked_example,
     check_fixed_nearest_levels,
     check_fixed_zero_error_fixed_point,

@@ -53,6 +53,8 @@ MUTANTS = [
      "float d = (float)q / s_e;"),
     ("fixed_reset_ignored", "int e8 = reset ? 0 :", "int e8 = 0 ? 0 :"),
     ("fixed_reduce_no_average", "grad_out[i] = acc * inv;", "grad_out[i] = acc;", 1),
+    ("clip_one_sided", "if (g < -clip_abs)\n            g = -clip_abs;", ""),
+    ("clip_sign_lost", "            g = -clip_abs;", "            g = clip_abs;"),
     ("fixed_reduce_stride", "int q = code_at(codes + (size_t)w * code_stride_bytes, bits, i);\n            float d = (float)q / s;",
      "int q = code_at(codes, bits, i);\n            float d = (float)q / s;"),
 ]
