@@ -60,7 +60,11 @@ def _bind(lib):
     lib.loco_ref_fixed_dequant_reduce.argtypes = [vp, sz, i, sz, i, i, vp]
     lib.loco_ref_fixed_dequant_reduce_mt.argtypes = [vp, sz, i, sz, i, i, vp, i]
     lib.loco_ref_clip_gradient.argtypes = [vp, i, sz, f, vp]
+    lib.loco_ref_sgd_update.argtypes = [vp, vp, sz, f]
+    lib.loco_ref_adam_update.argtypes = [vp, vp, vp, vp, sz, f, f, f, f]
     for name in (
+        "loco_ref_sgd_update",
+        "loco_ref_adam_update",
         "loco_ref_clip_gradient",
         "loco_ref_fixed_compensate_quantize",
         "loco_ref_fixed_compensate_quantize_mt",
@@ -216,3 +220,23 @@ def clip_gradient(grad, clip_abs, lib=None):
     if rc:
         raise ValueError("loco_ref_clip_gradient: status %d" % rc)
     return out
+
+
+def sgd_update(theta, g_avg, eta, lib=None):
+    """Eq. 9: theta <- theta - eta * g~ (in place, float32)."""
+    lib = lib or load()
+    assert theta.dtype == np.float32 and g_avg.dtype == np.float32 and theta.size == g_avg.size
+    rc = lib.loco_ref_sgd_update(_ptr(theta), _ptr(np.ascontiguousarray(g_avg)), theta.size, float(eta))
+    if rc:
+        raise ValueError("loco_ref_sgd_update: status %d" % rc)
+
+
+def adam_update(theta, m, v, g_avg, eta, beta1, beta2, delta, lib=None):
+    """Eq. 10 with Adam's pre-conditioner 1/sqrt(v + delta); theta, m, v updated in place."""
+    lib = lib or load()
+    for a in (theta, m, v, g_avg):
+        assert a.dtype == np.float32 and a.flags.c_contiguous and a.size == theta.size
+    rc = lib.loco_ref_adam_update(_ptr(theta), _ptr(m), _ptr(v), _ptr(g_avg), theta.size, float(eta),
+                                  float(beta1), float(beta2), float(delta))
+    if rc:
+        raise ValueError("loco_ref_adam_update: status %d" % rc)

@@ -345,3 +345,50 @@ int loco_ref_clip_gradient(const void *grad, int grad_dtype, size_t n, float cli
     }
     return LOCO_REF_OK;
 }
+
+/* ------------------------------------------------------------------------------------
+ * The optimizer steps that consume the averaged gradient g~ (Sec. 4).
+ *   SGD (Eq. 9):           theta' = theta - eta g~
+ *   Adam family (Eq. 10):  m'  = (1-beta1) m + beta1 g~
+ *                          v'  = (1-beta2) v + beta2 g~^2        (Adam's second moment)
+ *                          eta_k = eta / sqrt(v' + delta)         (the pre-conditioner v(.))
+ *                          theta' = theta - eta_k m'
+ * exactly as the paper writes them: no bias correction, delta inside the square root,
+ * m_0 = v_0 = 0.  Binary32, one rounding per operation; the two moving averages are
+ * written like Eq. 5, fmaf(1-beta, old, beta*new).
+ * ---------------------------------------------------------------------------------- */
+int loco_ref_sgd_update(float *theta, const float *g_avg, size_t n, float eta)
+{
+    if (n && (!theta || !g_avg))
+        return LOCO_REF_BAD_ARG;
+    for (size_t i = 0; i < n; ++i) {
+        float step = eta * g_avg[i];
+        theta[i] = theta[i] - step;
+    }
+    return LOCO_REF_OK;
+}
+
+int loco_ref_adam_update(float *theta, float *m, float *v, const float *g_avg, size_t n, float eta,
+                         float beta1, float beta2, float delta)
+{
+    if (n && (!theta || !m || !v || !g_avg))
+        return LOCO_REF_BAD_ARG;
+    if (!(beta1 >= 0.0f && beta1 <= 1.0f) || !(beta2 >= 0.0f && beta2 <= 1.0f) || !(delta >= 0.0f))
+        return LOCO_REF_BAD_ARG;
+    const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+    for (size_t i = 0; i < n; ++i) {
+        float g = g_avg[i];
+        float b1g = beta1 * g;
+        float m_new = fmaf(omb1, m[i], b1g);
+        float g2 = g * g;
+        float b2g2 = beta2 * g2;
+        float v_new = fmaf(omb2, v[i], b2g2);
+        float root = sqrtf(v_new + delta);
+        float eta_k = eta / root;
+        float step = eta_k * m_new;
+        m[i] = m_new;
+        v[i] = v_new;
+        theta[i] = theta[i] - step;
+    }
+    return LOCO_REF_OK;
+}

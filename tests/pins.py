@@ -700,8 +700,67 @@ def check_clip(lib):
     assert np.array_equal(out, np.clip(bf16_bits_to_f32(gb), -c, c)) and (out == c).any()
 
 
+def check_optimizer_steps(lib):
+    """Eq. 9 and Eq. 10 as written (no bias correction, delta inside the root, m_0 = v_0 = 0):
+    closed forms for a constant gradient, the unrolled recurrences in binary64 for a varying
+    one, beta1 = 1 (no momentum), a zero gradient, and the sign symmetry of the update."""
+    rng = np.random.default_rng(83)
+    n, K = 2000, 9
+    eta, b1, b2, dl = 1e-3, 0.1, 0.02, 1e-8
+    # SGD: theta_K = theta_0 - eta * sum g
+    th0 = rng.standard_normal(n).astype(np.float32)
+    th = th0.copy()
+    gs = [rng_grad(rng, n, "normal", 1e-2) for _ in range(K)]
+    for g in gs:
+        oracle.sgd_update(th, g, eta, lib=lib)
+    want = th0 - eta * np.sum(np.stack(gs).astype(np.float64), axis=0)
+    assert np.abs(th - want).max() <= K * 2.0 ** -23 * np.abs(th0).max()
+    assert np.abs(th - th0).max() > 1e-5
+    # Adam family, varying gradient: unrolled in binary64
+    th = th0.copy()
+    m, v = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    m64, v64, th64 = np.zeros(n), np.zeros(n), th0.astype(np.float64)
+    f = lambda x: np.float64(np.float32(x))
+    for g in gs:
+        oracle.adam_update(th, m, v, g, eta, b1, b2, dl, lib=lib)
+        m64 = (1 - f(b1)) * m64 + f(b1) * g
+        v64 = (1 - f(b2)) * v64 + f(b2) * g.astype(np.float64) ** 2
+        th64 = th64 - f(eta) / np.sqrt(v64 + f(dl)) * m64
+    assert np.abs(m - m64).max() <= K * 2.0 ** -22 * np.abs(m64).max()
+    assert np.abs(v - v64).max() <= K * 2.0 ** -22 * np.abs(v64).max()
+    assert np.abs(th - th64).max() <= K * 2.0 ** -21 * np.abs(th0).max()
+    assert np.abs(th - th0).max() > 1e-3                       # steps of order eta/sqrt(beta2) each
+    # constant gradient c: m_k = c (1 - (1-b1)^k), v_k = c^2 (1 - (1-b2)^k)
+    c = np.float32(3e-3)
+    th = np.zeros(4, np.float32)
+    m, v = np.zeros(4, np.float32), np.zeros(4, np.float32)
+    g = np.full(4, c, np.float32)
+    for k in range(1, 6):
+        oracle.adam_update(th, m, v, g, eta, b1, b2, 0.0, lib=lib)
+        assert abs(m[0] / (c * (1 - (1 - f(b1)) ** k)) - 1) < 1e-6
+        assert abs(v[0] / (f(c) ** 2 * (1 - (1 - f(b2)) ** k)) - 1) < 1e-6
+    # first step from zero moments, delta = 0: theta_1 = -eta * b1 * g / (sqrt(b2) |g|) whatever |g|
+    for scale in (1e-6, 1.0, 1e4):
+        th = np.zeros(2, np.float32)
+        m, v = np.zeros(2, np.float32), np.zeros(2, np.float32)
+        oracle.adam_update(th, m, v, np.array([scale, -scale], np.float32), eta, b1, b2, 0.0, lib=lib)
+        step = f(eta) * f(b1) / np.sqrt(f(b2))
+        assert abs(th[0] / -step - 1) < 1e-6 and th[1] == -th[0]
+    # beta1 = 1: no momentum; zero gradient: moments decay, theta moves only by the old momentum
+    th = th0.copy()
+    m, v = rng_grad(rng, n, "normal", 1e-2), np.abs(rng_grad(rng, n, "normal", 1e-4))
+    g = rng_grad(rng, n, "normal", 1e-2)
+    oracle.adam_update(th, m, v, g, eta, 1.0, b2, dl, lib=lib)
+    assert np.array_equal(m, g)
+    m0, v0, th1 = m.copy(), v.copy(), th.copy()
+    oracle.adam_update(th, m, v, np.zeros(n, np.float32), eta, b1, b2, dl, lib=lib)
+    assert np.allclose(m, (1 - f(b1)) * m0, rtol=1e-6) and np.allclose(v, (1 - f(b2)) * v0, rtol=1e-6)
+    assert np.all(np.sign(th1 - th) == np.sign(m))
+
+
 FIXED_CHECKS = [
     check_clip,
+    check_optimizer_steps,
     check_fixed_worked_example,
     check_fixed_nearest_levels,
     check_fixed_zero_error_fixed_point,

@@ -55,6 +55,14 @@ MUTANTS = [
     ("fixed_reduce_no_average", "grad_out[i] = acc * inv;", "grad_out[i] = acc;", 1),
     ("clip_one_sided", "if (g < -clip_abs)\n            g = -clip_abs;", ""),
     ("clip_sign_lost", "            g = -clip_abs;", "            g = clip_abs;"),
+    ("sgd_ascent", "theta[i] = theta[i] - step;\n    }\n    return LOCO_REF_OK;\n}\n\nint loco_ref_adam_update",
+     "theta[i] = theta[i] + step;\n    }\n    return LOCO_REF_OK;\n}\n\nint loco_ref_adam_update"),
+    ("adam_bias_corrected_root", "float root = sqrtf(v_new + delta);", "float root = sqrtf(v_new) + delta;"),
+    ("adam_second_moment_not_squared", "float g2 = g * g;", "float g2 = g;"),
+    ("adam_moment_weights_swapped", "float m_new = fmaf(omb1, m[i], b1g);", "float m_new = fmaf(beta1, m[i], omb1 * g);"),
+    ("adam_uses_old_v", "float root = sqrtf(v_new + delta);", "float root = sqrtf(v[i] + delta);"),
+    ("adam_uses_gradient_not_momentum", "float step = eta_k * m_new;", "float step = eta_k * g;"),
+    ("adam_v_not_stored", "        v[i] = v_new;\n", ""),
     ("fixed_reduce_stride", "int q = code_at(codes + (size_t)w * code_stride_bytes, bits, i);\n            float d = (float)q / s;",
      "int q = code_at(codes, bits, i);\n            float d = (float)q / s;"),
 ]
