@@ -177,6 +177,33 @@ loco_status_t loco_compensate_quantize_fixed_clip(const void *grad, loco_dtype_t
                                                   void *stream);
 
 /*
+ * The optimizer step that consumes the averaged gradient g~ of Eq. 8, fused into the reduce
+ * so that g~ is never written to memory and read back (saves 8 bytes per element):
+ *   _sgd   Eq. 9:   theta' = theta - eta g~
+ *   _adam  Eq. 10 with Adam's pre-conditioner, exactly as written in Sec. 4 (no bias
+ *          correction, delta inside the root, m_0 = v_0 = 0):
+ *            m' = (1-beta1) m + beta1 g~,  v' = (1-beta2) v + beta2 g~^2,
+ *            theta' = theta - (eta / sqrt(v' + delta)) m'
+ * theta, m, v: [n] fp32 device, 16-byte aligned, updated in place.  eta finite;
+ * 0 <= beta1, beta2 <= 1; 0 <= delta < inf.  Payload arguments as for the plain reduce.
+ * Binary32, one rounding per operation, correctly rounded square root and division.
+ */
+loco_status_t loco_dequant_reduce_sgd(const uint8_t *codes, size_t code_stride_bytes, const float *scales,
+                                      size_t scale_stride_elems, int num_workers, size_t n, int bits,
+                                      int block_size, float eta, float *theta, void *stream);
+loco_status_t loco_dequant_reduce_adam(const uint8_t *codes, size_t code_stride_bytes, const float *scales,
+                                       size_t scale_stride_elems, int num_workers, size_t n, int bits,
+                                       int block_size, float eta, float beta1, float beta2, float delta,
+                                       float *m, float *v, float *theta, void *stream);
+loco_status_t loco_dequant_reduce_fixed_sgd(const uint8_t *codes, size_t code_stride_bytes, int num_workers,
+                                            size_t n, int bits, int log2_s, float eta, float *theta,
+                                            void *stream);
+loco_status_t loco_dequant_reduce_fixed_adam(const uint8_t *codes, size_t code_stride_bytes, int num_workers,
+                                             size_t n, int bits, int log2_s, float eta, float beta1,
+                                             float beta2, float delta, float *m, float *v, float *theta,
+                                             void *stream);
+
+/*
  * Measurement aid, not part of the method: dst[i] = src[i] for `bytes` bytes
  * (a multiple of 16, both pointers 16-byte aligned) with the same load/store
  * shape as the kernels above.  Gives the practical HBM ceiling and the scale

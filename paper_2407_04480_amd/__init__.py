@@ -19,6 +19,10 @@ from .binding import (  # noqa: F401
     loco_dequant_reduce_fixed,
     loco_compensate_quantize_clip,
     loco_compensate_quantize_fixed_clip,
+    loco_dequant_reduce_sgd,
+    loco_dequant_reduce_adam,
+    loco_dequant_reduce_fixed_sgd,
+    loco_dequant_reduce_fixed_adam,
 )
 
 __all__ = [
@@ -35,4 +39,8 @@ __all__ = [
     "loco_dequant_reduce_fixed",
     "loco_compensate_quantize_clip",
     "loco_compensate_quantize_fixed_clip",
+    "loco_dequant_reduce_sgd",
+    "loco_dequant_reduce_adam",
+    "loco_dequant_reduce_fixed_sgd",
+    "loco_dequant_reduce_fixed_adam",
 ]

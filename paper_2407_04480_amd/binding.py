@@ -35,6 +35,10 @@ EXPORTS = (
     "loco_dequant_reduce_fixed",
     "loco_compensate_quantize_clip",
     "loco_compensate_quantize_fixed_clip",
+    "loco_dequant_reduce_sgd",
+    "loco_dequant_reduce_adam",
+    "loco_dequant_reduce_fixed_sgd",
+    "loco_dequant_reduce_fixed_adam",
 )
 
 _lib = None
@@ -82,6 +86,13 @@ def load_library(path: Optional[str] = None):
     lib.loco_compensate_quantize_clip.restype = i
     lib.loco_compensate_quantize_fixed_clip.argtypes = [vp, i, f, vp, sz, i, i, i, f, i, vp, vp]
     lib.loco_compensate_quantize_fixed_clip.restype = i
+    lib.loco_dequant_reduce_sgd.argtypes = [vp, sz, vp, sz, i, sz, i, i, f, vp, vp]
+    lib.loco_dequant_reduce_adam.argtypes = [vp, sz, vp, sz, i, sz, i, i, f, f, f, f, vp, vp, vp, vp]
+    lib.loco_dequant_reduce_fixed_sgd.argtypes = [vp, sz, i, sz, i, i, f, vp, vp]
+    lib.loco_dequant_reduce_fixed_adam.argtypes = [vp, sz, i, sz, i, i, f, f, f, f, vp, vp, vp, vp]
+    for _n in ("loco_dequant_reduce_sgd", "loco_dequant_reduce_adam", "loco_dequant_reduce_fixed_sgd",
+               "loco_dequant_reduce_fixed_adam"):
+        getattr(lib, _n).restype = i
     if path is None:
         _lib = lib
     return lib
@@ -266,3 +277,56 @@ def loco_dequant_reduce_fixed(codes: torch.Tensor, code_stride_bytes: int, num_w
     st = lib.loco_dequant_reduce_fixed(pc, int(code_stride_bytes), int(num_workers), int(n), int(bits),
                                        int(log2_s), po, _stream_handle(stream))
     _check("loco_dequant_reduce_fixed", st)
+
+
+def _f32(t, name, n):
+    p = _dev_ptr(t, name, torch.float32)
+    if t.numel() < n:
+        raise ValueError(f"{name} too small")
+    return p
+
+
+def loco_dequant_reduce_sgd(codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n, bits, block_size,
+                            eta: float, theta: torch.Tensor, stream=None) -> None:
+    """Eq. 8 fused with the SGD step of Eq. 9: theta <- theta - eta * g~ (in place)."""
+    lib = load_library()
+    st = lib.loco_dequant_reduce_sgd(_dev_ptr(codes, "codes", torch.uint8), int(code_stride_bytes),
+                                     _dev_ptr(scales, "scales", torch.float32), int(scale_stride_elems),
+                                     int(num_workers), int(n), int(bits), int(block_size), float(eta),
+                                     _f32(theta, "theta", n), _stream_handle(stream))
+    _check("loco_dequant_reduce_sgd", st)
+
+
+def loco_dequant_reduce_adam(codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n, bits, block_size,
+                             eta: float, beta1: float, beta2: float, delta: float, m: torch.Tensor,
+                             v: torch.Tensor, theta: torch.Tensor, stream=None) -> None:
+    """Eq. 8 fused with the Adam-family step of Eq. 10 (m, v, theta updated in place)."""
+    lib = load_library()
+    st = lib.loco_dequant_reduce_adam(_dev_ptr(codes, "codes", torch.uint8), int(code_stride_bytes),
+                                      _dev_ptr(scales, "scales", torch.float32), int(scale_stride_elems),
+                                      int(num_workers), int(n), int(bits), int(block_size), float(eta),
+                                      float(beta1), float(beta2), float(delta), _f32(m, "m", n), _f32(v, "v", n),
+                                      _f32(theta, "theta", n), _stream_handle(stream))
+    _check("loco_dequant_reduce_adam", st)
+
+
+def loco_dequant_reduce_fixed_sgd(codes, code_stride_bytes, num_workers, n, bits, log2_s, eta: float,
+                                  theta: torch.Tensor, stream=None) -> None:
+    """Eq. 8 with the global scale fused with Eq. 9."""
+    lib = load_library()
+    st = lib.loco_dequant_reduce_fixed_sgd(_dev_ptr(codes, "codes", torch.uint8), int(code_stride_bytes),
+                                           int(num_workers), int(n), int(bits), int(log2_s), float(eta),
+                                           _f32(theta, "theta", n), _stream_handle(stream))
+    _check("loco_dequant_reduce_fixed_sgd", st)
+
+
+def loco_dequant_reduce_fixed_adam(codes, code_stride_bytes, num_workers, n, bits, log2_s, eta: float, beta1: float,
+                                   beta2: float, delta: float, m: torch.Tensor, v: torch.Tensor,
+                                   theta: torch.Tensor, stream=None) -> None:
+    """Eq. 8 with the global scale fused with Eq. 10."""
+    lib = load_library()
+    st = lib.loco_dequant_reduce_fixed_adam(_dev_ptr(codes, "codes", torch.uint8), int(code_stride_bytes),
+                                            int(num_workers), int(n), int(bits), int(log2_s), float(eta),
+                                            float(beta1), float(beta2), float(delta), _f32(m, "m", n),
+                                            _f32(v, "v", n), _f32(theta, "theta", n), _stream_handle(stream))
+    _check("loco_dequant_reduce_fixed_adam", st)

@@ -108,26 +108,69 @@ bool dispatch_cq_block(int block, unsigned grid, hipStream_t s, const CqArgs& a)
     }
 }
 
-template <int BITS, int BLOCK>
-void launch_dr(unsigned grid, hipStream_t s, const uint8_t* codes, size_t cs, const float* scales,
-               size_t ss, int W, size_t n, float* out) {
-    const float inv_w = 1.0f / (float)W;
+struct DrArgs {
+    const uint8_t* codes;
+    size_t code_stride;
+    const float* scales;
+    size_t scale_stride;
+    int W;
+    size_t n;
+};
+
+template <int BITS, int BLOCK, Epilogue EPI>
+void launch_dr(unsigned grid, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
+    const float inv_w = 1.0f / (float)a.W;
     using Shape = DrShape<BITS>;
-    dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun>
-        <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(codes, cs, scales, ss, W, n, inv_w, out);
+    dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun, EPI>
+        <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.codes, a.code_stride, a.scales, a.scale_stride, a.W, a.n,
+                                                      inv_w, epi);
 }
 
-template <int BITS>
-bool dispatch_dr_block(int block, unsigned grid, hipStream_t s, const uint8_t* codes, size_t cs,
-                       const float* scales, size_t ss, int W, size_t n, float* out) {
+template <int BITS, Epilogue EPI>
+bool dispatch_dr_block(int block, unsigned grid, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
     switch (block) {
-        case 32: launch_dr<BITS, 32>(grid, s, codes, cs, scales, ss, W, n, out); return true;
-        case 64: launch_dr<BITS, 64>(grid, s, codes, cs, scales, ss, W, n, out); return true;
-        case 128: launch_dr<BITS, 128>(grid, s, codes, cs, scales, ss, W, n, out); return true;
-        case 256: launch_dr<BITS, 256>(grid, s, codes, cs, scales, ss, W, n, out); return true;
-        case 512: launch_dr<BITS, 512>(grid, s, codes, cs, scales, ss, W, n, out); return true;
+        case 32: launch_dr<BITS, 32, EPI>(grid, s, a, epi); return true;
+        case 64: launch_dr<BITS, 64, EPI>(grid, s, a, epi); return true;
+        case 128: launch_dr<BITS, 128, EPI>(grid, s, a, epi); return true;
+        case 256: launch_dr<BITS, 256, EPI>(grid, s, a, epi); return true;
+        case 512: launch_dr<BITS, 512, EPI>(grid, s, a, epi); return true;
         default: return false;
     }
+}
+
+template <Epilogue EPI>
+bool dispatch_dr(int bits, int block, unsigned grid, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
+    return bits == 4 ? dispatch_dr_block<4, EPI>(block, grid, s, a, epi)
+                     : dispatch_dr_block<8, EPI>(block, grid, s, a, epi);
+}
+
+// Checks the buffers an epilogue touches (16-byte aligned fp32 arrays of n elements, inside
+// one allocation) and its hyper-parameters.
+loco_status_t check_epilogue(Epilogue kind, const EpilogueArgs& e, size_t n) {
+    const float* arrays[4] = {e.out, e.theta, e.m, e.v};
+    const bool used[4] = {kind == Epilogue::kStore, kind != Epilogue::kStore, kind == Epilogue::kAdam,
+                          kind == Epilogue::kAdam};
+    for (int k = 0; k < 4; ++k) {
+        if (!used[k]) continue;
+        if (!arrays[k]) return LOCO_ERR_INVALID_ARG;
+        if (!aligned(arrays[k], 16)) return LOCO_ERR_ALIGNMENT;
+        if (loco_status_t st = check_device_range(arrays[k], n * sizeof(float))) return st;
+    }
+    if (kind != Epilogue::kStore && !std::isfinite(e.eta)) return LOCO_ERR_INVALID_ARG;
+    if (kind == Epilogue::kAdam) {
+        if (!(e.beta1 >= 0.0f && e.beta1 <= 1.0f) || !(e.beta2 >= 0.0f && e.beta2 <= 1.0f)) return LOCO_ERR_INVALID_ARG;
+        if (!(e.delta >= 0.0f) || std::isinf(e.delta)) return LOCO_ERR_INVALID_ARG;
+    }
+    return LOCO_OK;
+}
+
+EpilogueArgs make_epilogue(float* out, float* theta, float* m, float* v, float eta, float beta1, float beta2,
+                           float delta) {
+    EpilogueArgs e;
+    e.out = out; e.theta = theta; e.m = m; e.v = v;
+    e.eta = eta; e.beta1 = beta1; e.one_minus_beta1 = 1.0f - beta1;
+    e.beta2 = beta2; e.one_minus_beta2 = 1.0f - beta2; e.delta = delta;
+    return e;
 }
 
 // Launch shapes of the fixed-scale kernels (units of 512 elements per wavefront).
@@ -159,6 +202,85 @@ void dispatch_fixed_cq(int bits, bool pow2, unsigned grid, hipStream_t s, const 
         if (pow2) launch_fixed_cq<G, 8, true>(grid, s, grad, err8, n, k, reset, clip, codes);
         else launch_fixed_cq<G, 8, false>(grid, s, grad, err8, n, k, reset, clip, codes);
     }
+}
+
+loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const float* scales,
+                                  size_t scale_stride_elems, int num_workers, size_t n, int bits, int block_size,
+                                  Epilogue kind, const EpilogueArgs& epi, void* stream) {
+    if (bits != 4 && bits != 8) return LOCO_ERR_UNSUPPORTED;
+    if (!block_size_ok(block_size)) return LOCO_ERR_UNSUPPORTED;
+    if (num_workers < 1) return LOCO_ERR_INVALID_ARG;
+    if (n == 0) return LOCO_OK;
+    if (!codes || !scales) return LOCO_ERR_INVALID_ARG;
+    const size_t cb = loco_code_bytes(n, bits), nb = loco_num_blocks(n, block_size);
+    const size_t W = (size_t)num_workers;
+    if (W == 1) {  // strides are not used
+        code_stride_bytes = 0;
+        scale_stride_elems = 0;
+    } else {
+        if (code_stride_bytes < cb || scale_stride_elems < nb) return LOCO_ERR_INVALID_ARG;
+        if (code_stride_bytes % 16 != 0) return LOCO_ERR_ALIGNMENT;
+    }
+    if (!aligned(codes, 16) || !aligned(scales, 4)) return LOCO_ERR_ALIGNMENT;
+    if (loco_status_t st = check_device_range(codes, (W - 1) * code_stride_bytes + cb)) return st;
+    if (loco_status_t st = check_device_range(scales, ((W - 1) * scale_stride_elems + nb) * sizeof(float)))
+        return st;
+    if (loco_status_t st = check_epilogue(kind, epi, n)) return st;
+    unsigned grid;
+    const size_t per_group = bits == 4 ? (size_t)kSlot * DrShape<4>::kSlots * (DrShape<4>::kThreads / kWave)
+                                       : (size_t)kSlot * DrShape<8>::kSlots * (DrShape<8>::kThreads / kWave);
+    if (loco_status_t st = grid_for(n, per_group, &grid, kDrXcdRun ? 8 * kDrXcdRun : 1)) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const DrArgs a{codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n};
+    bool ok = false;
+    switch (kind) {
+        case Epilogue::kStore: ok = dispatch_dr<Epilogue::kStore>(bits, block_size, grid, s, a, epi); break;
+        case Epilogue::kSgd: ok = dispatch_dr<Epilogue::kSgd>(bits, block_size, grid, s, a, epi); break;
+        case Epilogue::kAdam: ok = dispatch_dr<Epilogue::kAdam>(bits, block_size, grid, s, a, epi); break;
+    }
+    if (!ok) return LOCO_ERR_UNSUPPORTED;
+    return launched();
+}
+
+template <Epilogue EPI>
+void launch_fixed_dr(int bits, unsigned grid, hipStream_t s, const uint8_t* codes, size_t cs, int W,
+                            size_t n, float inv_s, float inv_w, const EpilogueArgs& epi) {
+    if (bits == 4)
+        fixed_dr_kernel<4, FixedDrShape::kSlots, FixedDrShape::kThreads, FixedDrShape::kInFlight, kNonTemporal, EPI>
+            <<<dim3(grid), dim3(FixedDrShape::kThreads), 0, s>>>(codes, cs, W, n, inv_s, inv_w, epi);
+    else
+        fixed_dr_kernel<8, FixedDrShape::kSlots, FixedDrShape::kThreads, FixedDrShape::kInFlight, kNonTemporal, EPI>
+            <<<dim3(grid), dim3(FixedDrShape::kThreads), 0, s>>>(codes, cs, W, n, inv_s, inv_w, epi);
+}
+
+loco_status_t reduce_fixed(const uint8_t* codes, size_t code_stride_bytes, int num_workers, size_t n,
+                                  int bits, int log2_s, Epilogue kind, const EpilogueArgs& epi, void* stream) {
+    if (!fixed_args_ok(bits, log2_s, 1)) return LOCO_ERR_UNSUPPORTED;
+    if (num_workers < 1) return LOCO_ERR_INVALID_ARG;
+    if (n == 0) return LOCO_OK;
+    if (!codes) return LOCO_ERR_INVALID_ARG;
+    const size_t cb = loco_code_bytes(n, bits);
+    const size_t W = (size_t)num_workers;
+    if (W == 1) {
+        code_stride_bytes = 0;
+    } else {
+        if (code_stride_bytes < cb) return LOCO_ERR_INVALID_ARG;
+        if (code_stride_bytes % 16 != 0) return LOCO_ERR_ALIGNMENT;
+    }
+    if (!aligned(codes, 16)) return LOCO_ERR_ALIGNMENT;
+    if (loco_status_t st = check_device_range(codes, (W - 1) * code_stride_bytes + cb)) return st;
+    if (loco_status_t st = check_epilogue(kind, epi, n)) return st;
+    unsigned grid;
+    if (loco_status_t st = grid_for(n, (size_t)kSlot * FixedDrShape::kSlots * (FixedDrShape::kThreads / kWave), &grid))
+        return st;
+    const float inv_s = std::ldexp(1.0f, -log2_s), inv_w = 1.0f / (float)num_workers;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (kind) {
+        case Epilogue::kStore: launch_fixed_dr<Epilogue::kStore>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi); break;
+        case Epilogue::kSgd: launch_fixed_dr<Epilogue::kSgd>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi); break;
+        case Epilogue::kAdam: launch_fixed_dr<Epilogue::kAdam>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi); break;
+    }
+    return launched();
 }
 
 }  // namespace
@@ -248,36 +370,23 @@ loco_status_t loco_compensate_quantize(const void* grad, loco_dtype_t grad_dtype
 loco_status_t loco_dequant_reduce(const uint8_t* codes, size_t code_stride_bytes, const float* scales,
                                   size_t scale_stride_elems, int num_workers, size_t n, int bits,
                                   int block_size, float* grad_out, void* stream) {
-    if (bits != 4 && bits != 8) return LOCO_ERR_UNSUPPORTED;
-    if (!block_size_ok(block_size)) return LOCO_ERR_UNSUPPORTED;
-    if (num_workers < 1) return LOCO_ERR_INVALID_ARG;
-    if (n == 0) return LOCO_OK;
-    if (!codes || !scales || !grad_out) return LOCO_ERR_INVALID_ARG;
-    const size_t cb = loco_code_bytes(n, bits), nb = loco_num_blocks(n, block_size);
-    const size_t W = (size_t)num_workers;
-    if (W == 1) {  // strides are not used
-        code_stride_bytes = 0;
-        scale_stride_elems = 0;
-    } else {
-        if (code_stride_bytes < cb || scale_stride_elems < nb) return LOCO_ERR_INVALID_ARG;
-        if (code_stride_bytes % 16 != 0) return LOCO_ERR_ALIGNMENT;
-    }
-    if (!aligned(codes, 16) || !aligned(scales, 4) || !aligned(grad_out, 16)) return LOCO_ERR_ALIGNMENT;
-    if (loco_status_t st = check_device_range(codes, (W - 1) * code_stride_bytes + cb)) return st;
-    if (loco_status_t st = check_device_range(scales, ((W - 1) * scale_stride_elems + nb) * sizeof(float)))
-        return st;
-    if (loco_status_t st = check_device_range(grad_out, n * sizeof(float))) return st;
-    unsigned grid;
-    const size_t per_group = bits == 4 ? (size_t)kSlot * DrShape<4>::kSlots * (DrShape<4>::kThreads / kWave)
-                                       : (size_t)kSlot * DrShape<8>::kSlots * (DrShape<8>::kThreads / kWave);
-    if (loco_status_t st = grid_for(n, per_group, &grid, kDrXcdRun ? 8 * kDrXcdRun : 1)) return st;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool ok = bits == 4 ? dispatch_dr_block<4>(block_size, grid, s, codes, code_stride_bytes, scales,
-                                                    scale_stride_elems, num_workers, n, grad_out)
-                              : dispatch_dr_block<8>(block_size, grid, s, codes, code_stride_bytes, scales,
-                                                    scale_stride_elems, num_workers, n, grad_out);
-    if (!ok) return LOCO_ERR_UNSUPPORTED;
-    return launched();
+    return reduce_block(codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n, bits, block_size,
+                        Epilogue::kStore, make_epilogue(grad_out, nullptr, nullptr, nullptr, 0, 0, 0, 0), stream);
+}
+
+loco_status_t loco_dequant_reduce_sgd(const uint8_t* codes, size_t code_stride_bytes, const float* scales,
+                                      size_t scale_stride_elems, int num_workers, size_t n, int bits,
+                                      int block_size, float eta, float* theta, void* stream) {
+    return reduce_block(codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n, bits, block_size,
+                        Epilogue::kSgd, make_epilogue(nullptr, theta, nullptr, nullptr, eta, 0, 0, 0), stream);
+}
+
+loco_status_t loco_dequant_reduce_adam(const uint8_t* codes, size_t code_stride_bytes, const float* scales,
+                                       size_t scale_stride_elems, int num_workers, size_t n, int bits,
+                                       int block_size, float eta, float beta1, float beta2, float delta,
+                                       float* m, float* v, float* theta, void* stream) {
+    return reduce_block(codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n, bits, block_size,
+                        Epilogue::kAdam, make_epilogue(nullptr, theta, m, v, eta, beta1, beta2, delta), stream);
 }
 
 loco_status_t loco_stream_copy(void* dst, const void* src, size_t bytes, void* stream) {
@@ -352,35 +461,21 @@ loco_status_t loco_compensate_quantize_fixed_clip(const void* grad, loco_dtype_t
 
 loco_status_t loco_dequant_reduce_fixed(const uint8_t* codes, size_t code_stride_bytes, int num_workers,
                                         size_t n, int bits, int log2_s, float* grad_out, void* stream) {
-    if (!fixed_args_ok(bits, log2_s, 1)) return LOCO_ERR_UNSUPPORTED;
-    if (num_workers < 1) return LOCO_ERR_INVALID_ARG;
-    if (n == 0) return LOCO_OK;
-    if (!codes || !grad_out) return LOCO_ERR_INVALID_ARG;
-    const size_t cb = loco_code_bytes(n, bits);
-    const size_t W = (size_t)num_workers;
-    if (W == 1) {
-        code_stride_bytes = 0;
-    } else {
-        if (code_stride_bytes < cb) return LOCO_ERR_INVALID_ARG;
-        if (code_stride_bytes % 16 != 0) return LOCO_ERR_ALIGNMENT;
-    }
-    if (!aligned(codes, 16) || !aligned(grad_out, 16)) return LOCO_ERR_ALIGNMENT;
-    if (loco_status_t st = check_device_range(codes, (W - 1) * code_stride_bytes + cb)) return st;
-    if (loco_status_t st = check_device_range(grad_out, n * sizeof(float))) return st;
-    unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kSlot * FixedDrShape::kSlots * (FixedDrShape::kThreads / kWave), &grid))
-        return st;
-    const float inv_s = std::ldexp(1.0f, -log2_s), inv_w = 1.0f / (float)num_workers;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (bits == 4)
-        fixed_dr_kernel<4, FixedDrShape::kSlots, FixedDrShape::kThreads, FixedDrShape::kInFlight, kNonTemporal>
-            <<<dim3(grid), dim3(FixedDrShape::kThreads), 0, s>>>(codes, code_stride_bytes, num_workers, n, inv_s,
-                                                                  inv_w, grad_out);
-    else
-        fixed_dr_kernel<8, FixedDrShape::kSlots, FixedDrShape::kThreads, FixedDrShape::kInFlight, kNonTemporal>
-            <<<dim3(grid), dim3(FixedDrShape::kThreads), 0, s>>>(codes, code_stride_bytes, num_workers, n, inv_s,
-                                                                  inv_w, grad_out);
-    return launched();
+    return reduce_fixed(codes, code_stride_bytes, num_workers, n, bits, log2_s, Epilogue::kStore,
+                        make_epilogue(grad_out, nullptr, nullptr, nullptr, 0, 0, 0, 0), stream);
+}
+
+loco_status_t loco_dequant_reduce_fixed_sgd(const uint8_t* codes, size_t code_stride_bytes, int num_workers,
+                                            size_t n, int bits, int log2_s, float eta, float* theta, void* stream) {
+    return reduce_fixed(codes, code_stride_bytes, num_workers, n, bits, log2_s, Epilogue::kSgd,
+                        make_epilogue(nullptr, theta, nullptr, nullptr, eta, 0, 0, 0), stream);
+}
+
+loco_status_t loco_dequant_reduce_fixed_adam(const uint8_t* codes, size_t code_stride_bytes, int num_workers,
+                                             size_t n, int bits, int log2_s, float eta, float beta1, float beta2,
+                                             float delta, float* m, float* v, float* theta, void* stream) {
+    return reduce_fixed(codes, code_stride_bytes, num_workers, n, bits, log2_s, Epilogue::kAdam,
+                        make_epilogue(nullptr, theta, m, v, eta, beta1, beta2, delta), stream);
 }
 
 }  // extern "C"

@@ -163,10 +163,10 @@ fixed_cq_kernel(const void* __restrict__ grad, int8_t* __restrict__ err8, size_t
 // the byte sums are widened every 16 workers); 8-bit codes are biased to 0..255 and summed
 // in 16-bit halves (up to 256 workers per widening).  A lane owns 4 consecutive elements
 // per slot, as in dr_kernel, so the fp32 output is written 16 B per lane, gap-free.
-template <int BITS, int SLOTS, int THREADS, int WU, bool NT>
+template <int BITS, int SLOTS, int THREADS, int WU, bool NT, Epilogue EPI>
 __global__ void __launch_bounds__(THREADS)
 fixed_dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, int W, size_t n, float inv_s,
-                float inv_w, float* __restrict__ out) {
+                float inv_w, EpilogueArgs epi) {
     constexpr size_t TILE = (size_t)kSlot * SLOTS;
     constexpr uint32_t SLOT_CODE_BYTES = kSlot * BITS / 8;
     constexpr int FLUSH = BITS == 4 ? 16 : 256;   // workers per widening of the packed sums
@@ -178,10 +178,13 @@ fixed_dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, int W, si
         const uint8_t* cbase = codes + tile0 * BITS / 8;   // uniform, advanced per worker
         const uint32_t code_off = lane * (kQuad * BITS / 8);
         int total[SLOTS][4];
+        EpilogueState<EPI> est[SLOTS];
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s)
+        for (int s = 0; s < SLOTS; ++s) {
+            epilogue_prefetch<EPI, NT>(epi, tile0 + (size_t)s * kSlot + (size_t)lane * kQuad, est[s]);
 #pragma unroll
             for (int j = 0; j < 4; ++j) total[s][j] = 0;
+        }
         for (int w0 = 0; w0 < W; w0 += FLUSH) {
             const int wend = min(W, w0 + FLUSH);
             uint32_t lo[SLOTS], hi[SLOTS];   // packed partial sums of the biased codes
@@ -242,12 +245,10 @@ fixed_dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, int W, si
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
-            f32x4 v;
-            v.x = ((float)total[s][0] * inv_s) * inv_w;   // (sum float(q)/s) * (1/W)
-            v.y = ((float)total[s][1] * inv_s) * inv_w;
-            v.z = ((float)total[s][2] * inv_s) * inv_w;
-            v.w = ((float)total[s][3] * inv_s) * inv_w;
-            vstore<NT>(reinterpret_cast<f32x4*>(out + i), v);
+            float g[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) g[j] = ((float)total[s][j] * inv_s) * inv_w;   // (sum float(q)/s) * (1/W)
+            epilogue_finish<EPI, NT>(epi, i, g, est[s]);
         }
     } else {
 #pragma unroll 1
@@ -270,7 +271,7 @@ fixed_dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, int W, si
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (i + j < n) out[i + j] = ((float)total[j] * inv_s) * inv_w;
+                if (i + j < n) epilogue_element<EPI>(epi, i + j, ((float)total[j] * inv_s) * inv_w);
         }
     }
 }

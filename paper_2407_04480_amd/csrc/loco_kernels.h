@@ -265,6 +265,89 @@ cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, floa
     }
 }
 
+// ---- what happens to the averaged gradient g~ of Eq. 8 ----
+// kStore   write it out (Algorithm 1 step 3 as such);
+// kSgd     Eq. 9:   theta' = theta - eta g~
+// kAdam    Eq. 10:  m' = (1-b1) m + b1 g~;  v' = (1-b2) v + b2 g~^2;
+//                   theta' = theta - (eta / sqrt(v' + delta)) m'
+// Fusing the optimizer into the reduce saves writing g~ and reading it back (8 B/element).
+// The optimizer state of a quad is fetched before the decode loop so its latency is hidden.
+enum class Epilogue { kStore, kSgd, kAdam };
+
+struct EpilogueArgs {
+    float* out;                  // kStore
+    float* theta;                // kSgd, kAdam (in place)
+    float* m;                    // kAdam (in place)
+    float* v;                    // kAdam (in place)
+    float eta, beta1, one_minus_beta1, beta2, one_minus_beta2, delta;
+};
+
+template <Epilogue E> struct EpilogueState { f32x4 theta, m, v; };
+
+template <Epilogue E, bool NT>
+__device__ __forceinline__ void epilogue_prefetch(const EpilogueArgs& a, size_t i, EpilogueState<E>& st) {
+    if constexpr (E != Epilogue::kStore) st.theta = vload<NT>(reinterpret_cast<const f32x4*>(a.theta + i));
+    if constexpr (E == Epilogue::kAdam) {
+        st.m = vload<NT>(reinterpret_cast<const f32x4*>(a.m + i));
+        st.v = vload<NT>(reinterpret_cast<const f32x4*>(a.v + i));
+    }
+}
+
+// One element of the optimizer step; g is the averaged gradient.
+template <Epilogue E>
+__device__ __forceinline__ void optimizer_element(const EpilogueArgs& a, float g, float& theta, float& m, float& v) {
+    if constexpr (E == Epilogue::kSgd) {
+        const float step = a.eta * g;
+        theta = theta - step;
+    } else if constexpr (E == Epilogue::kAdam) {
+        const float b1g = a.beta1 * g;
+        m = __builtin_fmaf(a.one_minus_beta1, m, b1g);
+        const float g2 = g * g;
+        const float b2g2 = a.beta2 * g2;
+        v = __builtin_fmaf(a.one_minus_beta2, v, b2g2);
+        const float root = sqrtf(v + a.delta);      // correctly rounded (see the build flags)
+        const float eta_k = a.eta / root;
+        const float step = eta_k * m;
+        theta = theta - step;
+    }
+}
+
+template <Epilogue E, bool NT>
+__device__ __forceinline__ void epilogue_finish(const EpilogueArgs& a, size_t i, const float (&g)[4],
+                                                EpilogueState<E>& st) {
+    if constexpr (E == Epilogue::kStore) {
+        vstore<NT>(reinterpret_cast<f32x4*>(a.out + i), f32x4{g[0], g[1], g[2], g[3]});
+    } else {
+        float th[4] = {st.theta.x, st.theta.y, st.theta.z, st.theta.w};
+        float m[4] = {0.f, 0.f, 0.f, 0.f}, v[4] = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (E == Epilogue::kAdam) {
+            m[0] = st.m.x; m[1] = st.m.y; m[2] = st.m.z; m[3] = st.m.w;
+            v[0] = st.v.x; v[1] = st.v.y; v[2] = st.v.z; v[3] = st.v.w;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) optimizer_element<E>(a, g[j], th[j], m[j], v[j]);
+        vstore<NT>(reinterpret_cast<f32x4*>(a.theta + i), f32x4{th[0], th[1], th[2], th[3]});
+        if constexpr (E == Epilogue::kAdam) {
+            vstore<NT>(reinterpret_cast<f32x4*>(a.m + i), f32x4{m[0], m[1], m[2], m[3]});
+            vstore<NT>(reinterpret_cast<f32x4*>(a.v + i), f32x4{v[0], v[1], v[2], v[3]});
+        }
+    }
+}
+
+// Guarded (element-by-element) form for the last, partial tile.
+template <Epilogue E>
+__device__ __forceinline__ void epilogue_element(const EpilogueArgs& a, size_t i, float g) {
+    if constexpr (E == Epilogue::kStore) {
+        a.out[i] = g;
+    } else {
+        float th = a.theta[i], m = 0.f, v = 0.f;
+        if constexpr (E == Epilogue::kAdam) { m = a.m[i]; v = a.v[i]; }
+        optimizer_element<E>(a, g, th, m, v);
+        a.theta[i] = th;
+        if constexpr (E == Epilogue::kAdam) { a.m[i] = m; a.v[i] = v; }
+    }
+}
+
 // ---- Algorithm 1 step 3 / Eq. 8 ----
 // One worker's contribution to one quad: acc_j = acc_j + (float) q_j * D, j = 0..3, where c
 // holds the quad's codes in its low 16 (4-bit) or 32 (8-bit) bits.
@@ -315,10 +398,10 @@ constexpr uint32_t kBigStepBits = 0x7B800000u;  // 2^120 as a binary32 bit patte
 // are a wavefront-uniform base (SGPRs, advanced per worker on the scalar unit) plus a
 // 32-bit lane offset; with BLOCK >= 256 a slot lies in one block, so its step is a scalar
 // load shared by the wavefront.
-template <int BITS, int BLOCK, int SLOTS, int THREADS, int WU, bool NT, int XCDK>
+template <int BITS, int BLOCK, int SLOTS, int THREADS, int WU, bool NT, int XCDK, Epilogue EPI>
 __global__ void __launch_bounds__(THREADS)
 dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const float* __restrict__ scales,
-          size_t scale_stride, int W, size_t n, float inv_w, float* __restrict__ out) {
+          size_t scale_stride, int W, size_t n, float inv_w, EpilogueArgs epi) {
     constexpr size_t TILE = (size_t)kSlot * SLOTS;
     constexpr bool UNIFORM_STEP = BLOCK >= kSlot;
     constexpr uint32_t SLOT_CODE_BYTES = kSlot * BITS / 8;
@@ -333,10 +416,13 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const float* __
         const uint32_t code_off = lane * (kQuad * BITS / 8);
         const uint32_t step_off = UNIFORM_STEP ? 0u : lane / (uint32_t)(BLOCK / kQuad);
         float acc[SLOTS][4];
+        EpilogueState<EPI> est[SLOTS];
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s)
+        for (int s = 0; s < SLOTS; ++s) {
+            epilogue_prefetch<EPI, NT>(epi, tile0 + (size_t)s * kSlot + (size_t)lane * kQuad, est[s]);
 #pragma unroll
             for (int j = 0; j < 4; ++j) acc[s][j] = 0.0f;
+        }
 
         auto load_chunk = [&](int count, uint32_t (&c)[WU][SLOTS], float (&D)[WU][SLOTS]) {
 #pragma unroll
@@ -400,8 +486,8 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const float* __
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
-            vstore<NT>(reinterpret_cast<f32x4*>(out + i),
-                       f32x4{acc[s][0] * inv_w, acc[s][1] * inv_w, acc[s][2] * inv_w, acc[s][3] * inv_w});
+            const float g[4] = {acc[s][0] * inv_w, acc[s][1] * inv_w, acc[s][2] * inv_w, acc[s][3] * inv_w};
+            epilogue_finish<EPI, NT>(epi, i, g, est[s]);
         }
     } else {
 #pragma unroll 1
@@ -425,7 +511,7 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const float* __
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (i + j < n) out[i + j] = acc[j] * inv_w;
+                if (i + j < n) epilogue_element<EPI>(epi, i + j, acc[j] * inv_w);
         }
     }
 }

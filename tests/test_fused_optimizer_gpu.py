@@ -1,0 +1,104 @@
+"""Eq. 8 fused with the optimizer steps of Eq. 9 (SGD) and Eq. 10 (Adam family), both
+payload forms: the GPU call must equal the oracle's reduce followed by the oracle's
+optimizer step, over several steps (theta, m, v evolve in place)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2407_04480_amd import (loco_dequant_reduce_adam, loco_dequant_reduce_fixed_adam,
+                                  loco_dequant_reduce_fixed_sgd, loco_dequant_reduce_sgd)
+from paper_2407_04480_amd.binding import LocoError
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+ETA, B1, B2, DL = 3e-4, 0.1, 0.02, 1e-8      # Sec. 4: beta1 = 0.1, beta2 in [0.001, 0.05] are "typical"
+
+
+def block_payloads(rs, W, n, bits, B, pad=3):
+    cb, nb = oracle.code_bytes(n, bits), oracle.num_blocks(n, B)
+    cstride, sstride = (cb + 15) // 16 * 16, nb + pad
+    codes = np.zeros(W * cstride, np.uint8)
+    scales = np.zeros(W * sstride, np.float32)
+    for k in range(W):
+        g = (rs.standard_t(3, n) * 1e-3).astype(np.float32)
+        c, s = oracle.compensate_quantize(g, np.zeros(n, np.float32), bits, B, 0.25)
+        codes[k * cstride:k * cstride + cb] = c
+        scales[k * sstride:k * sstride + nb] = s
+    return codes, cstride, scales, sstride
+
+
+def same(name, got_t, want):
+    got = got_t.cpu().numpy()
+    top = float(np.abs(want).max())
+    assert float(np.abs(got.astype(np.float64) - want).max()) <= 1e-6 * top, name
+    assert np.array_equal(got, want), f"{name}: {np.count_nonzero(got != want)} of {want.size} differ"
+
+
+@pytest.mark.parametrize("bits,B,W", [(4, 256, 8), (8, 64, 3), (4, 32, 1), (4, 512, 16)])
+@pytest.mark.parametrize("n", [6 * 2048 + 777, 9, 2048])
+def test_block_reduce_with_sgd_and_adam(bits, B, W, n):
+    rs = np.random.default_rng(bits * B + W + n)
+    th0 = rs.standard_normal(n).astype(np.float32)
+    th_sgd_h, th_adam_h = th0.copy(), th0.copy()
+    m_h, v_h = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    th_sgd, th_adam = torch.from_numpy(th0).to(DEV), torch.from_numpy(th0).to(DEV)
+    m_t, v_t = torch.zeros(n, device=DEV), torch.zeros(n, device=DEV)
+    for step in range(3):
+        codes, cstride, scales, sstride = block_payloads(rs, W, n, bits, B)
+        c_t, s_t = torch.from_numpy(codes).to(DEV), torch.from_numpy(scales).to(DEV)
+        loco_dequant_reduce_sgd(c_t, cstride, s_t, sstride, W, n, bits, B, ETA, th_sgd)
+        loco_dequant_reduce_adam(c_t, cstride, s_t, sstride, W, n, bits, B, ETA, B1, B2, DL, m_t, v_t, th_adam)
+        torch.cuda.synchronize()
+        g_avg = oracle.dequant_reduce(codes, scales, W, n, bits, B, cstride, sstride)
+        oracle.sgd_update(th_sgd_h, g_avg, ETA)
+        oracle.adam_update(th_adam_h, m_h, v_h, g_avg, ETA, B1, B2, DL)
+        same(f"sgd theta step {step}", th_sgd, th_sgd_h)
+        same(f"adam m step {step}", m_t, m_h)
+        same(f"adam v step {step}", v_t, v_h)
+        same(f"adam theta step {step}", th_adam, th_adam_h)
+    assert np.abs(th_adam_h - th0).max() > 1e-4
+
+
+@pytest.mark.parametrize("bits,W", [(4, 8), (8, 5), (4, 33)])
+def test_fixed_reduce_with_sgd_and_adam(bits, W):
+    n, log2_s = 5 * 1024 + 301, 19
+    rs = np.random.default_rng(bits + W)
+    cb = oracle.code_bytes(n, bits)
+    stride = (cb + 15) // 16 * 16
+    th0 = rs.standard_normal(n).astype(np.float32)
+    th_sgd_h, th_adam_h = th0.copy(), th0.copy()
+    m_h, v_h = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    th_sgd, th_adam = torch.from_numpy(th0).to(DEV), torch.from_numpy(th0).to(DEV)
+    m_t, v_t = torch.zeros(n, device=DEV), torch.zeros(n, device=DEV)
+    for step in range(3):
+        codes = rs.integers(0, 256, W * stride, dtype=np.uint8)
+        c_t = torch.from_numpy(codes).to(DEV)
+        loco_dequant_reduce_fixed_sgd(c_t, stride, W, n, bits, log2_s, ETA, th_sgd)
+        loco_dequant_reduce_fixed_adam(c_t, stride, W, n, bits, log2_s, ETA, B1, B2, 1e-16 if step == 1 else DL, m_t, v_t, th_adam)
+        torch.cuda.synchronize()
+        g_avg = oracle.fixed_dequant_reduce(codes, W, n, bits, log2_s, code_stride_bytes=stride)
+        oracle.sgd_update(th_sgd_h, g_avg, ETA)
+        oracle.adam_update(th_adam_h, m_h, v_h, g_avg, ETA, B1, B2, 1e-16 if step == 1 else DL)
+        same(f"sgd theta step {step}", th_sgd, th_sgd_h)
+        same(f"adam m step {step}", m_t, m_h)
+        same(f"adam v step {step}", v_t, v_h)
+        same(f"adam theta step {step}", th_adam, th_adam_h)
+
+
+def test_fused_optimizer_argument_errors():
+    n = 4096
+    codes = torch.zeros(n // 2, dtype=torch.uint8, device=DEV)
+    scales = torch.ones(n // 256, device=DEV)
+    th, m, v = torch.zeros(n, device=DEV), torch.zeros(n, device=DEV), torch.zeros(n, device=DEV)
+    for kw in (dict(beta1=1.5), dict(beta2=-0.1), dict(delta=-1.0), dict(eta=float("nan")), dict(delta=float("inf"))):
+        a = dict(eta=ETA, beta1=B1, beta2=B2, delta=DL)
+        a.update(kw)
+        with pytest.raises(LocoError) as ei:
+            loco_dequant_reduce_adam(codes, 0, scales, 0, 1, n, 4, 256, a["eta"], a["beta1"], a["beta2"], a["delta"], m, v, th)
+        assert ei.value.status == 1
+    with pytest.raises(LocoError) as ei:
+        loco_dequant_reduce_sgd(codes, 0, scales, 0, 1, n, 4, 256, ETA, torch.zeros(n + 4, device=DEV)[1:])
+    assert ei.value.status == 3
+    torch.cuda.synchronize()
+    assert not th.any()
