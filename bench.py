@@ -51,6 +51,8 @@ def parse_args():
     ap.add_argument("--form", choices=["block", "fixed"], default="block",
                     help="block: per-block scales, fp32 error state (the headline path); fixed: Algorithm 1 as "
                          "printed, global scale s = 2^19 and 8-bit error state with s_e = 4s")
+    ap.add_argument("--optimizer", choices=["none", "sgd", "adam"], default="none",
+                    help="fuse the optimizer step of Eq. 9 / Eq. 10 into the reduce (theta, m, v fp32 in place)")
     ap.add_argument("--no-copy-ceiling", action="store_true")
     return ap.parse_args()
 
@@ -127,8 +129,10 @@ def main():
     import torch
 
     from paper_2407_04480_amd import (loco_code_bytes, loco_compensate_quantize, loco_compensate_quantize_fixed,
-                                      loco_dequant_reduce, loco_dequant_reduce_fixed, loco_error_state8_init,
-                                      loco_error_state_init, loco_num_blocks, workloads)
+                                      loco_dequant_reduce, loco_dequant_reduce_adam, loco_dequant_reduce_fixed,
+                                      loco_dequant_reduce_fixed_adam, loco_dequant_reduce_fixed_sgd,
+                                      loco_dequant_reduce_sgd, loco_error_state8_init, loco_error_state_init,
+                                      loco_num_blocks, workloads)
     from paper_2407_04480_amd.binding import loco_stream_copy
 
     if not torch.cuda.is_available():
@@ -146,6 +150,11 @@ def main():
     else:  # gradient + 8-bit state in and out + codes; W payloads of codes + fp32 out
         bytes_cq, bytes_dr = gsz + 1 + 1 + bits / 8.0, W * bits / 8.0 + 4
         names = ("loco_compensate_quantize_fixed", "loco_dequant_reduce_fixed")
+    opt = args.optimizer
+    if opt != "none":   # g~ is not written; theta (and m, v) are read and written in place
+        bytes_dr += {"sgd": 8, "adam": 24}[opt] - 4
+        names = (names[0], names[1] + "_" + opt)
+    ETA, BETA1, BETA2, DELTA = 1e-4, 0.1, 0.02, 1e-8   # Sec. 4 calls beta1 = 0.1, beta2 in [0.001, 0.05] typical
 
     # ---- resident inputs: two own gradients (used alternately), W-1 peers' payloads ----
     grads = [workloads.gradient(w, s, device=dev) for s in range(2)]
@@ -154,7 +163,10 @@ def main():
     recv_codes = torch.zeros(W * cstride, dtype=torch.uint8, device=dev)
     recv_scales = torch.zeros(W * nb, dtype=torch.float32, device=dev)
     own_codes, own_scales = recv_codes[:cb], recv_scales[:nb]
-    out = torch.empty(n, dtype=torch.float32, device=dev)
+    out = torch.empty(n, dtype=torch.float32, device=dev) if opt == "none" else None
+    theta = torch.randn(n, dtype=torch.float32, device=dev) if opt != "none" else None
+    mom = torch.zeros(n, dtype=torch.float32, device=dev) if opt == "adam" else None
+    var = torch.zeros(n, dtype=torch.float32, device=dev) if opt == "adam" else None
     stream = torch.cuda.current_stream()
 
     if form == "block":
@@ -165,7 +177,13 @@ def main():
             loco_compensate_quantize(g, e, bits, B, w.beta, False, codes, scales, stream)
 
         def dr():
-            loco_dequant_reduce(recv_codes, cstride, recv_scales, nb, W, n, bits, B, out, stream)
+            if opt == "none":
+                loco_dequant_reduce(recv_codes, cstride, recv_scales, nb, W, n, bits, B, out, stream)
+            elif opt == "sgd":
+                loco_dequant_reduce_sgd(recv_codes, cstride, recv_scales, nb, W, n, bits, B, ETA, theta, stream)
+            else:
+                loco_dequant_reduce_adam(recv_codes, cstride, recv_scales, nb, W, n, bits, B, ETA, BETA1, BETA2,
+                                         DELTA, mom, var, theta, stream)
         err = torch.empty(n, dtype=torch.float32, device=dev)
     else:
         def state_init(e):
@@ -175,7 +193,13 @@ def main():
             loco_compensate_quantize_fixed(g, e, bits, FIXED_LOG2_S, FIXED_SE_MULT, w.beta, False, codes, stream)
 
         def dr():
-            loco_dequant_reduce_fixed(recv_codes, cstride, W, n, bits, FIXED_LOG2_S, out, stream)
+            if opt == "none":
+                loco_dequant_reduce_fixed(recv_codes, cstride, W, n, bits, FIXED_LOG2_S, out, stream)
+            elif opt == "sgd":
+                loco_dequant_reduce_fixed_sgd(recv_codes, cstride, W, n, bits, FIXED_LOG2_S, ETA, theta, stream)
+            else:
+                loco_dequant_reduce_fixed_adam(recv_codes, cstride, W, n, bits, FIXED_LOG2_S, ETA, BETA1, BETA2,
+                                               DELTA, mom, var, theta, stream)
         err = torch.empty(n, dtype=torch.int8, device=dev)
     state_init(err)
     tmp_err = torch.empty_like(err)
@@ -246,7 +270,7 @@ def main():
         del src, dst
 
     cpu = None
-    if args.cpu_sample > 0:
+    if args.cpu_sample > 0 and opt == "none":
         # own payload for the sample: one compensate-quantize step from a zero state
         state_init(err)
         cq(grads[0], err, own_codes, own_scales)
@@ -267,7 +291,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "n": n, "grad_dtype": str(w.grad_dtype).replace("torch.", ""),
-                   "bits": bits, "beta": w.beta, "num_workers": W, "form": form,
+                   "bits": bits, "beta": w.beta, "num_workers": W, "form": form, "optimizer": opt,
                    **({"block_size": B} if form == "block" else
                       {"log2_s": FIXED_LOG2_S, "se_mult": FIXED_SE_MULT, "state": "int8"}),
                    "step": " + ".join(n_[5:] for n_ in names)},

@@ -7,6 +7,7 @@
 
 #include <atomic>
 #include <cmath>
+#include <type_traits>
 
 namespace {
 
@@ -117,10 +118,14 @@ struct DrArgs {
     size_t n;
 };
 
+// With Adam's three in-place fp32 streams one slot per wavefront and 256 threads measured best.
+template <int BITS, Epilogue EPI>
+using DrShapeFor = std::conditional_t<EPI == Epilogue::kAdam, DrShape<8>, DrShape<BITS>>;
+
 template <int BITS, int BLOCK, Epilogue EPI>
 void launch_dr(unsigned grid, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
     const float inv_w = 1.0f / (float)a.W;
-    using Shape = DrShape<BITS>;
+    using Shape = DrShapeFor<BITS, EPI>;
     dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun, EPI>
         <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.codes, a.code_stride, a.scales, a.scale_stride, a.W, a.n,
                                                       inv_w, epi);
@@ -227,8 +232,9 @@ loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const
         return st;
     if (loco_status_t st = check_epilogue(kind, epi, n)) return st;
     unsigned grid;
-    const size_t per_group = bits == 4 ? (size_t)kSlot * DrShape<4>::kSlots * (DrShape<4>::kThreads / kWave)
-                                       : (size_t)kSlot * DrShape<8>::kSlots * (DrShape<8>::kThreads / kWave);
+    const bool wide = bits == 8 || kind == Epilogue::kAdam;   // see DrShapeFor
+    const size_t per_group = wide ? (size_t)kSlot * DrShape<8>::kSlots * (DrShape<8>::kThreads / kWave)
+                                  : (size_t)kSlot * DrShape<4>::kSlots * (DrShape<4>::kThreads / kWave);
     if (loco_status_t st = grid_for(n, per_group, &grid, kDrXcdRun ? 8 * kDrXcdRun : 1)) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const DrArgs a{codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n};
