@@ -53,6 +53,8 @@ def parse_args():
                          "printed, global scale s = 2^19 and 8-bit error state with s_e = 4s")
     ap.add_argument("--optimizer", choices=["none", "sgd", "adam"], default="none",
                     help="fuse the optimizer step of Eq. 9 / Eq. 10 into the reduce (theta, m, v fp32 in place)")
+    ap.add_argument("--out", choices=["f32", "bf16"], default="f32",
+                    help="type the averaged gradient is written in (bf16: rounded to nearest even)")
     ap.add_argument("--no-copy-ceiling", action="store_true")
     return ap.parse_args()
 
@@ -129,7 +131,8 @@ def main():
     import torch
 
     from paper_2407_04480_amd import (loco_code_bytes, loco_compensate_quantize, loco_compensate_quantize_fixed,
-                                      loco_dequant_reduce, loco_dequant_reduce_adam, loco_dequant_reduce_fixed,
+                                      loco_dequant_reduce, loco_dequant_reduce_adam, loco_dequant_reduce_bf16,
+                                      loco_dequant_reduce_fixed, loco_dequant_reduce_fixed_bf16,
                                       loco_dequant_reduce_fixed_adam, loco_dequant_reduce_fixed_sgd,
                                       loco_dequant_reduce_sgd, loco_error_state8_init, loco_error_state_init,
                                       loco_num_blocks, workloads)
@@ -154,6 +157,12 @@ def main():
     if opt != "none":   # g~ is not written; theta (and m, v) are read and written in place
         bytes_dr += {"sgd": 8, "adam": 24}[opt] - 4
         names = (names[0], names[1] + "_" + opt)
+    if args.out == "bf16":
+        if opt != "none":
+            print("bench.py: --out bf16 has no meaning with a fused optimizer", file=sys.stderr)
+            return 2
+        bytes_dr -= 2
+        names = (names[0], names[1] + "_bf16")
     ETA, BETA1, BETA2, DELTA = 1e-4, 0.1, 0.02, 1e-8   # Sec. 4 calls beta1 = 0.1, beta2 in [0.001, 0.05] typical
 
     # ---- resident inputs: two own gradients (used alternately), W-1 peers' payloads ----
@@ -163,7 +172,8 @@ def main():
     recv_codes = torch.zeros(W * cstride, dtype=torch.uint8, device=dev)
     recv_scales = torch.zeros(W * nb, dtype=torch.float32, device=dev)
     own_codes, own_scales = recv_codes[:cb], recv_scales[:nb]
-    out = torch.empty(n, dtype=torch.float32, device=dev) if opt == "none" else None
+    out = torch.empty(n, dtype=torch.float32 if args.out == "f32" else torch.bfloat16, device=dev) \
+        if opt == "none" else None
     theta = torch.randn(n, dtype=torch.float32, device=dev) if opt != "none" else None
     mom = torch.zeros(n, dtype=torch.float32, device=dev) if opt == "adam" else None
     var = torch.zeros(n, dtype=torch.float32, device=dev) if opt == "adam" else None
@@ -177,7 +187,9 @@ def main():
             loco_compensate_quantize(g, e, bits, B, w.beta, False, codes, scales, stream)
 
         def dr():
-            if opt == "none":
+            if opt == "none" and args.out == "bf16":
+                loco_dequant_reduce_bf16(recv_codes, cstride, recv_scales, nb, W, n, bits, B, out, stream)
+            elif opt == "none":
                 loco_dequant_reduce(recv_codes, cstride, recv_scales, nb, W, n, bits, B, out, stream)
             elif opt == "sgd":
                 loco_dequant_reduce_sgd(recv_codes, cstride, recv_scales, nb, W, n, bits, B, ETA, theta, stream)
@@ -193,7 +205,9 @@ def main():
             loco_compensate_quantize_fixed(g, e, bits, FIXED_LOG2_S, FIXED_SE_MULT, w.beta, False, codes, stream)
 
         def dr():
-            if opt == "none":
+            if opt == "none" and args.out == "bf16":
+                loco_dequant_reduce_fixed_bf16(recv_codes, cstride, W, n, bits, FIXED_LOG2_S, out, stream)
+            elif opt == "none":
                 loco_dequant_reduce_fixed(recv_codes, cstride, W, n, bits, FIXED_LOG2_S, out, stream)
             elif opt == "sgd":
                 loco_dequant_reduce_fixed_sgd(recv_codes, cstride, W, n, bits, FIXED_LOG2_S, ETA, theta, stream)
@@ -270,7 +284,7 @@ def main():
         del src, dst
 
     cpu = None
-    if args.cpu_sample > 0 and opt == "none":
+    if args.cpu_sample > 0 and opt == "none" and args.out == "f32":
         # own payload for the sample: one compensate-quantize step from a zero state
         state_init(err)
         cq(grads[0], err, own_codes, own_scales)
@@ -291,7 +305,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "n": n, "grad_dtype": str(w.grad_dtype).replace("torch.", ""),
-                   "bits": bits, "beta": w.beta, "num_workers": W, "form": form, "optimizer": opt,
+                   "bits": bits, "beta": w.beta, "num_workers": W, "form": form, "optimizer": opt, "out": args.out,
                    **({"block_size": B} if form == "block" else
                       {"log2_s": FIXED_LOG2_S, "se_mult": FIXED_SE_MULT, "state": "int8"}),
                    "step": " + ".join(n_[5:] for n_ in names)},

@@ -204,6 +204,18 @@ loco_status_t loco_dequant_reduce_fixed_adam(const uint8_t *codes, size_t code_s
                                              void *stream);
 
 /*
+ * Eq. 8 with the averaged gradient handed on in bf16 (the paper trains in bf16, App. B.2):
+ * the fp32 average rounded to the nearest bf16, ties to even; 2 bytes per element written
+ * instead of 4.  grad_out_bf16: [n] bf16 bit patterns, device, 16-byte aligned.
+ */
+loco_status_t loco_dequant_reduce_bf16(const uint8_t *codes, size_t code_stride_bytes, const float *scales,
+                                       size_t scale_stride_elems, int num_workers, size_t n, int bits,
+                                       int block_size, uint16_t *grad_out_bf16, void *stream);
+loco_status_t loco_dequant_reduce_fixed_bf16(const uint8_t *codes, size_t code_stride_bytes, int num_workers,
+                                             size_t n, int bits, int log2_s, uint16_t *grad_out_bf16,
+                                             void *stream);
+
+/*
  * Measurement aid, not part of the method: dst[i] = src[i] for `bytes` bytes
  * (a multiple of 16, both pointers 16-byte aligned) with the same load/store
  * shape as the kernels above.  Gives the practical HBM ceiling and the scale

@@ -60,6 +60,8 @@ def _bind(lib):
     lib.loco_ref_fixed_dequant_reduce.argtypes = [vp, sz, i, sz, i, i, vp]
     lib.loco_ref_fixed_dequant_reduce_mt.argtypes = [vp, sz, i, sz, i, i, vp, i]
     lib.loco_ref_clip_gradient.argtypes = [vp, i, sz, f, vp]
+    lib.loco_ref_round_to_bf16.argtypes = [vp, sz, vp]
+    lib.loco_ref_round_to_bf16.restype = c.c_int
     lib.loco_ref_sgd_update.argtypes = [vp, vp, sz, f]
     lib.loco_ref_adam_update.argtypes = [vp, vp, vp, vp, sz, f, f, f, f]
     for name in (
@@ -240,3 +242,14 @@ def adam_update(theta, m, v, g_avg, eta, beta1, beta2, delta, lib=None):
                                   float(beta1), float(beta2), float(delta))
     if rc:
         raise ValueError("loco_ref_adam_update: status %d" % rc)
+
+
+def round_to_bf16(x, lib=None):
+    """float32 -> bf16 bit patterns (uint16), round to nearest, ties to even."""
+    lib = lib or load()
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.size, dtype=np.uint16)
+    rc = lib.loco_ref_round_to_bf16(_ptr(x), x.size, _ptr(out))
+    if rc:
+        raise ValueError("loco_ref_round_to_bf16: status %d" % rc)
+    return out

@@ -392,3 +392,26 @@ int loco_ref_adam_update(float *theta, float *m, float *v, const float *g_avg, s
     }
     return LOCO_REF_OK;
 }
+
+/* ------------------------------------------------------------------------------------
+ * Averaged gradient handed on in bf16 (the paper trains in bf16, App. B.2): the fp32
+ * result of Eq. 8 rounded to the nearest bf16, ties to even.  bf16 is the upper half of
+ * a binary32, so rounding adds half an ulp of the kept part (0x7FFF plus the lowest kept
+ * bit) and truncates; NaN stays NaN.
+ * ---------------------------------------------------------------------------------- */
+int loco_ref_round_to_bf16(const float *in, size_t n, uint16_t *out)
+{
+    if (n && (!in || !out))
+        return LOCO_REF_BAD_ARG;
+    for (size_t i = 0; i < n; ++i) {
+        uint32_t u;
+        memcpy(&u, &in[i], sizeof u);
+        if ((u & 0x7FFFFFFFu) > 0x7F800000u) { /* NaN: keep it one */
+            out[i] = (uint16_t)((u >> 16) | 0x0040u);
+            continue;
+        }
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        out[i] = (uint16_t)(u >> 16);
+    }
+    return LOCO_REF_OK;
+}

@@ -23,6 +23,8 @@ from .binding import (  # noqa: F401
     loco_dequant_reduce_adam,
     loco_dequant_reduce_fixed_sgd,
     loco_dequant_reduce_fixed_adam,
+    loco_dequant_reduce_bf16,
+    loco_dequant_reduce_fixed_bf16,
 )
 
 __all__ = [
@@ -43,4 +45,6 @@ __all__ = [
     "loco_dequant_reduce_adam",
     "loco_dequant_reduce_fixed_sgd",
     "loco_dequant_reduce_fixed_adam",
+    "loco_dequant_reduce_bf16",
+    "loco_dequant_reduce_fixed_bf16",
 ]

@@ -39,6 +39,8 @@ EXPORTS = (
     "loco_dequant_reduce_adam",
     "loco_dequant_reduce_fixed_sgd",
     "loco_dequant_reduce_fixed_adam",
+    "loco_dequant_reduce_bf16",
+    "loco_dequant_reduce_fixed_bf16",
 )
 
 _lib = None
@@ -90,6 +92,10 @@ def load_library(path: Optional[str] = None):
     lib.loco_dequant_reduce_adam.argtypes = [vp, sz, vp, sz, i, sz, i, i, f, f, f, f, vp, vp, vp, vp]
     lib.loco_dequant_reduce_fixed_sgd.argtypes = [vp, sz, i, sz, i, i, f, vp, vp]
     lib.loco_dequant_reduce_fixed_adam.argtypes = [vp, sz, i, sz, i, i, f, f, f, f, vp, vp, vp, vp]
+    lib.loco_dequant_reduce_bf16.argtypes = [vp, sz, vp, sz, i, sz, i, i, vp, vp]
+    lib.loco_dequant_reduce_bf16.restype = i
+    lib.loco_dequant_reduce_fixed_bf16.argtypes = [vp, sz, i, sz, i, i, vp, vp]
+    lib.loco_dequant_reduce_fixed_bf16.restype = i
     for _n in ("loco_dequant_reduce_sgd", "loco_dequant_reduce_adam", "loco_dequant_reduce_fixed_sgd",
                "loco_dequant_reduce_fixed_adam"):
         getattr(lib, _n).restype = i
@@ -330,3 +336,30 @@ def loco_dequant_reduce_fixed_adam(codes, code_stride_bytes, num_workers, n, bit
                                             float(beta1), float(beta2), float(delta), _f32(m, "m", n),
                                             _f32(v, "v", n), _f32(theta, "theta", n), _stream_handle(stream))
     _check("loco_dequant_reduce_fixed_adam", st)
+
+
+def loco_dequant_reduce_bf16(codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n, bits, block_size,
+                             grad_out: torch.Tensor, stream=None) -> None:
+    """Eq. 8 with the result rounded to bf16 (grad_out: torch.bfloat16)."""
+    lib = load_library()
+    po = _dev_ptr(grad_out, "grad_out", torch.bfloat16)
+    if grad_out.numel() < n:
+        raise ValueError("grad_out too small")
+    st = lib.loco_dequant_reduce_bf16(_dev_ptr(codes, "codes", torch.uint8), int(code_stride_bytes),
+                                      _dev_ptr(scales, "scales", torch.float32), int(scale_stride_elems),
+                                      int(num_workers), int(n), int(bits), int(block_size), po,
+                                      _stream_handle(stream))
+    _check("loco_dequant_reduce_bf16", st)
+
+
+def loco_dequant_reduce_fixed_bf16(codes, code_stride_bytes, num_workers, n, bits, log2_s, grad_out: torch.Tensor,
+                                   stream=None) -> None:
+    """Eq. 8 with the global scale, result rounded to bf16."""
+    lib = load_library()
+    po = _dev_ptr(grad_out, "grad_out", torch.bfloat16)
+    if grad_out.numel() < n:
+        raise ValueError("grad_out too small")
+    st = lib.loco_dequant_reduce_fixed_bf16(_dev_ptr(codes, "codes", torch.uint8), int(code_stride_bytes),
+                                            int(num_workers), int(n), int(bits), int(log2_s), po,
+                                            _stream_handle(stream))
+    _check("loco_dequant_reduce_fixed_bf16", st)

@@ -153,15 +153,16 @@ bool dispatch_dr(int bits, int block, unsigned grid, hipStream_t s, const DrArgs
 // one allocation) and its hyper-parameters.
 loco_status_t check_epilogue(Epilogue kind, const EpilogueArgs& e, size_t n) {
     const float* arrays[4] = {e.out, e.theta, e.m, e.v};
-    const bool used[4] = {kind == Epilogue::kStore, kind != Epilogue::kStore, kind == Epilogue::kAdam,
-                          kind == Epilogue::kAdam};
+    const bool stores = kind == Epilogue::kStore || kind == Epilogue::kStoreBf16;
+    const bool used[4] = {stores, !stores, kind == Epilogue::kAdam, kind == Epilogue::kAdam};
     for (int k = 0; k < 4; ++k) {
         if (!used[k]) continue;
         if (!arrays[k]) return LOCO_ERR_INVALID_ARG;
         if (!aligned(arrays[k], 16)) return LOCO_ERR_ALIGNMENT;
-        if (loco_status_t st = check_device_range(arrays[k], n * sizeof(float))) return st;
+        const size_t esz = kind == Epilogue::kStoreBf16 ? 2 : sizeof(float);
+        if (loco_status_t st = check_device_range(arrays[k], n * esz)) return st;
     }
-    if (kind != Epilogue::kStore && !std::isfinite(e.eta)) return LOCO_ERR_INVALID_ARG;
+    if (!stores && !std::isfinite(e.eta)) return LOCO_ERR_INVALID_ARG;
     if (kind == Epilogue::kAdam) {
         if (!(e.beta1 >= 0.0f && e.beta1 <= 1.0f) || !(e.beta2 >= 0.0f && e.beta2 <= 1.0f)) return LOCO_ERR_INVALID_ARG;
         if (!(e.delta >= 0.0f) || std::isinf(e.delta)) return LOCO_ERR_INVALID_ARG;
@@ -241,6 +242,7 @@ loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const
     bool ok = false;
     switch (kind) {
         case Epilogue::kStore: ok = dispatch_dr<Epilogue::kStore>(bits, block_size, grid, s, a, epi); break;
+        case Epilogue::kStoreBf16: ok = dispatch_dr<Epilogue::kStoreBf16>(bits, block_size, grid, s, a, epi); break;
         case Epilogue::kSgd: ok = dispatch_dr<Epilogue::kSgd>(bits, block_size, grid, s, a, epi); break;
         case Epilogue::kAdam: ok = dispatch_dr<Epilogue::kAdam>(bits, block_size, grid, s, a, epi); break;
     }
@@ -283,6 +285,7 @@ loco_status_t reduce_fixed(const uint8_t* codes, size_t code_stride_bytes, int n
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (kind) {
         case Epilogue::kStore: launch_fixed_dr<Epilogue::kStore>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi); break;
+        case Epilogue::kStoreBf16: launch_fixed_dr<Epilogue::kStoreBf16>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi); break;
         case Epilogue::kSgd: launch_fixed_dr<Epilogue::kSgd>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi); break;
         case Epilogue::kAdam: launch_fixed_dr<Epilogue::kAdam>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi); break;
     }
@@ -380,6 +383,15 @@ loco_status_t loco_dequant_reduce(const uint8_t* codes, size_t code_stride_bytes
                         Epilogue::kStore, make_epilogue(grad_out, nullptr, nullptr, nullptr, 0, 0, 0, 0), stream);
 }
 
+loco_status_t loco_dequant_reduce_bf16(const uint8_t* codes, size_t code_stride_bytes, const float* scales,
+                                       size_t scale_stride_elems, int num_workers, size_t n, int bits,
+                                       int block_size, uint16_t* grad_out_bf16, void* stream) {
+    return reduce_block(codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n, bits, block_size,
+                        Epilogue::kStoreBf16,
+                        make_epilogue(reinterpret_cast<float*>(grad_out_bf16), nullptr, nullptr, nullptr, 0, 0, 0, 0),
+                        stream);
+}
+
 loco_status_t loco_dequant_reduce_sgd(const uint8_t* codes, size_t code_stride_bytes, const float* scales,
                                       size_t scale_stride_elems, int num_workers, size_t n, int bits,
                                       int block_size, float eta, float* theta, void* stream) {
@@ -469,6 +481,14 @@ loco_status_t loco_dequant_reduce_fixed(const uint8_t* codes, size_t code_stride
                                         size_t n, int bits, int log2_s, float* grad_out, void* stream) {
     return reduce_fixed(codes, code_stride_bytes, num_workers, n, bits, log2_s, Epilogue::kStore,
                         make_epilogue(grad_out, nullptr, nullptr, nullptr, 0, 0, 0, 0), stream);
+}
+
+loco_status_t loco_dequant_reduce_fixed_bf16(const uint8_t* codes, size_t code_stride_bytes, int num_workers,
+                                             size_t n, int bits, int log2_s, uint16_t* grad_out_bf16,
+                                             void* stream) {
+    return reduce_fixed(codes, code_stride_bytes, num_workers, n, bits, log2_s, Epilogue::kStoreBf16,
+                        make_epilogue(reinterpret_cast<float*>(grad_out_bf16), nullptr, nullptr, nullptr, 0, 0, 0, 0),
+                        stream);
 }
 
 loco_status_t loco_dequant_reduce_fixed_sgd(const uint8_t* codes, size_t code_stride_bytes, int num_workers,

@@ -266,16 +266,17 @@ cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, floa
 }
 
 // ---- what happens to the averaged gradient g~ of Eq. 8 ----
-// kStore   write it out (Algorithm 1 step 3 as such);
+// kStore   write it out in fp32 (Algorithm 1 step 3 as such);
+// kStoreBf16  write it out rounded to bf16 (nearest, ties to even), 2 B/element instead of 4;
 // kSgd     Eq. 9:   theta' = theta - eta g~
 // kAdam    Eq. 10:  m' = (1-b1) m + b1 g~;  v' = (1-b2) v + b2 g~^2;
 //                   theta' = theta - (eta / sqrt(v' + delta)) m'
 // Fusing the optimizer into the reduce saves writing g~ and reading it back (8 B/element).
 // The optimizer state of a quad is fetched before the decode loop so its latency is hidden.
-enum class Epilogue { kStore, kSgd, kAdam };
+enum class Epilogue { kStore, kStoreBf16, kSgd, kAdam };
 
 struct EpilogueArgs {
-    float* out;                  // kStore
+    float* out;                  // kStore (fp32), kStoreBf16 (the same pointer, holding bf16)
     float* theta;                // kSgd, kAdam (in place)
     float* m;                    // kAdam (in place)
     float* v;                    // kAdam (in place)
@@ -284,9 +285,16 @@ struct EpilogueArgs {
 
 template <Epilogue E> struct EpilogueState { f32x4 theta, m, v; };
 
+// fp32 -> bf16, nearest with ties to even (the hardware conversion of gfx950); NaN stays NaN.
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
+    const __bf16 b = (__bf16)x;
+    return __builtin_bit_cast(uint16_t, b);
+}
+
 template <Epilogue E, bool NT>
 __device__ __forceinline__ void epilogue_prefetch(const EpilogueArgs& a, size_t i, EpilogueState<E>& st) {
-    if constexpr (E != Epilogue::kStore) st.theta = vload<NT>(reinterpret_cast<const f32x4*>(a.theta + i));
+    if constexpr (E == Epilogue::kSgd || E == Epilogue::kAdam)
+        st.theta = vload<NT>(reinterpret_cast<const f32x4*>(a.theta + i));
     if constexpr (E == Epilogue::kAdam) {
         st.m = vload<NT>(reinterpret_cast<const f32x4*>(a.m + i));
         st.v = vload<NT>(reinterpret_cast<const f32x4*>(a.v + i));
@@ -317,6 +325,10 @@ __device__ __forceinline__ void epilogue_finish(const EpilogueArgs& a, size_t i,
                                                 EpilogueState<E>& st) {
     if constexpr (E == Epilogue::kStore) {
         vstore<NT>(reinterpret_cast<f32x4*>(a.out + i), f32x4{g[0], g[1], g[2], g[3]});
+    } else if constexpr (E == Epilogue::kStoreBf16) {
+        const uint32_t lo = (uint32_t)f32_to_bf16_bits(g[0]) | ((uint32_t)f32_to_bf16_bits(g[1]) << 16);
+        const uint32_t hi = (uint32_t)f32_to_bf16_bits(g[2]) | ((uint32_t)f32_to_bf16_bits(g[3]) << 16);
+        vstore<NT>(reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(a.out) + i), u32x2{lo, hi});
     } else {
         float th[4] = {st.theta.x, st.theta.y, st.theta.z, st.theta.w};
         float m[4] = {0.f, 0.f, 0.f, 0.f}, v[4] = {0.f, 0.f, 0.f, 0.f};
@@ -339,6 +351,8 @@ template <Epilogue E>
 __device__ __forceinline__ void epilogue_element(const EpilogueArgs& a, size_t i, float g) {
     if constexpr (E == Epilogue::kStore) {
         a.out[i] = g;
+    } else if constexpr (E == Epilogue::kStoreBf16) {
+        reinterpret_cast<uint16_t*>(a.out)[i] = f32_to_bf16_bits(g);
     } else {
         float th = a.theta[i], m = 0.f, v = 0.f;
         if constexpr (E == Epilogue::kAdam) { m = a.m[i]; v = a.v[i]; }

@@ -758,7 +758,36 @@ def check_optimizer_steps(lib):
     assert np.all(np.sign(th1 - th) == np.sign(m))
 
 
+def check_round_to_bf16(lib):
+    """fp32 -> bf16, ties to even: the result is one of the two neighbouring bf16 values, the
+    nearer one, the even one at an exact tie; bf16 inputs come back unchanged; and the whole
+    map agrees with torch's own conversion on every exponent and on random bits."""
+    import torch
+    rng = np.random.default_rng(89)
+    bits = np.concatenate([rng.integers(0, 2 ** 32, 200000, dtype=np.uint64).astype(np.uint32),
+                           (np.arange(0, 256, dtype=np.uint32) << 23) | 0x00008000,      # exact ties, even below
+                           (np.arange(0, 256, dtype=np.uint32) << 23) | 0x00018000,      # exact ties, odd below
+                           (np.arange(0, 256, dtype=np.uint32) << 23) | 0x00007FFF,
+                           (np.arange(0, 256, dtype=np.uint32) << 23) | 0x00008001,
+                           np.array([0, 0x80000000, 0x7F7FFFFF, 0xFF7FFFFF, 0x7F800000, 0x00000001], np.uint32)])
+    x = bits.view(np.float32)
+    x = x[np.isfinite(x) | np.isinf(x)]
+    got = oracle.round_to_bf16(x, lib=lib)
+    want = torch.from_numpy(x.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, want)
+    back = bf16_bits_to_f32(got).astype(np.float64)
+    fin = np.isfinite(back) & np.isfinite(x)
+    lo = bf16_bits_to_f32((x.view(np.uint32) >> 16).astype(np.uint16)).astype(np.float64)   # truncation
+    assert np.all(np.abs(back[fin] - x[fin]) <= np.abs(x[fin] - lo[fin]) + 0.0)              # never worse than truncating
+    tie = (x.view(np.uint32) & 0xFFFF) == 0x8000
+    assert np.all((got[tie & fin] & 1) == 0)                                                  # ties land on even
+    exact = (x.view(np.uint32) & 0xFFFF) == 0
+    assert np.array_equal(got[exact], (x.view(np.uint32)[exact] >> 16).astype(np.uint16))
+    assert np.all(np.isnan(bf16_bits_to_f32(oracle.round_to_bf16(np.array([np.nan, -np.nan], np.float32), lib=lib))))
+
+
 FIXED_CHECKS = [
+    check_round_to_bf16,
     check_clip,
     check_optimizer_steps,
     check_fixed_worked_example,

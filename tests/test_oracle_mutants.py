@@ -63,6 +63,8 @@ MUTANTS = [
     ("adam_uses_old_v", "float root = sqrtf(v_new + delta);", "float root = sqrtf(v[i] + delta);"),
     ("adam_uses_gradient_not_momentum", "float step = eta_k * m_new;", "float step = eta_k * g;"),
     ("adam_v_not_stored", "        v[i] = v_new;\n", ""),
+    ("bf16_truncates", "u += 0x7FFFu + ((u >> 16) & 1u);", ""),
+    ("bf16_ties_away", "u += 0x7FFFu + ((u >> 16) & 1u);", "u += 0x8000u;"),
     ("fixed_reduce_stride", "int q = code_at(codes + (size_t)w * code_stride_bytes, bits, i);\n            float d = (float)q / s;",
      "int q = code_at(codes, bits, i);\n            float d = (float)q / s;"),
 ]
