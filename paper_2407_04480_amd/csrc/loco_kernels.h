@@ -60,7 +60,7 @@ __device__ __forceinline__ float clip_grad(float g, float c) {
 // Operands are bit patterns of non-negative floats, which order like unsigned ints.
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_move(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
 }
 template <int LANES>
 __device__ __forceinline__ uint32_t group_max_u32(uint32_t v, int lane) {
