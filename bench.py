@@ -121,6 +121,13 @@ def cpu_baseline(form, w, grads, recv_codes, cstride, recv_scales, nb_full, samp
     }
 
 
+def device_report(info):
+    """The device's own figures and the HBM peak they imply (two transfers per memory clock)."""
+    info = dict(info)
+    info["derived_hbm_peak_GBps"] = 2.0 * info["memory_clock_khz"] * 1e3 * info["memory_bus_bits"] / 8 / 1e9
+    return info
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -136,7 +143,7 @@ def main():
                                       loco_dequant_reduce_fixed_adam, loco_dequant_reduce_fixed_sgd,
                                       loco_dequant_reduce_sgd, loco_error_state8_init, loco_error_state_init,
                                       loco_num_blocks, workloads)
-    from paper_2407_04480_amd.binding import loco_stream_copy
+    from paper_2407_04480_amd.binding import loco_stream_copy, loco_device_info
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; there is no CPU path.", file=sys.stderr)
@@ -315,6 +322,7 @@ def main():
         | {"kernel": dominant["kernel"]},
         "kernels": [k_cq, k_dr],
         "copy_ceiling_GBps": copy_gbps,
+        "device": device_report(loco_device_info()),
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))

@@ -223,6 +223,17 @@ loco_status_t loco_dequant_reduce_fixed_bf16(const uint8_t *codes, size_t code_s
  */
 loco_status_t loco_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/*
+ * Measurement aid, not part of the method: what the current device reports
+ * about itself, for deriving the HBM peak (2 transfers per memory clock x bus
+ * width / 8) beside the published figure.  Each pointer may be NULL; values
+ * are written to host memory: memory clock in kHz, memory bus width in bits,
+ * number of compute units, engine clock in kHz.  LOCO_ERR_LAUNCH if the
+ * runtime cannot answer.
+ */
+loco_status_t loco_device_info(int *memory_clock_khz, int *memory_bus_bits, int *compute_units,
+                               int *engine_clock_khz);
+
 #ifdef __cplusplus
 }
 #endif

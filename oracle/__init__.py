@@ -59,6 +59,10 @@ def _bind(lib):
     lib.loco_ref_fixed_compensate_quantize_mt.argtypes = [vp, i, vp, sz, i, i, i, f, i, vp, i]
     lib.loco_ref_fixed_dequant_reduce.argtypes = [vp, sz, i, sz, i, i, vp]
     lib.loco_ref_fixed_dequant_reduce_mt.argtypes = [vp, sz, i, sz, i, i, vp, i]
+    lib.loco_ref_compensate_quantize_bf16_scales.argtypes = [vp, i, vp, sz, i, i, f, i, vp, vp]
+    lib.loco_ref_compensate_quantize_bf16_scales_mt.argtypes = [vp, i, vp, sz, i, i, f, i, vp, vp, i]
+    lib.loco_ref_dequant_reduce_bf16_scales.argtypes = [vp, sz, vp, sz, i, sz, i, i, vp]
+    lib.loco_ref_dequant_reduce_bf16_scales_mt.argtypes = [vp, sz, vp, sz, i, sz, i, i, vp, i]
     lib.loco_ref_clip_gradient.argtypes = [vp, i, sz, f, vp]
     lib.loco_ref_round_to_bf16.argtypes = [vp, sz, vp]
     lib.loco_ref_round_to_bf16.restype = c.c_int
@@ -78,6 +82,10 @@ def _bind(lib):
         "loco_ref_compensate_quantize_mt",
         "loco_ref_dequant_reduce",
         "loco_ref_dequant_reduce_mt",
+        "loco_ref_compensate_quantize_bf16_scales",
+        "loco_ref_compensate_quantize_bf16_scales_mt",
+        "loco_ref_dequant_reduce_bf16_scales",
+        "loco_ref_dequant_reduce_bf16_scales_mt",
     ):
         getattr(lib, name).restype = c.c_int
     return lib
@@ -122,10 +130,12 @@ def error_state_init(err_state: np.ndarray, lib=None) -> None:
         raise ValueError("loco_ref_error_state_init: status %d" % rc)
 
 
-def compensate_quantize(grad, err_state, bits, block_size, beta, reset=0, threads=1, lib=None):
+def compensate_quantize(grad, err_state, bits, block_size, beta, reset=0, threads=1, lib=None,
+                        bf16_scales=False):
     """Alg. 1 steps 1-2.  err_state (float32) is updated in place.
 
-    Returns (codes uint8[ceil(n*bits/8)], scales float32[ceil(n/block_size)]).
+    Returns (codes uint8[ceil(n*bits/8)], scales float32[ceil(n/block_size)]); with
+    bf16_scales the steps are rounded to bf16 before use and returned as uint16 bit patterns.
     """
     lib = lib or load()
     grad = np.ascontiguousarray(grad)
@@ -133,13 +143,15 @@ def compensate_quantize(grad, err_state, bits, block_size, beta, reset=0, thread
     n = grad.size
     assert err_state.size == n
     codes = np.zeros(code_bytes(n, bits), dtype=np.uint8)
-    scales = np.zeros(num_blocks(n, block_size) if block_size >= 1 else 0, dtype=np.float32)
+    scales = np.zeros(num_blocks(n, block_size) if block_size >= 1 else 0,
+                      dtype=np.uint16 if bf16_scales else np.float32)
     args = [_ptr(grad), _grad_dtype(grad), _ptr(err_state), n, bits, block_size,
             float(beta), int(reset), _ptr(codes), _ptr(scales)]
+    suffix = "_bf16_scales" if bf16_scales else ""
     if threads > 1:
-        rc = lib.loco_ref_compensate_quantize_mt(*args, int(threads))
+        rc = getattr(lib, "loco_ref_compensate_quantize%s_mt" % suffix)(*args, int(threads))
     else:
-        rc = lib.loco_ref_compensate_quantize(*args)
+        rc = getattr(lib, "loco_ref_compensate_quantize" + suffix)(*args)
     if rc:
         raise ValueError("loco_ref_compensate_quantize: status %d" % rc)
     return codes, scales
@@ -149,12 +161,13 @@ def dequant_reduce(codes, scales, num_workers, n, bits, block_size,
                    code_stride_bytes=None, scale_stride_elems=None, threads=1, lib=None):
     """Alg. 1 step 3 / Eq. 8.  codes/scales hold num_workers payloads at the given strides.
 
-    Returns the averaged gradient, float32[n].
+    scales is float32, or uint16 holding bf16 steps.  Returns the averaged gradient, float32[n].
     """
     lib = lib or load()
     codes = np.ascontiguousarray(codes).reshape(-1)
     scales = np.ascontiguousarray(scales).reshape(-1)
-    assert codes.dtype == np.uint8 and scales.dtype == np.float32
+    assert codes.dtype == np.uint8 and scales.dtype in (np.float32, np.uint16)
+    suffix = "_bf16_scales" if scales.dtype == np.uint16 else ""
     if code_stride_bytes is None:
         code_stride_bytes = code_bytes(n, bits)
     if scale_stride_elems is None:
@@ -166,9 +179,9 @@ def dequant_reduce(codes, scales, num_workers, n, bits, block_size,
     args = [_ptr(codes), code_stride_bytes, _ptr(scales), scale_stride_elems,
             int(num_workers), n, bits, block_size, _ptr(out)]
     if threads > 1:
-        rc = lib.loco_ref_dequant_reduce_mt(*args, int(threads))
+        rc = getattr(lib, "loco_ref_dequant_reduce%s_mt" % suffix)(*args, int(threads))
     else:
-        rc = lib.loco_ref_dequant_reduce(*args)
+        rc = getattr(lib, "loco_ref_dequant_reduce" + suffix)(*args)
     if rc:
         raise ValueError("loco_ref_dequant_reduce: status %d" % rc)
     return out

@@ -84,16 +84,19 @@ int loco_ref_error_state_init(float *err_state, size_t n)
  * Blocks are independent, so any split into block ranges gives the same bytes;
  * with 4-bit codes a range must start at an even element index.
  */
-int loco_ref_compensate_quantize_blocks(const void *grad, int grad_dtype, float *err_state,
-                                        size_t n, int bits, int block_size, float beta, int reset,
-                                        uint8_t *codes_out, float *scales_out,
-                                        size_t block_lo, size_t block_hi)
+static uint16_t bf16_nearest_even(float x);
+
+/* scales_out (binary32 steps) or scales16_out (bf16 steps): exactly one is given. */
+static int cq_blocks(const void *grad, int grad_dtype, float *err_state,
+                     size_t n, int bits, int block_size, float beta, int reset,
+                     uint8_t *codes_out, float *scales_out, uint16_t *scales16_out,
+                     size_t block_lo, size_t block_hi)
 {
     if (!args_ok(n, bits, block_size) || !(beta >= 0.0f && beta <= 1.0f))
         return LOCO_REF_BAD_ARG;
     if (grad_dtype != LOCO_REF_F32 && grad_dtype != LOCO_REF_BF16)
         return LOCO_REF_BAD_ARG;
-    if (n && (!grad || !err_state || !codes_out || !scales_out))
+    if (n && (!grad || !err_state || !codes_out || (!scales_out == !scales16_out)))
         return LOCO_REF_BAD_ARG;
 
     const int qmax = (1 << (bits - 1)) - 1; /* Eq. 1: range -2^(p-1) .. 2^(p-1)-1 */
@@ -117,13 +120,24 @@ int loco_ref_compensate_quantize_blocks(const void *grad, int grad_dtype, float 
         }
 
         float D = amax / (float)qmax; /* the step 1/s_b */
+        uint16_t D16 = 0;
+        if (scales16_out) {           /* step kept in bf16: round it first, then use */
+            D16 = bf16_nearest_even(D); /* the rounded value for everything below    */
+            uint32_t wide = (uint32_t)D16 << 16;
+            memcpy(&D, &wide, sizeof D);
+        }
         float r = 0.0f;               /* s_b */
         int dead = D < FLT_MIN;       /* zero or subnormal step: nothing to encode */
-        if (dead)
+        if (dead) {
             D = 0.0f;
-        else
+            D16 = 0;
+        } else {
             r = 1.0f / D;
-        scales_out[b] = D;
+        }
+        if (scales16_out)
+            scales16_out[b] = D16;
+        else
+            scales_out[b] = D;
 
         for (size_t i = lo; i < hi; ++i) {
             float e = err_state[i];
@@ -153,6 +167,46 @@ int loco_ref_compensate_quantize_blocks(const void *grad, int grad_dtype, float 
     return LOCO_REF_OK;
 }
 
+int loco_ref_compensate_quantize_blocks(const void *grad, int grad_dtype, float *err_state,
+                                        size_t n, int bits, int block_size, float beta, int reset,
+                                        uint8_t *codes_out, float *scales_out,
+                                        size_t block_lo, size_t block_hi)
+{
+    return cq_blocks(grad, grad_dtype, err_state, n, bits, block_size, beta, reset, codes_out,
+                     scales_out, 0, block_lo, block_hi);
+}
+
+/*
+ * The same with the block steps stored in bf16 (2 bytes per block instead of 4).
+ * D_b = max|h| / qmax is rounded to the nearest bf16 (ties to even) BEFORE it is
+ * used: the compressor multiplies by 1 / D_b of the rounded step and the sender's
+ * own decompressor uses the rounded step too, so sender and receivers still decode
+ * with one and the same D_b (the premise of Lemma 1).  Rounding can shrink the step
+ * by at most 2^-8 relative, so max|h| / D_b <= qmax / (1 - 2^-8) < qmax + 1/2 for
+ * qmax <= 127: the largest element still rounds to qmax, nothing saturates.
+ * The zero/subnormal test is made on the rounded step.
+ */
+int loco_ref_compensate_quantize_bf16_scales_blocks(const void *grad, int grad_dtype,
+                                                    float *err_state, size_t n, int bits,
+                                                    int block_size, float beta, int reset,
+                                                    uint8_t *codes_out, uint16_t *scales16_out,
+                                                    size_t block_lo, size_t block_hi)
+{
+    return cq_blocks(grad, grad_dtype, err_state, n, bits, block_size, beta, reset, codes_out,
+                     0, scales16_out, block_lo, block_hi);
+}
+
+int loco_ref_compensate_quantize_bf16_scales(const void *grad, int grad_dtype, float *err_state,
+                                             size_t n, int bits, int block_size, float beta,
+                                             int reset, uint8_t *codes_out, uint16_t *scales16_out)
+{
+    if (!args_ok(n, bits, block_size))
+        return LOCO_REF_BAD_ARG;
+    size_t nb = (n + (size_t)block_size - 1) / (size_t)block_size;
+    return cq_blocks(grad, grad_dtype, err_state, n, bits, block_size, beta, reset, codes_out,
+                     0, scales16_out, 0, nb);
+}
+
 /* Alg. 1 steps 1-2 on a whole shard; err_state is read and overwritten. */
 int loco_ref_compensate_quantize(const void *grad, int grad_dtype, float *err_state, size_t n,
                                  int bits, int block_size, float beta, int reset,
@@ -178,14 +232,14 @@ static int code_at(const uint8_t *codes, int bits, size_t i)
  * payload with that worker's block step and average in binary32.  Payload w is
  * codes + w*code_stride_bytes, scales + w*scale_stride_elems.
  */
-int loco_ref_dequant_reduce_range(const uint8_t *codes, size_t code_stride_bytes,
-                                  const float *scales, size_t scale_stride_elems,
-                                  int num_workers, size_t n, int bits, int block_size,
-                                  float *grad_out, size_t elem_lo, size_t elem_hi)
+static int dr_range(const uint8_t *codes, size_t code_stride_bytes,
+                    const float *scales, const uint16_t *scales16, size_t scale_stride_elems,
+                    int num_workers, size_t n, int bits, int block_size,
+                    float *grad_out, size_t elem_lo, size_t elem_hi)
 {
     if (!args_ok(n, bits, block_size) || num_workers < 1)
         return LOCO_REF_BAD_ARG;
-    if (n && (!codes || !scales || !grad_out))
+    if (n && (!codes || (!scales == !scales16) || !grad_out))
         return LOCO_REF_BAD_ARG;
     if (elem_hi > n)
         elem_hi = n;
@@ -195,13 +249,47 @@ int loco_ref_dequant_reduce_range(const uint8_t *codes, size_t code_stride_bytes
         float acc = 0.0f;
         for (int w = 0; w < num_workers; ++w) {
             int q = code_at(codes + (size_t)w * code_stride_bytes, bits, i);
-            float D = scales[(size_t)w * scale_stride_elems + b];
+            float D;
+            if (scales16) { /* bf16 step: widening is exact */
+                uint32_t wide = (uint32_t)scales16[(size_t)w * scale_stride_elems + b] << 16;
+                memcpy(&D, &wide, sizeof D);
+            } else {
+                D = scales[(size_t)w * scale_stride_elems + b];
+            }
             float d = (float)q * D;
             acc = acc + d;
         }
         grad_out[i] = acc * inv;
     }
     return LOCO_REF_OK;
+}
+
+int loco_ref_dequant_reduce_range(const uint8_t *codes, size_t code_stride_bytes,
+                                  const float *scales, size_t scale_stride_elems,
+                                  int num_workers, size_t n, int bits, int block_size,
+                                  float *grad_out, size_t elem_lo, size_t elem_hi)
+{
+    return dr_range(codes, code_stride_bytes, scales, 0, scale_stride_elems, num_workers, n, bits,
+                    block_size, grad_out, elem_lo, elem_hi);
+}
+
+/* Eq. 8 over payloads whose block steps are bf16 (see the bf16-step compressor above). */
+int loco_ref_dequant_reduce_bf16_scales_range(const uint8_t *codes, size_t code_stride_bytes,
+                                              const uint16_t *scales16, size_t scale_stride_elems,
+                                              int num_workers, size_t n, int bits, int block_size,
+                                              float *grad_out, size_t elem_lo, size_t elem_hi)
+{
+    return dr_range(codes, code_stride_bytes, 0, scales16, scale_stride_elems, num_workers, n, bits,
+                    block_size, grad_out, elem_lo, elem_hi);
+}
+
+int loco_ref_dequant_reduce_bf16_scales(const uint8_t *codes, size_t code_stride_bytes,
+                                        const uint16_t *scales16, size_t scale_stride_elems,
+                                        int num_workers, size_t n, int bits, int block_size,
+                                        float *grad_out)
+{
+    return dr_range(codes, code_stride_bytes, 0, scales16, scale_stride_elems, num_workers, n, bits,
+                    block_size, grad_out, 0, n);
 }
 
 int loco_ref_dequant_reduce(const uint8_t *codes, size_t code_stride_bytes, const float *scales,
@@ -399,19 +487,21 @@ int loco_ref_adam_update(float *theta, float *m, float *v, const float *g_avg, s
  * a binary32, so rounding adds half an ulp of the kept part (0x7FFF plus the lowest kept
  * bit) and truncates; NaN stays NaN.
  * ---------------------------------------------------------------------------------- */
+static uint16_t bf16_nearest_even(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, sizeof u);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) /* NaN: keep it one */
+        return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
 int loco_ref_round_to_bf16(const float *in, size_t n, uint16_t *out)
 {
     if (n && (!in || !out))
         return LOCO_REF_BAD_ARG;
-    for (size_t i = 0; i < n; ++i) {
-        uint32_t u;
-        memcpy(&u, &in[i], sizeof u);
-        if ((u & 0x7FFFFFFFu) > 0x7F800000u) { /* NaN: keep it one */
-            out[i] = (uint16_t)((u >> 16) | 0x0040u);
-            continue;
-        }
-        u += 0x7FFFu + ((u >> 16) & 1u);
-        out[i] = (uint16_t)(u >> 16);
-    }
+    for (size_t i = 0; i < n; ++i)
+        out[i] = bf16_nearest_even(in[i]);
     return LOCO_REF_OK;
 }

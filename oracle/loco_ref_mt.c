@@ -14,6 +14,10 @@ int loco_ref_compensate_quantize_blocks(const void *, int, float *, size_t, int,
                                         uint8_t *, float *, size_t, size_t);
 int loco_ref_dequant_reduce_range(const uint8_t *, size_t, const float *, size_t, int, size_t, int,
                                   int, float *, size_t, size_t);
+int loco_ref_compensate_quantize_bf16_scales_blocks(const void *, int, float *, size_t, int, int, float,
+                                                    int, uint8_t *, uint16_t *, size_t, size_t);
+int loco_ref_dequant_reduce_bf16_scales_range(const uint8_t *, size_t, const uint16_t *, size_t, int,
+                                              size_t, int, int, float *, size_t, size_t);
 int loco_ref_fixed_compensate_quantize_range(const void *, int, int8_t *, size_t, int, int, int, float,
                                              int, uint8_t *, size_t, size_t);
 int loco_ref_fixed_dequant_reduce_range(const uint8_t *, size_t, int, size_t, int, int, float *, size_t,
@@ -22,7 +26,10 @@ int loco_ref_fixed_dequant_reduce_range(const uint8_t *, size_t, int, size_t, in
 #define LOCO_REF_MAX_THREADS 256
 
 typedef struct {
-    int kind; /* 0 = compensate_quantize, 1 = dequant_reduce, 2 and 3 = their fixed-scale forms */
+    int kind; /* 0 = compensate_quantize, 1 = dequant_reduce, 2 and 3 = their fixed-scale forms,
+                 4 and 5 = their forms with bf16 block steps */
+    uint16_t *scales16_out;
+    const uint16_t *scales16;
     int8_t *err_state8;
     int log2_s, se_mult;
     const void *grad;
@@ -59,6 +66,16 @@ static void *run_job(void *p)
         j->status = loco_ref_fixed_compensate_quantize_range(j->grad, j->grad_dtype, j->err_state8, j->n,
                                                              j->bits, j->log2_s, j->se_mult, j->beta,
                                                              j->reset, j->codes_out, j->lo, j->hi);
+    else if (j->kind == 4)
+        j->status = loco_ref_compensate_quantize_bf16_scales_blocks(j->grad, j->grad_dtype, j->err_state,
+                                                                    j->n, j->bits, j->block_size, j->beta,
+                                                                    j->reset, j->codes_out,
+                                                                    j->scales16_out, j->lo, j->hi);
+    else if (j->kind == 5)
+        j->status = loco_ref_dequant_reduce_bf16_scales_range(j->codes, j->code_stride, j->scales16,
+                                                              j->scale_stride, j->num_workers, j->n,
+                                                              j->bits, j->block_size, j->grad_out, j->lo,
+                                                              j->hi);
     else
         j->status = loco_ref_fixed_dequant_reduce_range(j->codes, j->code_stride, j->num_workers, j->n,
                                                         j->bits, j->log2_s, j->grad_out, j->lo, j->hi);
@@ -173,6 +190,48 @@ int loco_ref_fixed_dequant_reduce_mt(const uint8_t *codes, size_t code_stride_by
     j.n = n;
     j.bits = bits;
     j.log2_s = log2_s;
+    j.grad_out = grad_out;
+    return run_split(&j, n, 64, threads);
+}
+
+int loco_ref_compensate_quantize_bf16_scales_mt(const void *grad, int grad_dtype, float *err_state,
+                                                size_t n, int bits, int block_size, float beta,
+                                                int reset, uint8_t *codes_out, uint16_t *scales16_out,
+                                                int threads)
+{
+    if (block_size < 1)
+        return 1;
+    job_t j = {0};
+    j.kind = 4;
+    j.grad = grad;
+    j.grad_dtype = grad_dtype;
+    j.err_state = err_state;
+    j.n = n;
+    j.bits = bits;
+    j.block_size = block_size;
+    j.beta = beta;
+    j.reset = reset;
+    j.codes_out = codes_out;
+    j.scales16_out = scales16_out;
+    size_t nb = (n + (size_t)block_size - 1) / (size_t)block_size;
+    return run_split(&j, nb, 2, threads);
+}
+
+int loco_ref_dequant_reduce_bf16_scales_mt(const uint8_t *codes, size_t code_stride_bytes,
+                                           const uint16_t *scales16, size_t scale_stride_elems,
+                                           int num_workers, size_t n, int bits, int block_size,
+                                           float *grad_out, int threads)
+{
+    job_t j = {0};
+    j.kind = 5;
+    j.codes = codes;
+    j.code_stride = code_stride_bytes;
+    j.scales16 = scales16;
+    j.scale_stride = scale_stride_elems;
+    j.num_workers = num_workers;
+    j.n = n;
+    j.bits = bits;
+    j.block_size = block_size;
     j.grad_out = grad_out;
     return run_split(&j, n, 64, threads);
 }

@@ -25,6 +25,8 @@ from .binding import (  # noqa: F401
     loco_dequant_reduce_fixed_adam,
     loco_dequant_reduce_bf16,
     loco_dequant_reduce_fixed_bf16,
+    loco_stream_copy,
+    loco_device_info,
 )
 
 __all__ = [
@@ -47,4 +49,6 @@ __all__ = [
     "loco_dequant_reduce_fixed_adam",
     "loco_dequant_reduce_bf16",
     "loco_dequant_reduce_fixed_bf16",
+    "loco_stream_copy",
+    "loco_device_info",
 ]

@@ -29,6 +29,7 @@ EXPORTS = (
     "loco_compensate_quantize",
     "loco_dequant_reduce",
     "loco_stream_copy",
+    "loco_device_info",
     "loco_reset_due",
     "loco_error_state8_init",
     "loco_compensate_quantize_fixed",
@@ -78,6 +79,8 @@ def load_library(path: Optional[str] = None):
     lib.loco_dequant_reduce.argtypes = [vp, sz, vp, sz, i, sz, i, i, vp, vp]
     lib.loco_dequant_reduce.restype = i
     lib.loco_stream_copy.argtypes, lib.loco_stream_copy.restype = [vp, vp, sz, vp], i
+    ip = ctypes.POINTER(ctypes.c_int)
+    lib.loco_device_info.argtypes, lib.loco_device_info.restype = [ip, ip, ip, ip], i
     lib.loco_reset_due.argtypes, lib.loco_reset_due.restype = [c.c_longlong, c.c_longlong], i
     lib.loco_error_state8_init.argtypes, lib.loco_error_state8_init.restype = [vp, sz, vp], i
     lib.loco_compensate_quantize_fixed.argtypes = [vp, i, vp, sz, i, i, i, f, i, vp, vp]
@@ -224,6 +227,16 @@ def loco_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
         raise ValueError("dst too small")
     st = lib.loco_stream_copy(_dev_ptr(dst, "dst"), _dev_ptr(src, "src"), nbytes, _stream_handle(stream))
     _check("loco_stream_copy", st)
+
+
+def loco_device_info() -> dict:
+    """What the current device reports: memory clock, bus width, unit count (measurement aid)."""
+    lib = load_library()
+    vals = [ctypes.c_int(0) for _ in range(4)]
+    st = lib.loco_device_info(*[ctypes.byref(v) for v in vals])
+    _check("loco_device_info", st)
+    keys = ("memory_clock_khz", "memory_bus_bits", "compute_units", "engine_clock_khz")
+    return {k: v.value for k, v in zip(keys, vals)}
 
 
 def loco_reset_due(step_index: int, reset_period: int) -> bool:

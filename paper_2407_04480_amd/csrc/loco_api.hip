@@ -421,6 +421,23 @@ loco_status_t loco_stream_copy(void* dst, const void* src, size_t bytes, void* s
     return launched();
 }
 
+loco_status_t loco_device_info(int* memory_clock_khz, int* memory_bus_bits, int* compute_units,
+                               int* engine_clock_khz) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return LOCO_ERR_LAUNCH;
+    const struct { int* out; hipDeviceAttribute_t attr; } wanted[] = {
+        {memory_clock_khz, hipDeviceAttributeMemoryClockRate},
+        {memory_bus_bits, hipDeviceAttributeMemoryBusWidth},
+        {compute_units, hipDeviceAttributeMultiprocessorCount},
+        {engine_clock_khz, hipDeviceAttributeClockRate},
+    };
+    for (const auto& w : wanted) {
+        if (!w.out) continue;
+        if (hipDeviceGetAttribute(w.out, w.attr, dev) != hipSuccess) return LOCO_ERR_LAUNCH;
+    }
+    return LOCO_OK;
+}
+
 int loco_reset_due(long long step_index, long long reset_period) {
     return reset_period > 0 && step_index % reset_period == 0;
 }

@@ -786,7 +786,101 @@ def check_round_to_bf16(lib):
     assert np.all(np.isnan(bf16_bits_to_f32(oracle.round_to_bf16(np.array([np.nan, -np.nan], np.float32), lib=lib))))
 
 
+def check_bf16_scales(lib):
+    """Block steps kept in bf16: the stored step is the binary32 step max|h|/qmax rounded to
+    the nearest bf16 (checked against torch's conversion), and everything else follows Eq. 1-5
+    with that rounded step: nearest level by brute force, the rounding bound of Lemma 5,
+    d + delta = h with d decoded by the receiver from the bf16 step, the telescoping identity
+    of Lemma 1, and Eq. 8 equal to the binary32-step reduce fed the widened steps."""
+    import torch
+    as_bf16 = lambda x: torch.from_numpy(np.ascontiguousarray(x, np.float32)).to(torch.bfloat16) \
+        .view(torch.int16).numpy().view(np.uint16)
+    # the dyadic worked example has a step that bf16 holds exactly: same bytes, same state
+    g = (np.array([7, -3.5, 2.5, 0.5, 1.5, -0.25, 0, -7]) * 2.0 ** -10).astype(np.float32)
+    e = np.zeros(8, np.float32)
+    codes, s16 = oracle.compensate_quantize(g, e, 4, 8, 0.25, bf16_scales=True, lib=lib)
+    assert codes.tolist() == [0xC7, 0x02, 0x02, 0x90] and s16.tolist() == [0x3A80]
+    assert np.array_equal(e * 2.0 ** 10, [0, .125, .125, .125, -.125, -.0625, 0, 0])
+
+    rng = np.random.default_rng(97)
+    for bits, B, kind in ((4, 256, "student"), (8, 64, "normal"), (4, 32, "wide"), (8, 512, "student")):
+        qmin, qmax = qrange(bits)
+        n = 50 * B + 9
+        g = rng_grad(rng, n, kind)
+        e0 = rng_grad(rng, n, "normal", 1e-4)
+        h = g + e0
+        e = e0.copy()
+        codes, s16 = oracle.compensate_quantize(g, e, bits, B, 1.0, bf16_scales=True, lib=lib)
+        assert s16.dtype == np.uint16
+        nb = oracle.num_blocks(n, B)
+        amax = np.array([np.abs(h[b * B:min(n, (b + 1) * B)]).max() for b in range(nb)], np.float32)
+        want = as_bf16(amax / np.float32(qmax))
+        assert np.array_equal(s16, want)
+        assert (s16 & 0x7F).any()                           # steps that are not powers of two
+        assert np.any(s16 != (((amax / np.float32(qmax)).view(np.uint32)) >> 16))  # some rounded up
+        D = bf16_bits_to_f32(s16)[block_index(n, B)].astype(np.float64)
+        q = unpack(codes, n, bits)
+        x = h.astype(np.float64) / D
+        assert np.all(np.abs(q - x) <= 0.5 + 4 * qmax * 2.0 ** -24)        # nearest level, Lemma 5
+        assert q.min() >= -qmax and q.max() <= qmax
+        assert np.all(np.abs(e) <= D * (0.5 + 4 * qmax * 2.0 ** -24))
+        top = np.array([b * B + np.argmax(np.abs(h[b * B:min(n, (b + 1) * B)])) for b in range(nb)])
+        assert np.all(np.abs(q[top]) == qmax)
+        # receiver's decode from the bf16 steps + the sender's error gives back h (Eq. 4)
+        d = oracle.dequant_reduce(codes, s16, 1, n, bits, B, lib=lib)
+        with np.errstate(divide="ignore", invalid="ignore"):
+            ratio = np.where(d != 0, h.astype(np.float64) / d.astype(np.float64), 1.0)
+        safe = (d == 0) | ((ratio >= 0.5) & (ratio <= 2.0))
+        assert safe.mean() > 0.99
+        assert np.array_equal((d + e).astype(np.float32)[safe], h[safe])
+        assert np.array_equal(d, (q * D).astype(np.float32))
+
+    # Eq. 8: the bf16-step reduce is the binary32-step reduce of the widened steps
+    bits, B, W, n = 4, 64, 5, 64 * 33 + 3
+    payload_c, payload_s = [], []
+    for w in range(W):
+        gw = rng_grad(rng, n, "student")
+        cw, sw = oracle.compensate_quantize(gw, np.zeros(n, np.float32), bits, B, 0.25, bf16_scales=True, lib=lib)
+        payload_c.append(cw); payload_s.append(sw)
+    C, S = np.concatenate(payload_c), np.concatenate(payload_s)
+    a = oracle.dequant_reduce(C, S, W, n, bits, B, lib=lib)
+    b = oracle.dequant_reduce(C, bf16_bits_to_f32(S), W, n, bits, B, lib=lib)
+    assert np.array_equal(a, b) and np.any(a != 0)
+    assert np.array_equal(a, oracle.dequant_reduce(C, S, W, n, bits, B, threads=3, lib=lib))
+
+    # Lemma 1 (same decompressor on both sides): sum_k d_k = sum_k g_k - e~_K / beta
+    bits, B, beta, K, n = 4, 128, 0.25, 12, 128 * 20
+    e = np.zeros(n, np.float32)
+    sum_d, sum_g = np.zeros(n), np.zeros(n)
+    for k in range(K):
+        gk = rng_grad(rng, n, "normal")
+        ck, sk = oracle.compensate_quantize(gk, e, bits, B, beta, bf16_scales=True, lib=lib)
+        sum_d += oracle.dequant_reduce(ck, sk, 1, n, bits, B, lib=lib)
+        sum_g += gk
+    gap = np.abs(sum_d - (sum_g - e.astype(np.float64) / beta))
+    assert gap.max() <= 20 * K * 2.0 ** -24 * 1e-3 * 8 and np.abs(e).max() > 0
+
+    # zero and subnormal steps: the test is made on the rounded step
+    tiny = np.float32(FLT_MIN)
+    g = np.zeros(24, np.float32)
+    g[0] = np.float32(7) * tiny * np.float32(1 - 2.0 ** -10)   # step just under FLT_MIN, rounds up to it
+    g[8] = np.float32(7) * tiny * np.float32(0.25)             # subnormal step also after rounding
+    e = np.zeros(24, np.float32)
+    codes, s16 = oracle.compensate_quantize(g, e, 4, 8, 1.0, bf16_scales=True, lib=lib)
+    assert s16.tolist() == [0x0080, 0, 0]
+    q = unpack(codes, 24, 4)
+    assert q[0] == 7 and not q[1:].any()
+    assert e[8] == g[8] and e[0] == g[0] - np.float32(7) * tiny
+    # threads and odd sizes
+    g = rng_grad(rng, 1003, "student")
+    e1, e2 = np.zeros(1003, np.float32), np.zeros(1003, np.float32)
+    r1 = oracle.compensate_quantize(g, e1, 8, 32, 0.5, bf16_scales=True, lib=lib)
+    r2 = oracle.compensate_quantize(g, e2, 8, 32, 0.5, bf16_scales=True, threads=4, lib=lib)
+    assert np.array_equal(r1[0], r2[0]) and np.array_equal(r1[1], r2[1]) and np.array_equal(e1, e2)
+
+
 FIXED_CHECKS = [
+    check_bf16_scales,
     check_round_to_bf16,
     check_clip,
     check_optimizer_steps,

@@ -65,6 +65,12 @@ MUTANTS = [
     ("adam_v_not_stored", "        v[i] = v_new;\n", ""),
     ("bf16_truncates", "u += 0x7FFFu + ((u >> 16) & 1u);", ""),
     ("bf16_ties_away", "u += 0x7FFFu + ((u >> 16) & 1u);", "u += 0x8000u;"),
+    ("bf16_step_stored_but_not_used", "            memcpy(&D, &wide, sizeof D);\n        }\n        float r = 0.0f;",
+     "        }\n        float r = 0.0f;"),
+    ("bf16_step_dead_test_before_rounding", "int dead = D < FLT_MIN;", "int dead = (amax / (float)qmax) < FLT_MIN;"),
+    ("bf16_step_decode_shift", "scales16[(size_t)w * scale_stride_elems + b] << 16;",
+     "scales16[(size_t)w * scale_stride_elems + b] << 15;"),
+    ("bf16_step_worker_stride", "scales16[(size_t)w * scale_stride_elems + b]", "scales16[b]"),
     ("fixed_reduce_stride", "int q = code_at(codes + (size_t)w * code_stride_bytes, bits, i);\n            float d = (float)q / s;",
      "int q = code_at(codes, bits, i);\n            float d = (float)q / s;"),
 ]
