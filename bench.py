@@ -55,6 +55,8 @@ def parse_args():
                     help="fuse the optimizer step of Eq. 9 / Eq. 10 into the reduce (theta, m, v fp32 in place)")
     ap.add_argument("--out", choices=["f32", "bf16"], default="f32",
                     help="type the averaged gradient is written in (bf16: rounded to nearest even)")
+    ap.add_argument("--scales", choices=["f32", "bf16"], default="f32",
+                    help="block form only: keep the block steps in bf16 (rounded before use)")
     ap.add_argument("--no-copy-ceiling", action="store_true")
     return ap.parse_args()
 
@@ -122,9 +124,10 @@ def cpu_baseline(form, w, grads, recv_codes, cstride, recv_scales, nb_full, samp
 
 
 def device_report(info):
-    """The device's own figures and the HBM peak they imply (two transfers per memory clock)."""
+    """The device's own figures and the HBM peak they imply.  HBM3/3E moves data on both edges
+    of a strobe that runs at twice the reported (command) clock: four transfers per clock and pin."""
     info = dict(info)
-    info["derived_hbm_peak_GBps"] = 2.0 * info["memory_clock_khz"] * 1e3 * info["memory_bus_bits"] / 8 / 1e9
+    info["derived_hbm_peak_GBps"] = 4.0 * info["memory_clock_khz"] * 1e3 * info["memory_bus_bits"] / 8 / 1e9
     return info
 
 
@@ -143,7 +146,9 @@ def main():
                                       loco_dequant_reduce_fixed_adam, loco_dequant_reduce_fixed_sgd,
                                       loco_dequant_reduce_sgd, loco_error_state8_init, loco_error_state_init,
                                       loco_num_blocks, workloads)
-    from paper_2407_04480_amd.binding import loco_stream_copy, loco_device_info
+    from paper_2407_04480_amd.binding import (loco_stream_copy, loco_device_info,
+                                              loco_compensate_quantize_bf16_scales,
+                                              loco_dequant_reduce_bf16_scales)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; there is no CPU path.", file=sys.stderr)
@@ -170,6 +175,14 @@ def main():
             return 2
         bytes_dr -= 2
         names = (names[0], names[1] + "_bf16")
+    bf16_steps = args.scales == "bf16"
+    if bf16_steps:
+        if form != "block" or opt != "none" or args.out != "f32":
+            print("bench.py: --scales bf16 goes with --form block, no optimizer and fp32 output", file=sys.stderr)
+            return 2
+        bytes_cq -= 2.0 / B
+        bytes_dr -= W * 2.0 / B
+        names = (names[0] + "_bf16_scales", names[1] + "_bf16_scales")
     ETA, BETA1, BETA2, DELTA = 1e-4, 0.1, 0.02, 1e-8   # Sec. 4 calls beta1 = 0.1, beta2 in [0.001, 0.05] typical
 
     # ---- resident inputs: two own gradients (used alternately), W-1 peers' payloads ----
@@ -177,7 +190,7 @@ def main():
     cb, nb = loco_code_bytes(n, bits), loco_num_blocks(n, B)
     cstride = (cb + 15) // 16 * 16
     recv_codes = torch.zeros(W * cstride, dtype=torch.uint8, device=dev)
-    recv_scales = torch.zeros(W * nb, dtype=torch.float32, device=dev)
+    recv_scales = torch.zeros(W * nb, dtype=torch.bfloat16 if bf16_steps else torch.float32, device=dev)
     own_codes, own_scales = recv_codes[:cb], recv_scales[:nb]
     out = torch.empty(n, dtype=torch.float32 if args.out == "f32" else torch.bfloat16, device=dev) \
         if opt == "none" else None
@@ -191,10 +204,15 @@ def main():
             loco_error_state_init(e, stream)
 
         def cq(g, e, codes, scales):
-            loco_compensate_quantize(g, e, bits, B, w.beta, False, codes, scales, stream)
+            if bf16_steps:
+                loco_compensate_quantize_bf16_scales(g, e, bits, B, w.beta, False, codes, scales, stream)
+            else:
+                loco_compensate_quantize(g, e, bits, B, w.beta, False, codes, scales, stream)
 
         def dr():
-            if opt == "none" and args.out == "bf16":
+            if bf16_steps:
+                loco_dequant_reduce_bf16_scales(recv_codes, cstride, recv_scales, nb, W, n, bits, B, out, stream)
+            elif opt == "none" and args.out == "bf16":
                 loco_dequant_reduce_bf16(recv_codes, cstride, recv_scales, nb, W, n, bits, B, out, stream)
             elif opt == "none":
                 loco_dequant_reduce(recv_codes, cstride, recv_scales, nb, W, n, bits, B, out, stream)
@@ -291,7 +309,7 @@ def main():
         del src, dst
 
     cpu = None
-    if args.cpu_sample > 0 and opt == "none" and args.out == "f32":
+    if args.cpu_sample > 0 and opt == "none" and args.out == "f32" and not bf16_steps:
         # own payload for the sample: one compensate-quantize step from a zero state
         state_init(err)
         cq(grads[0], err, own_codes, own_scales)
@@ -312,7 +330,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "n": n, "grad_dtype": str(w.grad_dtype).replace("torch.", ""),
-                   "bits": bits, "beta": w.beta, "num_workers": W, "form": form, "optimizer": opt, "out": args.out,
+                   "bits": bits, "beta": w.beta, "num_workers": W, "form": form, "optimizer": opt, "out": args.out, "scales": args.scales,
                    **({"block_size": B} if form == "block" else
                       {"log2_s": FIXED_LOG2_S, "se_mult": FIXED_SE_MULT, "state": "int8"}),
                    "step": " + ".join(n_[5:] for n_ in names)},

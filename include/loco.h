@@ -216,6 +216,26 @@ loco_status_t loco_dequant_reduce_fixed_bf16(const uint8_t *codes, size_t code_s
                                              void *stream);
 
 /*
+ * Algorithm 1 with the block steps kept in bf16 (2 bytes per block instead of 4;
+ * the paper's Eq. 1 has one global s and no per-block steps at all, so the step
+ * format is this library's choice).  The step D_b = max|h| / qmax is rounded to
+ * the nearest bf16 (ties to even) BEFORE use: compressor (Eq. 1, Eq. 3), the
+ * sender's own decompressor (Eq. 4) and every receiver (Eq. 8) work with the
+ * stored value, so the error feedback of Eq. 5 still sees exactly what the
+ * receivers decode.  The zero/subnormal test is made on the rounded step.
+ * Arguments as in loco_compensate_quantize / loco_dequant_reduce except that the
+ * steps are uint16_t bf16 bit patterns (array base 4-byte aligned; stride in
+ * elements, any parity).
+ */
+loco_status_t loco_compensate_quantize_bf16_scales(const void *grad, loco_dtype_t grad_dtype, float *err_state,
+                                                   size_t n, int bits, int block_size, float beta, int reset,
+                                                   uint8_t *codes_out, uint16_t *scales_out_bf16, void *stream);
+loco_status_t loco_dequant_reduce_bf16_scales(const uint8_t *codes, size_t code_stride_bytes,
+                                              const uint16_t *scales_bf16, size_t scale_stride_elems,
+                                              int num_workers, size_t n, int bits, int block_size,
+                                              float *grad_out, void *stream);
+
+/*
  * Measurement aid, not part of the method: dst[i] = src[i] for `bytes` bytes
  * (a multiple of 16, both pointers 16-byte aligned) with the same load/store
  * shape as the kernels above.  Gives the practical HBM ceiling and the scale
@@ -225,7 +245,7 @@ loco_status_t loco_stream_copy(void *dst, const void *src, size_t bytes, void *s
 
 /*
  * Measurement aid, not part of the method: what the current device reports
- * about itself, for deriving the HBM peak (2 transfers per memory clock x bus
+ * about itself, for deriving the HBM peak (transfers per memory clock x bus
  * width / 8) beside the published figure.  Each pointer may be NULL; values
  * are written to host memory: memory clock in kHz, memory bus width in bits,
  * number of compute units, engine clock in kHz.  LOCO_ERR_LAUNCH if the

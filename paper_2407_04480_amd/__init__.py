@@ -25,6 +25,8 @@ from .binding import (  # noqa: F401
     loco_dequant_reduce_fixed_adam,
     loco_dequant_reduce_bf16,
     loco_dequant_reduce_fixed_bf16,
+    loco_compensate_quantize_bf16_scales,
+    loco_dequant_reduce_bf16_scales,
     loco_stream_copy,
     loco_device_info,
 )
@@ -49,6 +51,8 @@ __all__ = [
     "loco_dequant_reduce_fixed_adam",
     "loco_dequant_reduce_bf16",
     "loco_dequant_reduce_fixed_bf16",
+    "loco_compensate_quantize_bf16_scales",
+    "loco_dequant_reduce_bf16_scales",
     "loco_stream_copy",
     "loco_device_info",
 ]

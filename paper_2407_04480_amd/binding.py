@@ -28,6 +28,8 @@ EXPORTS = (
     "loco_error_state_init",
     "loco_compensate_quantize",
     "loco_dequant_reduce",
+    "loco_compensate_quantize_bf16_scales",
+    "loco_dequant_reduce_bf16_scales",
     "loco_stream_copy",
     "loco_device_info",
     "loco_reset_due",
@@ -78,6 +80,10 @@ def load_library(path: Optional[str] = None):
     lib.loco_compensate_quantize.restype = i
     lib.loco_dequant_reduce.argtypes = [vp, sz, vp, sz, i, sz, i, i, vp, vp]
     lib.loco_dequant_reduce.restype = i
+    lib.loco_compensate_quantize_bf16_scales.argtypes = [vp, i, vp, sz, i, i, f, i, vp, vp, vp]
+    lib.loco_compensate_quantize_bf16_scales.restype = i
+    lib.loco_dequant_reduce_bf16_scales.argtypes = [vp, sz, vp, sz, i, sz, i, i, vp, vp]
+    lib.loco_dequant_reduce_bf16_scales.restype = i
     lib.loco_stream_copy.argtypes, lib.loco_stream_copy.restype = [vp, vp, sz, vp], i
     ip = ctypes.POINTER(ctypes.c_int)
     lib.loco_device_info.argtypes, lib.loco_device_info.restype = [ip, ip, ip, ip], i
@@ -165,7 +171,7 @@ def loco_compensate_quantize_fixed_clip(grad, clip_abs: float, err_state8, bits,
 
 def loco_compensate_quantize(grad: torch.Tensor, err_state: torch.Tensor, bits: int, block_size: int,
                              beta: float, reset: bool, codes_out: torch.Tensor, scales_out: torch.Tensor,
-                             stream=None, _clip_abs=None) -> None:
+                             stream=None, _clip_abs=None, _bf16_scales=False) -> None:
     """Algorithm 1 steps 1-2 (Eq. 1-5, 7): err_state is updated in place, codes_out
     (uint8) and scales_out (float32) receive the payload."""
     lib = load_library()
@@ -179,7 +185,7 @@ def loco_compensate_quantize(grad: torch.Tensor, err_state: torch.Tensor, bits: 
     pg = _dev_ptr(grad, "grad")
     pe = _dev_ptr(err_state, "err_state", torch.float32)
     pc = _dev_ptr(codes_out, "codes_out", torch.uint8)
-    ps = _dev_ptr(scales_out, "scales_out", torch.float32)
+    ps = _dev_ptr(scales_out, "scales_out", torch.bfloat16 if _bf16_scales else torch.float32)
     if err_state.numel() != n:
         raise ValueError("err_state must have as many elements as grad")
     if bits in (4, 8) and block_size >= 1:
@@ -187,7 +193,13 @@ def loco_compensate_quantize(grad: torch.Tensor, err_state: torch.Tensor, bits: 
             raise ValueError("codes_out too small")
         if scales_out.numel() < (n + block_size - 1) // block_size:
             raise ValueError("scales_out too small")
-    if _clip_abs is None:
+    if _bf16_scales:
+        if _clip_abs is not None:
+            raise ValueError("bf16 block steps are offered without clipping")
+        st = lib.loco_compensate_quantize_bf16_scales(pg, gd, pe, n, int(bits), int(block_size), float(beta),
+                                                      1 if reset else 0, pc, ps, _stream_handle(stream))
+        _check("loco_compensate_quantize_bf16_scales", st)
+    elif _clip_abs is None:
         st = lib.loco_compensate_quantize(pg, gd, pe, n, int(bits), int(block_size), float(beta),
                                           1 if reset else 0, pc, ps, _stream_handle(stream))
         _check("loco_compensate_quantize", st)
@@ -199,11 +211,11 @@ def loco_compensate_quantize(grad: torch.Tensor, err_state: torch.Tensor, bits: 
 
 def loco_dequant_reduce(codes: torch.Tensor, code_stride_bytes: int, scales: torch.Tensor,
                         scale_stride_elems: int, num_workers: int, n: int, bits: int, block_size: int,
-                        grad_out: torch.Tensor, stream=None) -> None:
+                        grad_out: torch.Tensor, stream=None, _bf16_scales=False) -> None:
     """Algorithm 1 step 3 / Eq. 8: decode num_workers payloads and average into grad_out (float32)."""
     lib = load_library()
     pc = _dev_ptr(codes, "codes", torch.uint8)
-    ps = _dev_ptr(scales, "scales", torch.float32)
+    ps = _dev_ptr(scales, "scales", torch.bfloat16 if _bf16_scales else torch.float32)
     po = _dev_ptr(grad_out, "grad_out", torch.float32)
     if grad_out.numel() < n:
         raise ValueError("grad_out too small")
@@ -214,9 +226,24 @@ def loco_dequant_reduce(codes: torch.Tensor, code_stride_bytes: int, scales: tor
             raise ValueError("codes too small for num_workers payloads at this stride")
         if scales.numel() < (num_workers - 1) * ss + (n + block_size - 1) // block_size:
             raise ValueError("scales too small for num_workers payloads at this stride")
-    st = lib.loco_dequant_reduce(pc, int(code_stride_bytes), ps, int(scale_stride_elems), int(num_workers),
-                                 int(n), int(bits), int(block_size), po, _stream_handle(stream))
-    _check("loco_dequant_reduce", st)
+    name = "loco_dequant_reduce_bf16_scales" if _bf16_scales else "loco_dequant_reduce"
+    st = getattr(lib, name)(pc, int(code_stride_bytes), ps, int(scale_stride_elems), int(num_workers),
+                            int(n), int(bits), int(block_size), po, _stream_handle(stream))
+    _check(name, st)
+
+
+def loco_compensate_quantize_bf16_scales(grad, err_state, bits, block_size, beta, reset, codes_out,
+                                         scales_out, stream=None) -> None:
+    """Algorithm 1 steps 1-2 with the block steps rounded to bf16 before use; scales_out is bfloat16."""
+    loco_compensate_quantize(grad, err_state, bits, block_size, beta, reset, codes_out, scales_out, stream,
+                             _bf16_scales=True)
+
+
+def loco_dequant_reduce_bf16_scales(codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n, bits,
+                                    block_size, grad_out, stream=None) -> None:
+    """Eq. 8 over payloads whose block steps are bfloat16."""
+    loco_dequant_reduce(codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n, bits, block_size,
+                        grad_out, stream, _bf16_scales=True)
 
 
 def loco_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

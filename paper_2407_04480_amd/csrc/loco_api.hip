@@ -80,21 +80,26 @@ struct CqArgs {
     int reset;
     float clip;   // +inf: no clipping
     uint8_t* codes;
-    float* scales;
+    void* scales;      // float[nb], or uint16_t[nb] holding bf16 steps
+    bool scales_bf16;
 };
 
 template <typename G, int BITS, int BLOCK>
 void launch_cq(unsigned grid, hipStream_t s, const CqArgs& a) {
     const float one_minus_beta = 1.0f - a.beta;
     using Shape = CqShape<BITS>;
-    if (std::isinf(a.clip))
-        cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false>
+    if (a.scales_bf16)   // offered without clipping only
+        cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, uint16_t>
             <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset,
-                                                          a.clip, a.codes, a.scales);
+                                                          a.clip, a.codes, static_cast<uint16_t*>(a.scales));
+    else if (std::isinf(a.clip))
+        cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, float>
+            <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset,
+                                                          a.clip, a.codes, static_cast<float*>(a.scales));
     else
-        cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, true>
+        cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, true, float>
             <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset,
-                                                          a.clip, a.codes, a.scales);
+                                                          a.clip, a.codes, static_cast<float*>(a.scales));
 }
 
 template <typename G, int BITS>
@@ -112,7 +117,8 @@ bool dispatch_cq_block(int block, unsigned grid, hipStream_t s, const CqArgs& a)
 struct DrArgs {
     const uint8_t* codes;
     size_t code_stride;
-    const float* scales;
+    const void* scales;   // float, or uint16_t holding bf16 steps
+    bool scales_bf16;
     size_t scale_stride;
     int W;
     size_t n;
@@ -126,9 +132,18 @@ template <int BITS, int BLOCK, Epilogue EPI>
 void launch_dr(unsigned grid, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
     const float inv_w = 1.0f / (float)a.W;
     using Shape = DrShapeFor<BITS, EPI>;
-    dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun, EPI>
-        <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.codes, a.code_stride, a.scales, a.scale_stride, a.W, a.n,
-                                                      inv_w, epi);
+    if constexpr (EPI == Epilogue::kStore) {   // bf16 steps are offered with the plain fp32 output only
+        if (a.scales_bf16) {
+            dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun, EPI, uint16_t>
+                <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.codes, a.code_stride,
+                                                              static_cast<const uint16_t*>(a.scales),
+                                                              a.scale_stride, a.W, a.n, inv_w, epi);
+            return;
+        }
+    }
+    dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun, EPI, float>
+        <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.codes, a.code_stride, static_cast<const float*>(a.scales),
+                                                      a.scale_stride, a.W, a.n, inv_w, epi);
 }
 
 template <int BITS, Epilogue EPI>
@@ -210,9 +225,11 @@ void dispatch_fixed_cq(int bits, bool pow2, unsigned grid, hipStream_t s, const 
     }
 }
 
-loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const float* scales,
-                                  size_t scale_stride_elems, int num_workers, size_t n, int bits, int block_size,
-                                  Epilogue kind, const EpilogueArgs& epi, void* stream) {
+loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const void* scales,
+                           size_t scale_stride_elems, int num_workers, size_t n, int bits, int block_size,
+                           Epilogue kind, const EpilogueArgs& epi, void* stream, bool scales_bf16 = false) {
+    if (scales_bf16 && kind != Epilogue::kStore) return LOCO_ERR_UNSUPPORTED;
+    const size_t step_bytes = scales_bf16 ? sizeof(uint16_t) : sizeof(float);
     if (bits != 4 && bits != 8) return LOCO_ERR_UNSUPPORTED;
     if (!block_size_ok(block_size)) return LOCO_ERR_UNSUPPORTED;
     if (num_workers < 1) return LOCO_ERR_INVALID_ARG;
@@ -229,7 +246,7 @@ loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const
     }
     if (!aligned(codes, 16) || !aligned(scales, 4)) return LOCO_ERR_ALIGNMENT;
     if (loco_status_t st = check_device_range(codes, (W - 1) * code_stride_bytes + cb)) return st;
-    if (loco_status_t st = check_device_range(scales, ((W - 1) * scale_stride_elems + nb) * sizeof(float)))
+    if (loco_status_t st = check_device_range(scales, ((W - 1) * scale_stride_elems + nb) * step_bytes))
         return st;
     if (loco_status_t st = check_epilogue(kind, epi, n)) return st;
     unsigned grid;
@@ -238,7 +255,7 @@ loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const
                                   : (size_t)kSlot * DrShape<4>::kSlots * (DrShape<4>::kThreads / kWave);
     if (loco_status_t st = grid_for(n, per_group, &grid, kDrXcdRun ? 8 * kDrXcdRun : 1)) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const DrArgs a{codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n};
+    const DrArgs a{codes, code_stride_bytes, scales, scales_bf16, scale_stride_elems, num_workers, n};
     bool ok = false;
     switch (kind) {
         case Epilogue::kStore: ok = dispatch_dr<Epilogue::kStore>(bits, block_size, grid, s, a, epi); break;
@@ -292,6 +309,43 @@ loco_status_t reduce_fixed(const uint8_t* codes, size_t code_stride_bytes, int n
     return launched();
 }
 
+loco_status_t compress_block(const void* grad, loco_dtype_t grad_dtype, float clip_abs, float* err_state,
+                             size_t n, int bits, int block_size, float beta, int reset, uint8_t* codes_out,
+                             void* scales_out, bool scales_bf16, void* stream) {
+    const size_t step_bytes = scales_bf16 ? sizeof(uint16_t) : sizeof(float);
+    if (bits != 4 && bits != 8) return LOCO_ERR_UNSUPPORTED;
+    if (!block_size_ok(block_size)) return LOCO_ERR_UNSUPPORTED;
+    if (grad_dtype != LOCO_F32 && grad_dtype != LOCO_BF16) return LOCO_ERR_UNSUPPORTED;
+    if (!(beta >= 0.0f && beta <= 1.0f)) return LOCO_ERR_INVALID_ARG;  // also rejects NaN
+    if (!(clip_abs > 0.0f)) return LOCO_ERR_INVALID_ARG;               // NaN, zero, negative
+    if (n == 0) return LOCO_OK;
+    if (!grad || !err_state || !codes_out || !scales_out) return LOCO_ERR_INVALID_ARG;
+    if (!aligned(grad, 16) || !aligned(err_state, 16) || !aligned(codes_out, 16) || !aligned(scales_out, 4))
+        return LOCO_ERR_ALIGNMENT;
+    const size_t gsz = grad_dtype == LOCO_BF16 ? 2 : 4;
+    if (loco_status_t st = check_device_range(grad, n * gsz)) return st;
+    if (loco_status_t st = check_device_range(err_state, n * sizeof(float))) return st;
+    if (loco_status_t st = check_device_range(codes_out, loco_code_bytes(n, bits))) return st;
+    if (loco_status_t st = check_device_range(scales_out, loco_num_blocks(n, block_size) * step_bytes))
+        return st;
+    unsigned grid;
+    const size_t per_group = bits == 4 ? (size_t)kSlot * CqShape<4>::kSlots * (CqShape<4>::kThreads / kWave)
+                                       : (size_t)kSlot * CqShape<8>::kSlots * (CqShape<8>::kThreads / kWave);
+    if (loco_status_t st = grid_for(n, per_group, &grid, kCqXcdRun ? 8 * kCqXcdRun : 1)) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const CqArgs a{grad, err_state, n, beta, reset, clip_abs, codes_out, scales_out, scales_bf16};
+    bool ok;
+    if (grad_dtype == LOCO_BF16) {
+        ok = bits == 4 ? dispatch_cq_block<bf16_t, 4>(block_size, grid, s, a)
+                       : dispatch_cq_block<bf16_t, 8>(block_size, grid, s, a);
+    } else {
+        ok = bits == 4 ? dispatch_cq_block<float, 4>(block_size, grid, s, a)
+                       : dispatch_cq_block<float, 8>(block_size, grid, s, a);
+    }
+    if (!ok) return LOCO_ERR_UNSUPPORTED;
+    return launched();
+}
+
 }  // namespace
 
 extern "C" {
@@ -336,44 +390,31 @@ loco_status_t loco_error_state_init(float* err_state, size_t n, void* stream) {
 loco_status_t loco_compensate_quantize_clip(const void* grad, loco_dtype_t grad_dtype, float clip_abs,
                                             float* err_state, size_t n, int bits, int block_size, float beta,
                                             int reset, uint8_t* codes_out, float* scales_out, void* stream) {
-    if (bits != 4 && bits != 8) return LOCO_ERR_UNSUPPORTED;
-    if (!block_size_ok(block_size)) return LOCO_ERR_UNSUPPORTED;
-    if (grad_dtype != LOCO_F32 && grad_dtype != LOCO_BF16) return LOCO_ERR_UNSUPPORTED;
-    if (!(beta >= 0.0f && beta <= 1.0f)) return LOCO_ERR_INVALID_ARG;  // also rejects NaN
-    if (!(clip_abs > 0.0f)) return LOCO_ERR_INVALID_ARG;               // NaN, zero, negative
-    if (n == 0) return LOCO_OK;
-    if (!grad || !err_state || !codes_out || !scales_out) return LOCO_ERR_INVALID_ARG;
-    if (!aligned(grad, 16) || !aligned(err_state, 16) || !aligned(codes_out, 16) || !aligned(scales_out, 4))
-        return LOCO_ERR_ALIGNMENT;
-    const size_t gsz = grad_dtype == LOCO_BF16 ? 2 : 4;
-    if (loco_status_t st = check_device_range(grad, n * gsz)) return st;
-    if (loco_status_t st = check_device_range(err_state, n * sizeof(float))) return st;
-    if (loco_status_t st = check_device_range(codes_out, loco_code_bytes(n, bits))) return st;
-    if (loco_status_t st = check_device_range(scales_out, loco_num_blocks(n, block_size) * sizeof(float)))
-        return st;
-    unsigned grid;
-    const size_t per_group = bits == 4 ? (size_t)kSlot * CqShape<4>::kSlots * (CqShape<4>::kThreads / kWave)
-                                       : (size_t)kSlot * CqShape<8>::kSlots * (CqShape<8>::kThreads / kWave);
-    if (loco_status_t st = grid_for(n, per_group, &grid, kCqXcdRun ? 8 * kCqXcdRun : 1)) return st;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const CqArgs a{grad, err_state, n, beta, reset, clip_abs, codes_out, scales_out};
-    bool ok;
-    if (grad_dtype == LOCO_BF16) {
-        ok = bits == 4 ? dispatch_cq_block<bf16_t, 4>(block_size, grid, s, a)
-                       : dispatch_cq_block<bf16_t, 8>(block_size, grid, s, a);
-    } else {
-        ok = bits == 4 ? dispatch_cq_block<float, 4>(block_size, grid, s, a)
-                       : dispatch_cq_block<float, 8>(block_size, grid, s, a);
-    }
-    if (!ok) return LOCO_ERR_UNSUPPORTED;
-    return launched();
+    return compress_block(grad, grad_dtype, clip_abs, err_state, n, bits, block_size, beta, reset, codes_out,
+                          scales_out, false, stream);
 }
 
 loco_status_t loco_compensate_quantize(const void* grad, loco_dtype_t grad_dtype, float* err_state,
                                        size_t n, int bits, int block_size, float beta, int reset,
                                        uint8_t* codes_out, float* scales_out, void* stream) {
-    return loco_compensate_quantize_clip(grad, grad_dtype, INFINITY, err_state, n, bits, block_size, beta, reset,
-                                         codes_out, scales_out, stream);
+    return compress_block(grad, grad_dtype, INFINITY, err_state, n, bits, block_size, beta, reset, codes_out,
+                          scales_out, false, stream);
+}
+
+loco_status_t loco_compensate_quantize_bf16_scales(const void* grad, loco_dtype_t grad_dtype, float* err_state,
+                                                   size_t n, int bits, int block_size, float beta, int reset,
+                                                   uint8_t* codes_out, uint16_t* scales_out_bf16, void* stream) {
+    return compress_block(grad, grad_dtype, INFINITY, err_state, n, bits, block_size, beta, reset, codes_out,
+                          scales_out_bf16, true, stream);
+}
+
+loco_status_t loco_dequant_reduce_bf16_scales(const uint8_t* codes, size_t code_stride_bytes,
+                                              const uint16_t* scales_bf16, size_t scale_stride_elems,
+                                              int num_workers, size_t n, int bits, int block_size,
+                                              float* grad_out, void* stream) {
+    return reduce_block(codes, code_stride_bytes, scales_bf16, scale_stride_elems, num_workers, n, bits, block_size,
+                        Epilogue::kStore, make_epilogue(grad_out, nullptr, nullptr, nullptr, 0, 0, 0, 0), stream,
+                        true);
 }
 
 loco_status_t loco_dequant_reduce(const uint8_t* codes, size_t code_stride_bytes, const float* scales,

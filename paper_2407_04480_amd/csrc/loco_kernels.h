@@ -128,7 +128,32 @@ template <> struct Grad<bf16_t> {
 // ---- Algorithm 1 steps 1-2 on a wavefront's tile held in registers ----
 // h: compensated gradient (Eq. 2), e: old state; on return e holds the new state, packed
 // the codes of each quad (16 or 32 bits) and step the quad's block step D.
-template <int BITS, int BLOCK, int SLOTS>
+// A block step as it is stored: binary32, or bf16 bits (uint16_t).  A bf16 step is rounded
+// (nearest, ties to even, in integer arithmetic so that subnormal steps round like any
+// other) before anything uses it, so compressor, own decompressor and the receivers all
+// work with the stored value.  Steps are non-negative and finite.
+__device__ __forceinline__ float round_step_to_bf16(float D) {
+    uint32_t u = __float_as_uint(D);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return __uint_as_float(u & 0xFFFF0000u);
+}
+template <typename S> __device__ __forceinline__ S step_to_storage(float D);
+template <> __device__ __forceinline__ float step_to_storage<float>(float D) { return D; }
+template <> __device__ __forceinline__ uint16_t step_to_storage<uint16_t>(float D) {
+    return (uint16_t)(__float_as_uint(D) >> 16);   // already rounded: the low half is zero
+}
+__device__ __forceinline__ float step_from_storage(float v) { return v; }
+__device__ __forceinline__ float step_from_storage(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+// Step k of an array at a wavefront-uniform index.  The scalar unit loads whole dwords only,
+// so a bf16 step is taken out of the dword that holds it; the array starts on a dword
+// boundary (checked by the host) and device allocations end on one.
+__device__ __forceinline__ float load_uniform_step(const float* base, size_t k) { return base[k]; }
+__device__ __forceinline__ float load_uniform_step(const uint16_t* base, size_t k) {
+    const uint32_t word = reinterpret_cast<const uint32_t*>(base)[k >> 1];
+    return __uint_as_float((k & 1) ? (word & 0xFFFF0000u) : (word << 16));
+}
+
+template <int BITS, int BLOCK, int SLOTS, bool S16>
 __device__ __forceinline__ void cq_tile(const float (&h)[SLOTS][4], float (&e)[SLOTS][4], float beta,
                                         float one_minus_beta, bool reset, int lane,
                                         uint32_t (&packed)[SLOTS], float (&step)[SLOTS]) {
@@ -158,6 +183,7 @@ __device__ __forceinline__ void cq_tile(const float (&h)[SLOTS][4], float (&e)[S
 #pragma unroll
     for (int s = 0; s < SLOTS; ++s) {
         float D = a[s] / (float)QMAX;        // step of the block: 1/s_b, correctly rounded
+        if constexpr (S16) D = round_step_to_bf16(D);
         const bool live = !(D < FLT_MIN);    // zero or subnormal step: encode nothing
         const float r = live ? 1.0f / D : 0.0f;
         D = live ? D : 0.0f;
@@ -181,11 +207,12 @@ __device__ __forceinline__ void cq_tile(const float (&h)[SLOTS][4], float (&e)[S
 // own contiguous tile.  grid = ceil(n / (SLOTS*256*THREADS/64)), rounded up to a multiple of 8*XCDK.  A wavefront whose tile
 // lies inside [0, n) takes the vector path; the last one may take the guarded path, which
 // touches memory element by element and never at or beyond n.
-template <typename G, int BITS, int BLOCK, int SLOTS, int THREADS, bool NT, int XCDK, bool CLIP>
+template <typename G, int BITS, int BLOCK, int SLOTS, int THREADS, bool NT, int XCDK, bool CLIP, typename S>
 __global__ void __launch_bounds__(THREADS)
 cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, float beta,
           float one_minus_beta, int reset, float clip, uint8_t* __restrict__ codes,
-          float* __restrict__ scales) {
+          S* __restrict__ scales) {
+    constexpr bool S16 = sizeof(S) == 2;
     constexpr int GROUP = BLOCK >= kSlot ? kWave : BLOCK / kQuad;  // lanes per block within a slot
     constexpr size_t TILE = (size_t)kSlot * SLOTS;
     const int lane = threadIdx.x & (kWave - 1);
@@ -208,7 +235,7 @@ cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, floa
         for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
             for (int j = 0; j < 4; ++j) h[s][j] = clip_grad<CLIP>(h[s][j], clip) + e[s][j];  // Eq. 2
-        cq_tile<BITS, BLOCK, SLOTS>(h, e, beta, one_minus_beta, rst, lane, pk, step);
+        cq_tile<BITS, BLOCK, SLOTS, S16>(h, e, beta, one_minus_beta, rst, lane, pk, step);
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
@@ -222,11 +249,12 @@ cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, floa
             // store writes them side by side from a wavefront-uniform base address
             // (measured: up to 13 % faster than letting each block's first lane store).
             if constexpr (BLOCK > kSlot) {
-                if (lane == 0 && s % (BLOCK / kSlot) == 0) scales[(tile0 + (size_t)s * kSlot) / BLOCK] = step[s];
+                if (lane == 0 && s % (BLOCK / kSlot) == 0)
+                    scales[(tile0 + (size_t)s * kSlot) / BLOCK] = step_to_storage<S>(step[s]);
             } else {
                 constexpr int NBLK = kWave / GROUP;
                 const float v = NBLK > 1 ? __shfl(step[s], (lane * GROUP) & (kWave - 1), kWave) : step[s];
-                if (lane < NBLK) scales[(tile0 + (size_t)s * kSlot) / BLOCK + lane] = v;
+                if (lane < NBLK) scales[(tile0 + (size_t)s * kSlot) / BLOCK + lane] = step_to_storage<S>(v);
             }
         }
     } else {
@@ -241,7 +269,7 @@ cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, floa
                 h[s][j] = clip_grad<CLIP>(gj, clip) + e[s][j];  // past n: h = 0, neutral for the max, code 0
             }
         }
-        cq_tile<BITS, BLOCK, SLOTS>(h, e, beta, one_minus_beta, rst, lane, pk, step);
+        cq_tile<BITS, BLOCK, SLOTS, S16>(h, e, beta, one_minus_beta, rst, lane, pk, step);
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
@@ -257,9 +285,9 @@ cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, floa
                     if (i + j < n) codes[i + j] = (uint8_t)(pk[s] >> (8 * j));
             }
             if constexpr (BLOCK > kSlot) {
-                if (lane == 0 && s % (BLOCK / kSlot) == 0 && i < n) scales[i / BLOCK] = step[s];
+                if (lane == 0 && s % (BLOCK / kSlot) == 0 && i < n) scales[i / BLOCK] = step_to_storage<S>(step[s]);
             } else {
-                if ((lane & (GROUP - 1)) == 0 && i < n) scales[i / BLOCK] = step[s];
+                if ((lane & (GROUP - 1)) == 0 && i < n) scales[i / BLOCK] = step_to_storage<S>(step[s]);
             }
         }
     }
@@ -412,9 +440,9 @@ constexpr uint32_t kBigStepBits = 0x7B800000u;  // 2^120 as a binary32 bit patte
 // are a wavefront-uniform base (SGPRs, advanced per worker on the scalar unit) plus a
 // 32-bit lane offset; with BLOCK >= 256 a slot lies in one block, so its step is a scalar
 // load shared by the wavefront.
-template <int BITS, int BLOCK, int SLOTS, int THREADS, int WU, bool NT, int XCDK, Epilogue EPI>
+template <int BITS, int BLOCK, int SLOTS, int THREADS, int WU, bool NT, int XCDK, Epilogue EPI, typename S>
 __global__ void __launch_bounds__(THREADS)
-dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const float* __restrict__ scales,
+dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __restrict__ scales,
           size_t scale_stride, int W, size_t n, float inv_w, EpilogueArgs epi) {
     constexpr size_t TILE = (size_t)kSlot * SLOTS;
     constexpr bool UNIFORM_STEP = BLOCK >= kSlot;
@@ -426,7 +454,7 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const float* __
 
     if (tile0 + TILE <= n) {
         const uint8_t* cbase = codes + tile0 * BITS / 8;   // uniform
-        const float* sbase = scales + tile0 / BLOCK;       // uniform
+        size_t sidx = tile0 / BLOCK;                        // uniform
         const uint32_t code_off = lane * (kQuad * BITS / 8);
         const uint32_t step_off = UNIFORM_STEP ? 0u : lane / (uint32_t)(BLOCK / kQuad);
         float acc[SLOTS][4];
@@ -445,11 +473,11 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const float* __
 #pragma unroll
                     for (int s = 0; s < SLOTS; ++s) {
                         c[u][s] = load_quad_codes<BITS, NT>(cbase + (size_t)(s * SLOT_CODE_BYTES + code_off));
-                        if constexpr (UNIFORM_STEP) D[u][s] = sbase[(s * kSlot) / BLOCK];
-                        else D[u][s] = sbase[(size_t)(s * (kSlot / BLOCK) + step_off)];
+                        if constexpr (UNIFORM_STEP) D[u][s] = load_uniform_step(scales, sidx + (s * kSlot) / BLOCK);
+                        else D[u][s] = step_from_storage(scales[sidx + (size_t)(s * (kSlot / BLOCK) + step_off)]);
                     }
                     cbase += code_stride;
-                    sbase += scale_stride;
+                    sidx += scale_stride;
                 }
             }
         };
@@ -520,7 +548,7 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const float* __
                     for (int j = 0; j < 4; ++j)
                         if (i + j < n) c |= (uint32_t)p[i + j] << (8 * j);
                 }
-                const float D = scales[(size_t)w * scale_stride + i / BLOCK];
+                const float D = step_from_storage(scales[(size_t)w * scale_stride + i / BLOCK]);
                 dr_accumulate<BITS>(c, D, acc);
             }
 #pragma unroll
