@@ -224,8 +224,9 @@ loco_status_t loco_dequant_reduce_fixed_bf16(const uint8_t *codes, size_t code_s
  * stored value, so the error feedback of Eq. 5 still sees exactly what the
  * receivers decode.  The zero/subnormal test is made on the rounded step.
  * Arguments as in loco_compensate_quantize / loco_dequant_reduce except that the
- * steps are uint16_t bf16 bit patterns (array base 4-byte aligned; stride in
- * elements, any parity).
+ * steps are uint16_t bf16 bit patterns (scales_out_bf16 2-byte aligned, so a
+ * payload may be written anywhere into a receive buffer; the reduce wants the
+ * base of that buffer 4-byte aligned, stride in elements of any parity).
  */
 loco_status_t loco_compensate_quantize_bf16_scales(const void *grad, loco_dtype_t grad_dtype, float *err_state,
                                                    size_t n, int bits, int block_size, float beta, int reset,

@@ -320,7 +320,7 @@ loco_status_t compress_block(const void* grad, loco_dtype_t grad_dtype, float cl
     if (!(clip_abs > 0.0f)) return LOCO_ERR_INVALID_ARG;               // NaN, zero, negative
     if (n == 0) return LOCO_OK;
     if (!grad || !err_state || !codes_out || !scales_out) return LOCO_ERR_INVALID_ARG;
-    if (!aligned(grad, 16) || !aligned(err_state, 16) || !aligned(codes_out, 16) || !aligned(scales_out, 4))
+    if (!aligned(grad, 16) || !aligned(err_state, 16) || !aligned(codes_out, 16) || !aligned(scales_out, step_bytes))
         return LOCO_ERR_ALIGNMENT;
     const size_t gsz = grad_dtype == LOCO_BF16 ? 2 : 4;
     if (loco_status_t st = check_device_range(grad, n * gsz)) return st;
