@@ -37,6 +37,13 @@ MEASURED_TRAFFIC = {
     ("llama7b_shard_8bit_b64", "loco_dequant_reduce"): 1.05485e10,
     ("llama7b_shard_4bit_b256", "loco_compensate_quantize_fixed"): 3.7904e9,
     ("llama7b_shard_4bit_b256", "loco_dequant_reduce_fixed"): 6.7384e9,
+    ("llama7b_shard_4bit_b256", "loco_compensate_quantize_clip"): 8.8753e9,
+    ("llama7b_shard_4bit_b256", "loco_dequant_reduce_sgd"): 1.03412e10,
+    ("llama7b_shard_4bit_b256", "loco_dequant_reduce_adam"): 2.38180e10,
+    ("llama7b_shard_4bit_b256", "loco_dequant_reduce_fixed_adam"): 2.35843e10,
+    ("llama7b_shard_4bit_b256", "loco_dequant_reduce_bf16"): 5.2874e9,
+    ("llama7b_shard_8bit_b64", "loco_compensate_quantize_bf16_scales"): 9.3179e9,
+    ("llama7b_shard_8bit_b64", "loco_dequant_reduce_bf16_scales"): 1.03412e10,
 }
 
 
@@ -57,6 +64,8 @@ def parse_args():
                     help="type the averaged gradient is written in (bf16: rounded to nearest even)")
     ap.add_argument("--scales", choices=["f32", "bf16"], default="f32",
                     help="block form only: keep the block steps in bf16 (rounded before use)")
+    ap.add_argument("--clip-abs", type=float, default=None,
+                    help="clip the gradient element-wise to [-c, c] before compensation (Sec. 5.2)")
     ap.add_argument("--no-copy-ceiling", action="store_true")
     return ap.parse_args()
 
@@ -146,7 +155,8 @@ def main():
                                       loco_dequant_reduce_fixed_adam, loco_dequant_reduce_fixed_sgd,
                                       loco_dequant_reduce_sgd, loco_error_state8_init, loco_error_state_init,
                                       loco_num_blocks, workloads)
-    from paper_2407_04480_amd.binding import (loco_stream_copy, loco_device_info,
+    from paper_2407_04480_amd.binding import (loco_stream_copy, loco_device_info, loco_compensate_quantize_clip,
+                                              loco_compensate_quantize_fixed_clip,
                                               loco_compensate_quantize_bf16_scales,
                                               loco_dequant_reduce_bf16_scales)
 
@@ -176,8 +186,11 @@ def main():
         bytes_dr -= 2
         names = (names[0], names[1] + "_bf16")
     bf16_steps = args.scales == "bf16"
+    clip = args.clip_abs
+    if clip is not None:
+        names = (names[0] + "_clip", names[1])
     if bf16_steps:
-        if form != "block" or opt != "none" or args.out != "f32":
+        if form != "block" or opt != "none" or args.out != "f32" or clip is not None:
             print("bench.py: --scales bf16 goes with --form block, no optimizer and fp32 output", file=sys.stderr)
             return 2
         bytes_cq -= 2.0 / B
@@ -206,6 +219,8 @@ def main():
         def cq(g, e, codes, scales):
             if bf16_steps:
                 loco_compensate_quantize_bf16_scales(g, e, bits, B, w.beta, False, codes, scales, stream)
+            elif clip is not None:
+                loco_compensate_quantize_clip(g, clip, e, bits, B, w.beta, False, codes, scales, stream)
             else:
                 loco_compensate_quantize(g, e, bits, B, w.beta, False, codes, scales, stream)
 
@@ -227,7 +242,11 @@ def main():
             loco_error_state8_init(e, stream)
 
         def cq(g, e, codes, scales):
-            loco_compensate_quantize_fixed(g, e, bits, FIXED_LOG2_S, FIXED_SE_MULT, w.beta, False, codes, stream)
+            if clip is not None:
+                loco_compensate_quantize_fixed_clip(g, clip, e, bits, FIXED_LOG2_S, FIXED_SE_MULT, w.beta, False,
+                                                    codes, stream)
+            else:
+                loco_compensate_quantize_fixed(g, e, bits, FIXED_LOG2_S, FIXED_SE_MULT, w.beta, False, codes, stream)
 
         def dr():
             if opt == "none" and args.out == "bf16":
@@ -309,7 +328,7 @@ def main():
         del src, dst
 
     cpu = None
-    if args.cpu_sample > 0 and opt == "none" and args.out == "f32" and not bf16_steps:
+    if args.cpu_sample > 0 and opt == "none" and args.out == "f32" and not bf16_steps and clip is None:
         # own payload for the sample: one compensate-quantize step from a zero state
         state_init(err)
         cq(grads[0], err, own_codes, own_scales)
@@ -330,7 +349,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "n": n, "grad_dtype": str(w.grad_dtype).replace("torch.", ""),
-                   "bits": bits, "beta": w.beta, "num_workers": W, "form": form, "optimizer": opt, "out": args.out, "scales": args.scales,
+                   "bits": bits, "beta": w.beta, "num_workers": W, "form": form, "optimizer": opt, "out": args.out, "scales": args.scales, "clip_abs": clip,
                    **({"block_size": B} if form == "block" else
                       {"log2_s": FIXED_LOG2_S, "se_mult": FIXED_SE_MULT, "state": "int8"}),
                    "step": " + ".join(n_[5:] for n_ in names)},

@@ -197,6 +197,9 @@ EpilogueArgs make_epilogue(float* out, float* theta, float* m, float* v, float e
 // Launch shapes of the fixed-scale kernels (units of 512 elements per wavefront).
 struct FixedCqShape { static constexpr int kUnits = 2, kThreads = 128; };
 struct FixedDrShape { static constexpr int kSlots = 2, kThreads = 128, kInFlight = 4; };
+struct FixedDrWideShape { static constexpr int kSlots = 1, kThreads = 256, kInFlight = 4; };  // Adam, as DrShapeFor
+template <Epilogue EPI>
+using FixedDrShapeFor = std::conditional_t<EPI == Epilogue::kAdam, FixedDrWideShape, FixedDrShape>;
 
 bool fixed_args_ok(int bits, int log2_s, int se_mult) {
     return (bits == 4 || bits == 8) && log2_s >= -64 && log2_s <= 64 && se_mult >= 1 && se_mult <= 64;
@@ -270,12 +273,13 @@ loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const
 template <Epilogue EPI>
 void launch_fixed_dr(int bits, unsigned grid, hipStream_t s, const uint8_t* codes, size_t cs, int W,
                             size_t n, float inv_s, float inv_w, const EpilogueArgs& epi) {
+    using Shape = FixedDrShapeFor<EPI>;
     if (bits == 4)
-        fixed_dr_kernel<4, FixedDrShape::kSlots, FixedDrShape::kThreads, FixedDrShape::kInFlight, kNonTemporal, EPI>
-            <<<dim3(grid), dim3(FixedDrShape::kThreads), 0, s>>>(codes, cs, W, n, inv_s, inv_w, epi);
+        fixed_dr_kernel<4, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI>
+            <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(codes, cs, W, n, inv_s, inv_w, epi);
     else
-        fixed_dr_kernel<8, FixedDrShape::kSlots, FixedDrShape::kThreads, FixedDrShape::kInFlight, kNonTemporal, EPI>
-            <<<dim3(grid), dim3(FixedDrShape::kThreads), 0, s>>>(codes, cs, W, n, inv_s, inv_w, epi);
+        fixed_dr_kernel<8, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI>
+            <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(codes, cs, W, n, inv_s, inv_w, epi);
 }
 
 loco_status_t reduce_fixed(const uint8_t* codes, size_t code_stride_bytes, int num_workers, size_t n,
@@ -296,8 +300,10 @@ loco_status_t reduce_fixed(const uint8_t* codes, size_t code_stride_bytes, int n
     if (loco_status_t st = check_device_range(codes, (W - 1) * code_stride_bytes + cb)) return st;
     if (loco_status_t st = check_epilogue(kind, epi, n)) return st;
     unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kSlot * FixedDrShape::kSlots * (FixedDrShape::kThreads / kWave), &grid))
-        return st;
+    const size_t per_group = kind == Epilogue::kAdam
+        ? (size_t)kSlot * FixedDrWideShape::kSlots * (FixedDrWideShape::kThreads / kWave)
+        : (size_t)kSlot * FixedDrShape::kSlots * (FixedDrShape::kThreads / kWave);
+    if (loco_status_t st = grid_for(n, per_group, &grid)) return st;
     const float inv_s = std::ldexp(1.0f, -log2_s), inv_w = 1.0f / (float)num_workers;
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (kind) {
