@@ -155,7 +155,7 @@ def main():
                                       loco_dequant_reduce_fixed_adam, loco_dequant_reduce_fixed_sgd,
                                       loco_dequant_reduce_sgd, loco_error_state8_init, loco_error_state_init,
                                       loco_num_blocks, workloads)
-    from paper_2407_04480_amd.binding import (loco_stream_copy, loco_device_info, loco_compensate_quantize_clip,
+    from paper_2407_04480_amd.binding import (loco_stream_copy, loco_stream_read, loco_stream_fill, loco_device_info, loco_compensate_quantize_clip,
                                               loco_compensate_quantize_fixed_clip,
                                               loco_compensate_quantize_bf16_scales,
                                               loco_dequant_reduce_bf16_scales)
@@ -310,22 +310,32 @@ def main():
     k_dr = kernel_entry(names[1], bytes_dr, dr_avg, dr_ms)
     dominant = k_cq if cq_avg >= dr_avg else k_dr
 
-    copy_gbps = None
+    # What the memory system sustains for plain streams of 2 GiB in the same run: the ceiling
+    # of a pure read stream, a pure write stream and a one-to-one copy.
+    copy_gbps, ceilings = None, None
     if not args.no_copy_ceiling:
         nbytes = 1 << 31
         src = torch.empty(nbytes, dtype=torch.uint8, device=dev)
         dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        sink = torch.zeros(16, dtype=torch.uint8, device=dev)
         src.zero_()
-        for _ in range(2):
-            loco_stream_copy(dst, src, stream)
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record(stream)
-        for _ in range(10):
-            loco_stream_copy(dst, src, stream)
-        b.record(stream)
-        torch.cuda.synchronize()
-        copy_gbps = 2 * nbytes * 10 / (a.elapsed_time(b) * 1e-3) / 1e9
-        del src, dst
+
+        def timed(fn, moved):
+            for _ in range(2):
+                fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(10):
+                fn()
+            b.record(stream)
+            torch.cuda.synchronize()
+            return moved * 10 / (a.elapsed_time(b) * 1e-3) / 1e9
+
+        copy_gbps = timed(lambda: loco_stream_copy(dst, src, stream), 2 * nbytes)
+        ceilings = {"copy": copy_gbps,
+                    "read_only": timed(lambda: loco_stream_read(src, sink, stream), nbytes),
+                    "write_only": timed(lambda: loco_stream_fill(dst, stream), nbytes)}
+        del src, dst, sink
 
     cpu = None
     if args.cpu_sample > 0 and opt == "none" and args.out == "f32" and not bf16_steps and clip is None:
@@ -359,6 +369,7 @@ def main():
         | {"kernel": dominant["kernel"]},
         "kernels": [k_cq, k_dr],
         "copy_ceiling_GBps": copy_gbps,
+        "stream_ceilings_GBps": ceilings,
         "device": device_report(loco_device_info()),
         "cpu_baseline": cpu,
     }

@@ -10,7 +10,8 @@
  * the caller's.
  *
  * Conventions for every call
- *   - All data pointers are DEVICE pointers on the current HIP device; the caller
+ *   - All data pointers are DEVICE pointers on the current HIP device (memory of another
+ *     device is refused with LOCO_ERR_BAD_POINTER while pointer checks are on); the caller
  *     owns every buffer.  The library allocates nothing, frees nothing and never
  *     synchronises: work is enqueued on `stream` (a hipStream_t passed as void*,
  *     NULL = the default stream) and is ordered by it.
@@ -237,12 +238,20 @@ loco_status_t loco_dequant_reduce_bf16_scales(const uint8_t *codes, size_t code_
                                               float *grad_out, void *stream);
 
 /*
- * Measurement aid, not part of the method: dst[i] = src[i] for `bytes` bytes
- * (a multiple of 16, both pointers 16-byte aligned) with the same load/store
- * shape as the kernels above.  Gives the practical HBM ceiling and the scale
- * factor for hardware byte counters.
+ * Measurement aids, not part of the method: plain streaming kernels with the same
+ * 16-byte-per-lane accesses as the kernels above, each in the launch shape that is
+ * fastest for it.  They give the practical HBM ceiling for a pure read stream, a pure
+ * write stream and a one-to-one mix, and the scale factor for hardware byte counters.
+ * `bytes` is a multiple of 16 and every pointer 16-byte aligned.
+ *   loco_stream_copy  dst[i] = src[i]
+ *   loco_stream_read  reads all of src; sink16 is 16 bytes of device memory that may be
+ *                     written (only if a lane's four words xor to a fixed constant, which
+ *                     keeps the loads alive without a store stream)
+ *   loco_stream_fill  dst[i] = 0
  */
 loco_status_t loco_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
+loco_status_t loco_stream_read(const void *src, size_t bytes, void *sink16, void *stream);
+loco_status_t loco_stream_fill(void *dst, size_t bytes, void *stream);
 
 /*
  * Measurement aid, not part of the method: what the current device reports

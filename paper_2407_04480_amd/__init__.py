@@ -28,6 +28,8 @@ from .binding import (  # noqa: F401
     loco_compensate_quantize_bf16_scales,
     loco_dequant_reduce_bf16_scales,
     loco_stream_copy,
+    loco_stream_read,
+    loco_stream_fill,
     loco_device_info,
 )
 
@@ -54,5 +56,7 @@ __all__ = [
     "loco_compensate_quantize_bf16_scales",
     "loco_dequant_reduce_bf16_scales",
     "loco_stream_copy",
+    "loco_stream_read",
+    "loco_stream_fill",
     "loco_device_info",
 ]

@@ -31,6 +31,8 @@ EXPORTS = (
     "loco_compensate_quantize_bf16_scales",
     "loco_dequant_reduce_bf16_scales",
     "loco_stream_copy",
+    "loco_stream_read",
+    "loco_stream_fill",
     "loco_device_info",
     "loco_reset_due",
     "loco_error_state8_init",
@@ -85,6 +87,8 @@ def load_library(path: Optional[str] = None):
     lib.loco_dequant_reduce_bf16_scales.argtypes = [vp, sz, vp, sz, i, sz, i, i, vp, vp]
     lib.loco_dequant_reduce_bf16_scales.restype = i
     lib.loco_stream_copy.argtypes, lib.loco_stream_copy.restype = [vp, vp, sz, vp], i
+    lib.loco_stream_read.argtypes, lib.loco_stream_read.restype = [vp, sz, vp, vp], i
+    lib.loco_stream_fill.argtypes, lib.loco_stream_fill.restype = [vp, sz, vp], i
     ip = ctypes.POINTER(ctypes.c_int)
     lib.loco_device_info.argtypes, lib.loco_device_info.restype = [ip, ip, ip, ip], i
     lib.loco_reset_due.argtypes, lib.loco_reset_due.restype = [c.c_longlong, c.c_longlong], i
@@ -254,6 +258,23 @@ def loco_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
         raise ValueError("dst too small")
     st = lib.loco_stream_copy(_dev_ptr(dst, "dst"), _dev_ptr(src, "src"), nbytes, _stream_handle(stream))
     _check("loco_stream_copy", st)
+
+
+def loco_stream_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """Reads all of src and writes (almost) nothing: the pure-read ceiling (measurement aid)."""
+    lib = load_library()
+    if sink.numel() * sink.element_size() < 16:
+        raise ValueError("sink must hold 16 bytes")
+    st = lib.loco_stream_read(_dev_ptr(src, "src"), src.numel() * src.element_size(), _dev_ptr(sink, "sink"),
+                              _stream_handle(stream))
+    _check("loco_stream_read", st)
+
+
+def loco_stream_fill(dst: torch.Tensor, stream=None) -> None:
+    """Zero fill with the kernels' store shape: the pure-write ceiling (measurement aid)."""
+    lib = load_library()
+    st = lib.loco_stream_fill(_dev_ptr(dst, "dst"), dst.numel() * dst.element_size(), _stream_handle(stream))
+    _check("loco_stream_fill", st)
 
 
 def loco_device_info() -> dict:

@@ -22,6 +22,10 @@ template <> struct CqShape<8> { static constexpr int kSlots = 2, kThreads = 64; 
 template <int BITS> struct DrShape;
 template <> struct DrShape<4> { static constexpr int kSlots = 2, kThreads = 128, kInFlight = 4; };
 template <> struct DrShape<8> { static constexpr int kSlots = 1, kThreads = 256, kInFlight = 4; };
+// With few workers the reduce is mostly a write stream, which measured 3-9 % faster with
+// 2 KB of output per wavefront and 8 KB per workgroup.
+struct DrFewWorkersShape { static constexpr int kSlots = 2, kThreads = 256, kInFlight = 4; };
+constexpr bool dr_few_workers(int bits, int W) { return bits == 4 ? W <= 4 : W == 1; }
 constexpr bool kNonTemporal = true;
 // Consecutive workgroups' tiles per XCD (see wave_tile_index).  Measured: compensate-
 // quantize is fastest with the hardware's own round robin (0); dequant-reduce loses
@@ -29,8 +33,11 @@ constexpr bool kNonTemporal = true;
 // of fetching it into all eight.
 constexpr int kCqXcdRun = 0;
 constexpr int kDrXcdRun = 32;
-constexpr int kCopySlots = 2;
-constexpr int kCopyThreads = 64;
+// Plain streaming kernels, each in the shape that measured fastest for its mix: a pure write
+// stream likes 4 KB per workgroup, a copy one wavefront per KB, a pure read 4 KB per wavefront.
+struct FillShape { static constexpr int kSlots = 1, kThreads = 256; };
+struct CopyShape { static constexpr int kSlots = 1, kThreads = 64; };
+struct ReadShape { static constexpr int kSlots = 4, kThreads = 64; };
 static_assert(CqShape<4>::kSlots % 2 == 0 && CqShape<8>::kSlots % 2 == 0,
               "block size 512 spans two slots of one wavefront");
 
@@ -49,6 +56,12 @@ loco_status_t check_device_range(const void* p, size_t bytes) {
         return LOCO_ERR_BAD_POINTER;
     }
     if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged) return LOCO_ERR_BAD_POINTER;
+    int current = -1;   // the kernels run on the current device: memory of another GPU is refused
+    if (hipGetDevice(&current) != hipSuccess) {
+        (void)hipGetLastError();
+        return LOCO_ERR_BAD_POINTER;
+    }
+    if (attr.type == hipMemoryTypeDevice && attr.device != current) return LOCO_ERR_BAD_POINTER;
     hipDeviceptr_t base = nullptr;
     size_t size = 0;
     if (hipMemGetAddressRange(&base, &size, const_cast<void*>(p)) != hipSuccess) {
@@ -128,10 +141,18 @@ struct DrArgs {
 template <int BITS, Epilogue EPI>
 using DrShapeFor = std::conditional_t<EPI == Epilogue::kAdam, DrShape<8>, DrShape<BITS>>;
 
-template <int BITS, int BLOCK, Epilogue EPI>
-void launch_dr(unsigned grid, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
+// Elements per workgroup of the shape launch_dr picks.
+size_t dr_elements_per_group(int bits, Epilogue kind, int W) {
+    if (kind == Epilogue::kAdam || (bits == 8 && !dr_few_workers(bits, W)))
+        return (size_t)kSlot * DrShape<8>::kSlots * (DrShape<8>::kThreads / kWave);
+    if (dr_few_workers(bits, W))
+        return (size_t)kSlot * DrFewWorkersShape::kSlots * (DrFewWorkersShape::kThreads / kWave);
+    return (size_t)kSlot * DrShape<4>::kSlots * (DrShape<4>::kThreads / kWave);
+}
+
+template <int BITS, int BLOCK, Epilogue EPI, typename Shape>
+void launch_dr_shape(unsigned grid, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
     const float inv_w = 1.0f / (float)a.W;
-    using Shape = DrShapeFor<BITS, EPI>;
     if constexpr (EPI == Epilogue::kStore) {   // bf16 steps are offered with the plain fp32 output only
         if (a.scales_bf16) {
             dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun, EPI, uint16_t>
@@ -144,6 +165,17 @@ void launch_dr(unsigned grid, hipStream_t s, const DrArgs& a, const EpilogueArgs
     dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun, EPI, float>
         <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.codes, a.code_stride, static_cast<const float*>(a.scales),
                                                       a.scale_stride, a.W, a.n, inv_w, epi);
+}
+
+template <int BITS, int BLOCK, Epilogue EPI>
+void launch_dr(unsigned grid, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
+    if constexpr (EPI != Epilogue::kAdam) {
+        if (dr_few_workers(BITS, a.W)) {
+            launch_dr_shape<BITS, BLOCK, EPI, DrFewWorkersShape>(grid, s, a, epi);
+            return;
+        }
+    }
+    launch_dr_shape<BITS, BLOCK, EPI, DrShapeFor<BITS, EPI>>(grid, s, a, epi);
 }
 
 template <int BITS, Epilogue EPI>
@@ -253,10 +285,9 @@ loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const
         return st;
     if (loco_status_t st = check_epilogue(kind, epi, n)) return st;
     unsigned grid;
-    const bool wide = bits == 8 || kind == Epilogue::kAdam;   // see DrShapeFor
-    const size_t per_group = wide ? (size_t)kSlot * DrShape<8>::kSlots * (DrShape<8>::kThreads / kWave)
-                                  : (size_t)kSlot * DrShape<4>::kSlots * (DrShape<4>::kThreads / kWave);
-    if (loco_status_t st = grid_for(n, per_group, &grid, kDrXcdRun ? 8 * kDrXcdRun : 1)) return st;
+    if (loco_status_t st = grid_for(n, dr_elements_per_group(bits, kind, num_workers), &grid,
+                                    kDrXcdRun ? 8 * kDrXcdRun : 1))
+        return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const DrArgs a{codes, code_stride_bytes, scales, scales_bf16, scale_stride_elems, num_workers, n};
     bool ok = false;
@@ -352,6 +383,17 @@ loco_status_t compress_block(const void* grad, loco_dtype_t grad_dtype, float cl
     return launched();
 }
 
+template <StreamMode MODE, typename Shape>
+loco_status_t launch_stream(void* dst, const void* src, size_t bytes, void* stream) {
+    const size_t n16 = bytes / 16;
+    unsigned grid;
+    if (loco_status_t st = grid_for(n16, (size_t)Shape::kThreads * Shape::kSlots, &grid)) return st;
+    stream_kernel<MODE, Shape::kSlots, Shape::kThreads, kNonTemporal>
+        <<<dim3(grid), dim3(Shape::kThreads), 0, static_cast<hipStream_t>(stream)>>>(
+            static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n16, 0x9E3779B9u);
+    return launched();
+}
+
 }  // namespace
 
 extern "C" {
@@ -387,9 +429,9 @@ loco_status_t loco_error_state_init(float* err_state, size_t n, void* stream) {
     if (!aligned(err_state, 16)) return LOCO_ERR_ALIGNMENT;
     if (loco_status_t st = check_device_range(err_state, n * sizeof(float))) return st;
     unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kCopyThreads * 4 * kCopySlots, &grid)) return st;
-    fill_zero_kernel<kCopySlots, kCopyThreads, kNonTemporal>
-        <<<dim3(grid), dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream)>>>(err_state, n);
+    if (loco_status_t st = grid_for(n, (size_t)FillShape::kThreads * 4 * FillShape::kSlots, &grid)) return st;
+    fill_zero_kernel<FillShape::kSlots, FillShape::kThreads, kNonTemporal>
+        <<<dim3(grid), dim3(FillShape::kThreads), 0, static_cast<hipStream_t>(stream)>>>(err_state, n);
     return launched();
 }
 
@@ -460,12 +502,24 @@ loco_status_t loco_stream_copy(void* dst, const void* src, size_t bytes, void* s
     if (bytes % 16 != 0 || !aligned(dst, 16) || !aligned(src, 16)) return LOCO_ERR_ALIGNMENT;
     if (loco_status_t st = check_device_range(dst, bytes)) return st;
     if (loco_status_t st = check_device_range(src, bytes)) return st;
-    const size_t n16 = bytes / 16;
-    unsigned grid;
-    if (loco_status_t st = grid_for(n16, (size_t)kCopyThreads * kCopySlots, &grid)) return st;
-    copy_kernel<kCopySlots, kCopyThreads, kNonTemporal><<<dim3(grid), dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream)>>>(
-        static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n16);
-    return launched();
+    return launch_stream<StreamMode::kCopy, CopyShape>(dst, src, bytes, stream);
+}
+
+loco_status_t loco_stream_read(const void* src, size_t bytes, void* sink16, void* stream) {
+    if (bytes == 0) return LOCO_OK;
+    if (!src || !sink16) return LOCO_ERR_INVALID_ARG;
+    if (bytes % 16 != 0 || !aligned(src, 16) || !aligned(sink16, 16)) return LOCO_ERR_ALIGNMENT;
+    if (loco_status_t st = check_device_range(src, bytes)) return st;
+    if (loco_status_t st = check_device_range(sink16, 16)) return st;
+    return launch_stream<StreamMode::kRead, ReadShape>(sink16, src, bytes, stream);
+}
+
+loco_status_t loco_stream_fill(void* dst, size_t bytes, void* stream) {
+    if (bytes == 0) return LOCO_OK;
+    if (!dst) return LOCO_ERR_INVALID_ARG;
+    if (bytes % 16 != 0 || !aligned(dst, 16)) return LOCO_ERR_ALIGNMENT;
+    if (loco_status_t st = check_device_range(dst, bytes)) return st;
+    return launch_stream<StreamMode::kFill, FillShape>(dst, nullptr, bytes, stream);
 }
 
 loco_status_t loco_device_info(int* memory_clock_khz, int* memory_bus_bits, int* compute_units,
@@ -495,9 +549,9 @@ loco_status_t loco_error_state8_init(int8_t* err_state8, size_t n, void* stream)
     if (!aligned(err_state8, 16)) return LOCO_ERR_ALIGNMENT;
     if (loco_status_t st = check_device_range(err_state8, n)) return st;
     unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kCopyThreads * 16 * kCopySlots, &grid)) return st;
-    fill_zero_bytes_kernel<kCopySlots, kCopyThreads, kNonTemporal>
-        <<<dim3(grid), dim3(kCopyThreads), 0, static_cast<hipStream_t>(stream)>>>(
+    if (loco_status_t st = grid_for(n, (size_t)FillShape::kThreads * 16 * FillShape::kSlots, &grid)) return st;
+    fill_zero_bytes_kernel<FillShape::kSlots, FillShape::kThreads, kNonTemporal>
+        <<<dim3(grid), dim3(FillShape::kThreads), 0, static_cast<hipStream_t>(stream)>>>(
             reinterpret_cast<uint8_t*>(err_state8), n);
     return launched();
 }

@@ -558,7 +558,7 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __rest
     }
 }
 
-// ---- helpers: zero fill and plain copy in the same shape (16 bytes per lane and slot) ----
+// ---- helpers: zero fill of the state, plain streaming kernels (16 bytes per lane and slot) ----
 template <int SLOTS, int THREADS, bool NT>
 __global__ void __launch_bounds__(THREADS)
 fill_zero_kernel(float* __restrict__ dst, size_t n) {
@@ -576,9 +576,13 @@ fill_zero_kernel(float* __restrict__ dst, size_t n) {
     }
 }
 
-template <int SLOTS, int THREADS, bool NT>
+// Plain streaming kernels for measuring what the memory system sustains for a given mix of
+// reads and writes: kCopy dst = src; kRead loads src and stores (to sink) only if the words of
+// a lane's 16 bytes xor to `never`, so that the loads cannot be dropped; kFill writes zeros.
+enum class StreamMode { kCopy, kRead, kFill };
+template <StreamMode MODE, int SLOTS, int THREADS, bool NT>
 __global__ void __launch_bounds__(THREADS)
-copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n16) {
+stream_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n16, uint32_t never) {
     const int lane = threadIdx.x & (kWave - 1);
     const size_t wave = (size_t)blockIdx.x * (THREADS / kWave) + (threadIdx.x >> 6);
     const size_t tile0 = wave * ((size_t)kWave * SLOTS);
@@ -586,12 +590,18 @@ copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n16) 
 #pragma unroll
     for (int s = 0; s < SLOTS; ++s) {
         const size_t i = tile0 + (size_t)s * kWave + lane;
-        if (i < n16) v[s] = vload<NT>(src + i);
+        v[s] = u32x4{0u, 0u, 0u, 0u};
+        if constexpr (MODE != StreamMode::kFill)
+            if (i < n16) v[s] = vload<NT>(src + i);
     }
 #pragma unroll
     for (int s = 0; s < SLOTS; ++s) {
         const size_t i = tile0 + (size_t)s * kWave + lane;
-        if (i < n16) vstore<NT>(dst + i, v[s]);
+        if constexpr (MODE == StreamMode::kRead) {
+            if (i < n16 && (v[s].x ^ v[s].y ^ v[s].z ^ v[s].w) == never) dst[0] = v[s];
+        } else {
+            if (i < n16) vstore<NT>(dst + i, v[s]);
+        }
     }
 }
 

@@ -74,6 +74,10 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.loco_dequant_reduce(one, 40, one, 2, 2, 64, 4, 32, one, null) == 3
     assert lib.loco_error_state_init(ctypes.c_void_p(4), 8, null) == 3
     assert lib.loco_stream_copy(one, one, 24, null) == 3
+    assert lib.loco_stream_read(one, 24, one, null) == 3
+    assert lib.loco_stream_fill(ctypes.c_void_p(8), 32, null) == 3
+    assert lib.loco_stream_read(null, 32, one, null) == 1
+    assert lib.loco_stream_fill(null, 0, null) == 0
 
 
 def test_missing_library_is_an_error(tmp_path):

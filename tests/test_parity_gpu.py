@@ -258,3 +258,37 @@ def test_pointer_and_argument_errors_on_gpu():
     st = lib.loco_error_state_init(ctypes.c_void_p(host.ctypes.data), n, None)
     assert st == 5
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("nbytes", [16, 1008, 1024, 4096 + 16, 3 * 65536 + 48, (1 << 24) + 16])
+def test_stream_measurement_aids(nbytes):
+    """The plain copy / read / fill kernels behind bench.py's ceilings do what they say."""
+    from paper_2407_04480_amd import loco_stream_copy, loco_stream_fill, loco_stream_read
+    rng = torch.Generator(device="cpu").manual_seed(nbytes)
+    src = torch.randint(0, 256, (nbytes,), generator=rng, dtype=torch.uint8).to(DEV)
+    dst = torch.full((nbytes + 16,), 0x5A, dtype=torch.uint8, device=DEV)
+    loco_stream_copy(dst[:nbytes], src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:nbytes], src) and int(dst[nbytes:].min()) == 0x5A     # nothing past the end
+    sink = torch.full((16,), 0x33, dtype=torch.uint8, device=DEV)
+    before = src.clone()
+    loco_stream_read(src, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(src, before)
+    loco_stream_fill(dst[:nbytes])
+    torch.cuda.synchronize()
+    assert int(dst[:nbytes].max()) == 0 and int(dst[nbytes:].min()) == 0x5A
+
+
+@pytest.mark.parametrize("n", [1, 3, 4, 1023, 1024, 1025, 4099, 1 << 20])
+def test_state_init_sizes(n):
+    """Both state initialisers write exactly n zeros (Eq. 5: e~_0 = 0) and nothing beyond."""
+    from paper_2407_04480_amd import loco_error_state8_init
+    pad = 16
+    e = torch.full((n + pad,), 7.0, dtype=torch.float32, device=DEV)
+    loco_error_state_init(e[:n])
+    e8 = torch.full((n + pad,), 7, dtype=torch.int8, device=DEV)
+    loco_error_state8_init(e8[:n])
+    torch.cuda.synchronize()
+    assert not e[:n].any() and bool((e[n:] == 7.0).all())
+    assert not e8[:n].any() and bool((e8[n:] == 7).all())
