@@ -35,12 +35,16 @@ MEASURED_TRAFFIC = {
     ("llama7b_shard_4bit_b256", "loco_dequant_reduce"): 6.9720e9,
     ("llama7b_shard_8bit_b64", "loco_compensate_quantize"): 9.3179e9,
     ("llama7b_shard_8bit_b64", "loco_dequant_reduce"): 1.05485e10,
+    ("mixtral_moe_shard_4bit_b128", "loco_compensate_quantize"): 1.48414e10,
+    ("mixtral_moe_shard_4bit_b128", "loco_dequant_reduce"): 6.3858e9,
+    ("dense70b_shard_4bit_b256", "loco_compensate_quantize"): 2.31829e10,
+    ("dense70b_shard_4bit_b256", "loco_dequant_reduce"): 2.76200e10,
     ("llama7b_shard_4bit_b256", "loco_compensate_quantize_fixed"): 3.7904e9,
     ("llama7b_shard_4bit_b256", "loco_dequant_reduce_fixed"): 6.7384e9,
-    ("llama7b_shard_4bit_b256", "loco_compensate_quantize_clip"): 8.8753e9,
-    ("llama7b_shard_4bit_b256", "loco_dequant_reduce_sgd"): 1.03412e10,
+    ("llama7b_shard_4bit_b256", "loco_compensate_quantize_clip"): 8.8752e9,
+    ("llama7b_shard_4bit_b256", "loco_dequant_reduce_sgd"): 1.03411e10,
     ("llama7b_shard_4bit_b256", "loco_dequant_reduce_adam"): 2.38180e10,
-    ("llama7b_shard_4bit_b256", "loco_dequant_reduce_fixed_adam"): 2.35843e10,
+    ("llama7b_shard_4bit_b256", "loco_dequant_reduce_fixed_adam"): 2.35842e10,
     ("llama7b_shard_4bit_b256", "loco_dequant_reduce_bf16"): 5.2874e9,
     ("llama7b_shard_8bit_b64", "loco_compensate_quantize_bf16_scales"): 9.3179e9,
     ("llama7b_shard_8bit_b64", "loco_dequant_reduce_bf16_scales"): 1.03412e10,

@@ -137,13 +137,15 @@ struct DrArgs {
     size_t n;
 };
 
-// With Adam's three in-place fp32 streams one slot per wavefront and 256 threads measured best.
+// With fp32 arrays updated in place behind the decode (theta; m and v for Adam) one slot per
+// wavefront and 256 threads measured best, whatever the worker count.
+constexpr bool dr_updates_in_place(Epilogue e) { return e == Epilogue::kSgd || e == Epilogue::kAdam; }
 template <int BITS, Epilogue EPI>
-using DrShapeFor = std::conditional_t<EPI == Epilogue::kAdam, DrShape<8>, DrShape<BITS>>;
+using DrShapeFor = std::conditional_t<dr_updates_in_place(EPI), DrShape<8>, DrShape<BITS>>;
 
 // Elements per workgroup of the shape launch_dr picks.
 size_t dr_elements_per_group(int bits, Epilogue kind, int W) {
-    if (kind == Epilogue::kAdam || (bits == 8 && !dr_few_workers(bits, W)))
+    if (dr_updates_in_place(kind) || (bits == 8 && !dr_few_workers(bits, W)))
         return (size_t)kSlot * DrShape<8>::kSlots * (DrShape<8>::kThreads / kWave);
     if (dr_few_workers(bits, W))
         return (size_t)kSlot * DrFewWorkersShape::kSlots * (DrFewWorkersShape::kThreads / kWave);
@@ -169,7 +171,7 @@ void launch_dr_shape(unsigned grid, hipStream_t s, const DrArgs& a, const Epilog
 
 template <int BITS, int BLOCK, Epilogue EPI>
 void launch_dr(unsigned grid, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
-    if constexpr (EPI != Epilogue::kAdam) {
+    if constexpr (!dr_updates_in_place(EPI)) {
         if (dr_few_workers(BITS, a.W)) {
             launch_dr_shape<BITS, BLOCK, EPI, DrFewWorkersShape>(grid, s, a, epi);
             return;

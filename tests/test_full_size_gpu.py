@@ -176,3 +176,74 @@ def test_full_size_exact_reconstruction():
     # Lemma 5: |h - d| <= D/2 (+ rounding of 1/D), for every element
     step = scales.repeat_interleave(B)[:n]
     assert bool((err.abs() <= step * (0.5 + 2.0 ** -18)).all())
+
+
+@pytest.mark.parametrize("name,steps", [("llama7b_shard_4bit_b256", 2), ("llama7b_shard_8bit_b64", 2),
+                                        ("mixtral_moe_shard_4bit_b128", 3), ("dense70b_shard_4bit_b256", 1)])
+def test_full_size_every_element(name, steps, capsys):
+    """A workload compared with the oracle over the WHOLE array, not a sample: a few steps of
+    compensate-quantize (every code byte, every block step, every state value) and the reduce
+    over the W payloads (every element of the averaged gradient; the largest workload has more
+    than 2^31 elements and 16 payloads).  The oracle runs on all host threads over disjoint
+    block ranges, which gives the bytes of its single-threaded run."""
+    import os
+
+    def print(*a, **k):   # progress lines reach the terminal also when pytest captures output
+        import builtins
+        with capsys.disabled():
+            builtins.print(*a, **k)
+
+    w = workloads.by_name(name)
+    n, bits, B, W = w.n, w.bits, w.block_size, w.num_workers
+    threads = max(1, min(16, os.cpu_count() or 1))
+    cb, nb = loco_code_bytes(n, bits), loco_num_blocks(n, B)
+    cstride = (cb + 15) // 16 * 16
+    print(f"[{name}] whole array: n={n} bits={bits} B={B} W={W} oracle threads={threads}", flush=True)
+    err = torch.empty(n, dtype=torch.float32, device=DEV)
+    loco_error_state_init(err)
+    recv_codes = torch.zeros(W * cstride, dtype=torch.uint8, device=DEV)
+    recv_scales = torch.zeros(W * nb, dtype=torch.float32, device=DEV)
+    e_ref = np.zeros(n, np.float32)
+    ref_codes = np.zeros((W, cstride), np.uint8)
+    ref_scales = np.zeros((W, nb), np.float32)
+    for step in range(steps):
+        g = workloads.gradient(w, step, device=DEV)
+        loco_compensate_quantize(g, err, bits, B, w.beta, False, recv_codes[:cb], recv_scales[:nb])
+        c_ref, s_ref = oracle.compensate_quantize(host_grad(g), e_ref, bits, B, w.beta, threads=threads)
+        torch.cuda.synchronize()
+        del g
+        assert np.array_equal(recv_codes[:cb].cpu().numpy(), c_ref), f"step {step}: code bytes differ"
+        assert np.array_equal(recv_scales[:nb].cpu().numpy().view(np.uint32), s_ref.view(np.uint32)), \
+            f"step {step}: block steps differ"
+        e_gpu = err.cpu().numpy()
+        bad = int(np.count_nonzero(e_gpu != e_ref))
+        assert bad == 0, f"step {step}: {bad} of {n} state values differ"
+        del e_gpu
+        print(f"[{name}] step {step}: codes, steps and state identical over {n} elements", flush=True)
+    ref_codes[0, :cb], ref_scales[0] = c_ref, s_ref
+    del c_ref, s_ref, e_ref
+    tmp = torch.empty(n, dtype=torch.float32, device=DEV)
+    zero = np.zeros(n, np.float32)
+    for k in range(1, W):
+        gk = workloads.gradient(w, 0, worker=k, device=DEV)
+        loco_error_state_init(tmp)
+        loco_compensate_quantize(gk, tmp, bits, B, w.beta, False, recv_codes[k * cstride:k * cstride + cb],
+                                 recv_scales[k * nb:(k + 1) * nb])
+        zero[:] = 0
+        ref_codes[k, :cb], ref_scales[k] = oracle.compensate_quantize(host_grad(gk), zero, bits, B, w.beta,
+                                                                      threads=threads)
+        del gk
+    del tmp, zero
+    torch.cuda.synchronize()
+    assert np.array_equal(recv_codes.cpu().numpy(), ref_codes.reshape(-1)), "a peer's payload differs"
+    out = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    loco_dequant_reduce(recv_codes, cstride, recv_scales, nb, W, n, bits, B, out)
+    want = oracle.dequant_reduce(ref_codes.reshape(-1), ref_scales.reshape(-1), W, n, bits, B, cstride, nb,
+                                 threads=threads)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    top = float(np.abs(want).max())
+    assert float(np.abs(got - want).max()) <= 1e-6 * top
+    bad = int(np.count_nonzero(got != want))
+    assert bad == 0, f"{bad} of {n} averaged values differ"
+    print(f"[{name}] reduce over W={W}: identical over {n} elements", flush=True)

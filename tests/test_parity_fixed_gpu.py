@@ -177,6 +177,45 @@ def test_fixed_full_size_sampled():
     assert bool(torch.isfinite(out).all())
 
 
+def test_fixed_full_size_every_element(capsys):
+    """The 7B shard over the WHOLE array for Algorithm 1 as printed (s = 2^19, s_e = 6s, so the
+    state decode takes the corrected-quotient path): two steps, every code byte and every 8-bit
+    state value, then Eq. 8 over the W payloads, every element."""
+    import os
+    w = workloads.by_name("llama7b_shard_4bit_b256")
+    n, bits, log2_s, mult, W = w.n, 4, 19, 6, 8
+    threads = max(1, min(16, os.cpu_count() or 1))
+    cb = loco_code_bytes(n, bits)
+    stride = (cb + 15) // 16 * 16
+    recv = torch.zeros(W * stride, dtype=torch.uint8, device=DEV)
+    ref = np.zeros((W, stride), np.uint8)
+    err = torch.empty(n, dtype=torch.int8, device=DEV)
+    loco_error_state8_init(err)
+    e_ref = np.zeros(n, np.int8)
+    for k in range(W):
+        for step in range(2 if k == 0 else 1):
+            g = (workloads.gradient(w, step, worker=None if k == 0 else k, device=DEV) * 1e-2).to(torch.bfloat16)
+            if k:
+                loco_error_state8_init(err)
+                e_ref[:] = 0
+            loco_compensate_quantize_fixed(g, err, bits, log2_s, mult, w.beta, False, recv[k * stride:k * stride + cb])
+            ref[k, :cb] = oracle.fixed_compensate_quantize(workloads.as_numpy_grad(g), e_ref, bits, log2_s, mult,
+                                                           w.beta, threads=threads)
+            torch.cuda.synchronize()
+            del g
+            assert np.array_equal(recv[k * stride:k * stride + cb].cpu().numpy(), ref[k, :cb]), f"w={k} step={step}: codes"
+            assert np.array_equal(err.cpu().numpy(), e_ref), f"w={k} step={step}: state"
+            with capsys.disabled():
+                print(f"[fixed, whole array] worker {k} step {step}: codes and state identical over {n} elements",
+                      flush=True)
+    out = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    loco_dequant_reduce_fixed(recv, stride, W, n, bits, log2_s, out)
+    want = oracle.fixed_dequant_reduce(ref.reshape(-1), W, n, bits, log2_s, code_stride_bytes=stride, threads=threads)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert int(np.count_nonzero(got != want)) == 0
+
+
 def test_fixed_argument_errors():
     n = 4096
     g = torch.zeros(n, device=DEV)
