@@ -159,7 +159,7 @@ def main():
                                       loco_dequant_reduce_fixed_adam, loco_dequant_reduce_fixed_sgd,
                                       loco_dequant_reduce_sgd, loco_error_state8_init, loco_error_state_init,
                                       loco_num_blocks, workloads)
-    from paper_2407_04480_amd.binding import (loco_stream_copy, loco_stream_read, loco_stream_fill, loco_device_info, loco_compensate_quantize_clip,
+    from paper_2407_04480_amd.binding import (loco_stream_copy, loco_stream_read, loco_stream_fill, loco_stream_sum2, loco_device_info, loco_compensate_quantize_clip,
                                               loco_compensate_quantize_fixed_clip,
                                               loco_compensate_quantize_bf16_scales,
                                               loco_dequant_reduce_bf16_scales)
@@ -315,7 +315,7 @@ def main():
     dominant = k_cq if cq_avg >= dr_avg else k_dr
 
     # What the memory system sustains for plain streams of 2 GiB in the same run: the ceiling
-    # of a pure read stream, a pure write stream and a one-to-one copy.
+    # of a pure read stream, a pure write stream, a one-to-one copy and two reads per write.
     copy_gbps, ceilings = None, None
     if not args.no_copy_ceiling:
         nbytes = 1 << 31
@@ -339,7 +339,9 @@ def main():
         ceilings = {"copy": copy_gbps,
                     "read_only": timed(lambda: loco_stream_read(src, sink, stream), nbytes),
                     "write_only": timed(lambda: loco_stream_fill(dst, stream), nbytes)}
-        del src, dst, sink
+        src2 = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+        ceilings["two_reads_one_write"] = timed(lambda: loco_stream_sum2(dst, src, src2, stream), 3 * nbytes)
+        del src, src2, dst, sink
 
     cpu = None
     if args.cpu_sample > 0 and opt == "none" and args.out == "f32" and not bf16_steps and clip is None:

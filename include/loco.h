@@ -241,17 +241,20 @@ loco_status_t loco_dequant_reduce_bf16_scales(const uint8_t *codes, size_t code_
  * Measurement aids, not part of the method: plain streaming kernels with the same
  * 16-byte-per-lane accesses as the kernels above, each in the launch shape that is
  * fastest for it.  They give the practical HBM ceiling for a pure read stream, a pure
- * write stream and a one-to-one mix, and the scale factor for hardware byte counters.
+ * write stream, a one-to-one mix and two reads per write (the mix of the compensate-
+ * quantize pass), and the scale factor for hardware byte counters.
  * `bytes` is a multiple of 16 and every pointer 16-byte aligned.
  *   loco_stream_copy  dst[i] = src[i]
  *   loco_stream_read  reads all of src; sink16 is 16 bytes of device memory that may be
  *                     written (only if a lane's four words xor to a fixed constant, which
  *                     keeps the loads alive without a store stream)
  *   loco_stream_fill  dst[i] = 0
+ *   loco_stream_sum2  dst[i] = src_a[i] + src_b[i] on 32-bit words (wrapping)
  */
 loco_status_t loco_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
 loco_status_t loco_stream_read(const void *src, size_t bytes, void *sink16, void *stream);
 loco_status_t loco_stream_fill(void *dst, size_t bytes, void *stream);
+loco_status_t loco_stream_sum2(void *dst, const void *src_a, const void *src_b, size_t bytes, void *stream);
 
 /*
  * Measurement aid, not part of the method: what the current device reports

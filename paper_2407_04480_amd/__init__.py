@@ -30,6 +30,7 @@ from .binding import (  # noqa: F401
     loco_stream_copy,
     loco_stream_read,
     loco_stream_fill,
+    loco_stream_sum2,
     loco_device_info,
 )
 
@@ -58,5 +59,6 @@ __all__ = [
     "loco_stream_copy",
     "loco_stream_read",
     "loco_stream_fill",
+    "loco_stream_sum2",
     "loco_device_info",
 ]

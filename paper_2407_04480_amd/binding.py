@@ -33,6 +33,7 @@ EXPORTS = (
     "loco_stream_copy",
     "loco_stream_read",
     "loco_stream_fill",
+    "loco_stream_sum2",
     "loco_device_info",
     "loco_reset_due",
     "loco_error_state8_init",
@@ -89,6 +90,7 @@ def load_library(path: Optional[str] = None):
     lib.loco_stream_copy.argtypes, lib.loco_stream_copy.restype = [vp, vp, sz, vp], i
     lib.loco_stream_read.argtypes, lib.loco_stream_read.restype = [vp, sz, vp, vp], i
     lib.loco_stream_fill.argtypes, lib.loco_stream_fill.restype = [vp, sz, vp], i
+    lib.loco_stream_sum2.argtypes, lib.loco_stream_sum2.restype = [vp, vp, vp, sz, vp], i
     ip = ctypes.POINTER(ctypes.c_int)
     lib.loco_device_info.argtypes, lib.loco_device_info.restype = [ip, ip, ip, ip], i
     lib.loco_reset_due.argtypes, lib.loco_reset_due.restype = [c.c_longlong, c.c_longlong], i
@@ -275,6 +277,17 @@ def loco_stream_fill(dst: torch.Tensor, stream=None) -> None:
     lib = load_library()
     st = lib.loco_stream_fill(_dev_ptr(dst, "dst"), dst.numel() * dst.element_size(), _stream_handle(stream))
     _check("loco_stream_fill", st)
+
+
+def loco_stream_sum2(dst: torch.Tensor, src_a: torch.Tensor, src_b: torch.Tensor, stream=None) -> None:
+    """dst = src_a + src_b on 32-bit words: two read streams and one write stream (measurement aid)."""
+    lib = load_library()
+    nbytes = src_a.numel() * src_a.element_size()
+    if src_b.numel() * src_b.element_size() != nbytes or dst.numel() * dst.element_size() < nbytes:
+        raise ValueError("sizes differ")
+    st = lib.loco_stream_sum2(_dev_ptr(dst, "dst"), _dev_ptr(src_a, "src_a"), _dev_ptr(src_b, "src_b"), nbytes,
+                              _stream_handle(stream))
+    _check("loco_stream_sum2", st)
 
 
 def loco_device_info() -> dict:

@@ -38,6 +38,7 @@ constexpr int kDrXcdRun = 32;
 struct FillShape { static constexpr int kSlots = 1, kThreads = 256; };
 struct CopyShape { static constexpr int kSlots = 1, kThreads = 64; };
 struct ReadShape { static constexpr int kSlots = 4, kThreads = 64; };
+struct Sum2Shape { static constexpr int kSlots = 1, kThreads = 64; };
 static_assert(CqShape<4>::kSlots % 2 == 0 && CqShape<8>::kSlots % 2 == 0,
               "block size 512 spans two slots of one wavefront");
 
@@ -386,13 +387,14 @@ loco_status_t compress_block(const void* grad, loco_dtype_t grad_dtype, float cl
 }
 
 template <StreamMode MODE, typename Shape>
-loco_status_t launch_stream(void* dst, const void* src, size_t bytes, void* stream) {
+loco_status_t launch_stream(void* dst, const void* src, const void* src2, size_t bytes, void* stream) {
     const size_t n16 = bytes / 16;
     unsigned grid;
     if (loco_status_t st = grid_for(n16, (size_t)Shape::kThreads * Shape::kSlots, &grid)) return st;
     stream_kernel<MODE, Shape::kSlots, Shape::kThreads, kNonTemporal>
         <<<dim3(grid), dim3(Shape::kThreads), 0, static_cast<hipStream_t>(stream)>>>(
-            static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n16, 0x9E3779B9u);
+            static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), static_cast<const u32x4*>(src2), n16,
+            0x9E3779B9u);
     return launched();
 }
 
@@ -504,7 +506,7 @@ loco_status_t loco_stream_copy(void* dst, const void* src, size_t bytes, void* s
     if (bytes % 16 != 0 || !aligned(dst, 16) || !aligned(src, 16)) return LOCO_ERR_ALIGNMENT;
     if (loco_status_t st = check_device_range(dst, bytes)) return st;
     if (loco_status_t st = check_device_range(src, bytes)) return st;
-    return launch_stream<StreamMode::kCopy, CopyShape>(dst, src, bytes, stream);
+    return launch_stream<StreamMode::kCopy, CopyShape>(dst, src, nullptr, bytes, stream);
 }
 
 loco_status_t loco_stream_read(const void* src, size_t bytes, void* sink16, void* stream) {
@@ -513,7 +515,17 @@ loco_status_t loco_stream_read(const void* src, size_t bytes, void* sink16, void
     if (bytes % 16 != 0 || !aligned(src, 16) || !aligned(sink16, 16)) return LOCO_ERR_ALIGNMENT;
     if (loco_status_t st = check_device_range(src, bytes)) return st;
     if (loco_status_t st = check_device_range(sink16, 16)) return st;
-    return launch_stream<StreamMode::kRead, ReadShape>(sink16, src, bytes, stream);
+    return launch_stream<StreamMode::kRead, ReadShape>(sink16, src, nullptr, bytes, stream);
+}
+
+loco_status_t loco_stream_sum2(void* dst, const void* src_a, const void* src_b, size_t bytes, void* stream) {
+    if (bytes == 0) return LOCO_OK;
+    if (!dst || !src_a || !src_b) return LOCO_ERR_INVALID_ARG;
+    if (bytes % 16 != 0 || !aligned(dst, 16) || !aligned(src_a, 16) || !aligned(src_b, 16)) return LOCO_ERR_ALIGNMENT;
+    if (loco_status_t st = check_device_range(dst, bytes)) return st;
+    if (loco_status_t st = check_device_range(src_a, bytes)) return st;
+    if (loco_status_t st = check_device_range(src_b, bytes)) return st;
+    return launch_stream<StreamMode::kSum2, Sum2Shape>(dst, src_a, src_b, bytes, stream);
 }
 
 loco_status_t loco_stream_fill(void* dst, size_t bytes, void* stream) {
@@ -521,7 +533,7 @@ loco_status_t loco_stream_fill(void* dst, size_t bytes, void* stream) {
     if (!dst) return LOCO_ERR_INVALID_ARG;
     if (bytes % 16 != 0 || !aligned(dst, 16)) return LOCO_ERR_ALIGNMENT;
     if (loco_status_t st = check_device_range(dst, bytes)) return st;
-    return launch_stream<StreamMode::kFill, FillShape>(dst, nullptr, bytes, stream);
+    return launch_stream<StreamMode::kFill, FillShape>(dst, nullptr, nullptr, bytes, stream);
 }
 
 loco_status_t loco_device_info(int* memory_clock_khz, int* memory_bus_bits, int* compute_units,

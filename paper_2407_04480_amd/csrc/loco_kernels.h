@@ -578,11 +578,13 @@ fill_zero_kernel(float* __restrict__ dst, size_t n) {
 
 // Plain streaming kernels for measuring what the memory system sustains for a given mix of
 // reads and writes: kCopy dst = src; kRead loads src and stores (to sink) only if the words of
-// a lane's 16 bytes xor to `never`, so that the loads cannot be dropped; kFill writes zeros.
-enum class StreamMode { kCopy, kRead, kFill };
+// a lane's 16 bytes xor to `never`, so that the loads cannot be dropped; kFill writes zeros;
+// kSum2 dst = src + src2 word by word (two read streams, one write stream).
+enum class StreamMode { kCopy, kRead, kFill, kSum2 };
 template <StreamMode MODE, int SLOTS, int THREADS, bool NT>
 __global__ void __launch_bounds__(THREADS)
-stream_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n16, uint32_t never) {
+stream_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, const u32x4* __restrict__ src2,
+              size_t n16, uint32_t never) {
     const int lane = threadIdx.x & (kWave - 1);
     const size_t wave = (size_t)blockIdx.x * (THREADS / kWave) + (threadIdx.x >> 6);
     const size_t tile0 = wave * ((size_t)kWave * SLOTS);
@@ -593,6 +595,8 @@ stream_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n16
         v[s] = u32x4{0u, 0u, 0u, 0u};
         if constexpr (MODE != StreamMode::kFill)
             if (i < n16) v[s] = vload<NT>(src + i);
+        if constexpr (MODE == StreamMode::kSum2)
+            if (i < n16) v[s] += vload<NT>(src2 + i);
     }
 #pragma unroll
     for (int s = 0; s < SLOTS; ++s) {

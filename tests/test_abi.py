@@ -78,6 +78,7 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.loco_stream_fill(ctypes.c_void_p(8), 32, null) == 3
     assert lib.loco_stream_read(null, 32, one, null) == 1
     assert lib.loco_stream_fill(null, 0, null) == 0
+    assert lib.loco_stream_sum2(one, one, null, 32, null) == 1
 
 
 def test_missing_library_is_an_error(tmp_path):

@@ -263,7 +263,7 @@ def test_pointer_and_argument_errors_on_gpu():
 @pytest.mark.parametrize("nbytes", [16, 1008, 1024, 4096 + 16, 3 * 65536 + 48, (1 << 24) + 16])
 def test_stream_measurement_aids(nbytes):
     """The plain copy / read / fill kernels behind bench.py's ceilings do what they say."""
-    from paper_2407_04480_amd import loco_stream_copy, loco_stream_fill, loco_stream_read
+    from paper_2407_04480_amd import loco_stream_copy, loco_stream_fill, loco_stream_read, loco_stream_sum2
     rng = torch.Generator(device="cpu").manual_seed(nbytes)
     src = torch.randint(0, 256, (nbytes,), generator=rng, dtype=torch.uint8).to(DEV)
     dst = torch.full((nbytes + 16,), 0x5A, dtype=torch.uint8, device=DEV)
@@ -275,6 +275,11 @@ def test_stream_measurement_aids(nbytes):
     loco_stream_read(src, sink)
     torch.cuda.synchronize()
     assert torch.equal(src, before)
+    other = torch.randint(0, 256, (nbytes,), generator=rng, dtype=torch.uint8).to(DEV)
+    loco_stream_sum2(dst[:nbytes], src, other)
+    torch.cuda.synchronize()
+    want = (src.view(torch.int32) + other.view(torch.int32)).view(torch.uint8)     # wraps, like the kernel
+    assert torch.equal(dst[:nbytes], want) and int(dst[nbytes:].min()) == 0x5A
     loco_stream_fill(dst[:nbytes])
     torch.cuda.synchronize()
     assert int(dst[:nbytes].max()) == 0 and int(dst[nbytes:].min()) == 0x5A
