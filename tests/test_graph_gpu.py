@@ -66,3 +66,51 @@ def test_step_replays_from_a_graph():
             # eager work between replays
             scratch = torch.randn(1 << 16, device=DEV).sum().item()
             assert np.isfinite(scratch)
+
+
+def test_two_streams_overlap():
+    """Compensate-quantize of the next bucket on one stream while the reduce of the previous
+    bucket runs on another (the overlap the exchange would use): the calls share no state,
+    so both streams' results equal the serial ones."""
+    w = workloads.small("llama7b_shard_4bit_b256")
+    n, bits, B, W = w.n, w.bits, w.block_size, 4
+    cb, nb = loco_code_bytes(n, bits), loco_num_blocks(n, B)
+    cs = (cb + 15) // 16 * 16
+    grads = [workloads.gradient(w, k, device=DEV) for k in range(W + 6)]
+
+    def payloads(stream=None):
+        codes = torch.zeros(W * cs, dtype=torch.uint8, device=DEV)
+        scales = torch.zeros(W * nb, dtype=torch.float32, device=DEV)
+        e = torch.empty(n, dtype=torch.float32, device=DEV)
+        for k in range(W):
+            loco_error_state_init(e, stream)
+            loco_compensate_quantize(grads[k], e, bits, B, w.beta, False, codes[k * cs:k * cs + cb],
+                                     scales[k * nb:(k + 1) * nb], stream)
+        return codes, scales
+
+    recv_codes, recv_scales = payloads()
+    # serial reference: 6 steps of compensate-quantize, 6 reduces
+    err = torch.zeros(n, dtype=torch.float32, device=DEV)
+    oc, os_ = torch.zeros(cb, dtype=torch.uint8, device=DEV), torch.zeros(nb, dtype=torch.float32, device=DEV)
+    out = torch.empty(n, dtype=torch.float32, device=DEV)
+    serial = []
+    for k in range(6):
+        loco_compensate_quantize(grads[W + k], err, bits, B, w.beta, False, oc, os_)
+        loco_dequant_reduce(recv_codes, cs, recv_scales, nb, W, n, bits, B, out)
+        torch.cuda.synchronize()
+        serial.append((oc.clone(), os_.clone(), err.clone(), out.clone()))
+    # the same work with the two calls on two streams, no ordering between them
+    a, b = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    err.zero_()
+    torch.cuda.synchronize()
+    for k in range(6):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        loco_compensate_quantize(grads[W + k], err, bits, B, w.beta, False, oc, os_, a)
+        loco_dequant_reduce(recv_codes, cs, recv_scales, nb, W, n, bits, B, out, b)
+        a.synchronize()
+        b.synchronize()
+        c, s, e, o = serial[k]
+        assert torch.equal(oc, c) and torch.equal(os_, s) and torch.equal(err, e), f"step {k}: compress"
+        assert torch.equal(out, o), f"step {k}: reduce"
