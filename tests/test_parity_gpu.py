@@ -297,3 +297,34 @@ def test_state_init_sizes(n):
     torch.cuda.synchronize()
     assert not e[:n].any() and bool((e[n:] == 7.0).all())
     assert not e8[:n].any() and bool((e8[n:] == 7).all())
+
+
+def test_resume_from_saved_state():
+    """The error state (and the step index, for the reset schedule) is all that persists between
+    steps: a run that saves the state to the host after step 3, frees it, reloads it into a new
+    allocation and carries on gives the bytes of the uninterrupted run."""
+    n, bits, B, beta, K = 9 * 2048 + 517, 4, 128, 0.25, 7
+    rng = torch.Generator(device="cpu").manual_seed(4242)
+    grads = [(torch.randn(n, generator=rng) * 1e-3).to(torch.bfloat16).to(DEV) for _ in range(K)]
+
+    def run(interrupt_after=None):
+        e = torch.empty(n, dtype=torch.float32, device=DEV)
+        loco_error_state_init(e)
+        trace = []
+        for k in range(K):
+            codes, scales = gpu_cq(grads[k], e, bits, B, beta, reset=(k == 5))
+            trace.append((codes.cpu(), scales.cpu()))
+            if interrupt_after == k:
+                saved = e.cpu().clone()
+                del e
+                torch.cuda.empty_cache()
+                e = saved.to(DEV)
+        torch.cuda.synchronize()
+        return trace, e.cpu()
+
+    straight, e_straight = run()
+    resumed, e_resumed = run(interrupt_after=3)
+    for k in range(K):
+        assert torch.equal(straight[k][0], resumed[k][0]), f"step {k}: codes differ after the resume"
+        assert torch.equal(straight[k][1].view(torch.int32), resumed[k][1].view(torch.int32)), f"step {k}: steps"
+    assert torch.equal(e_straight.view(torch.int32), e_resumed.view(torch.int32))
