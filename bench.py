@@ -77,6 +77,17 @@ def parse_args():
 FIXED_LOG2_S, FIXED_SE_MULT = 19, 4   # the paper's s = 2^19 and s_e = 4s (Sec. 3.1, 3.2)
 
 
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(form, w, grads, recv_codes, cstride, recv_scales, nb_full, sample, bytes_cq, bytes_dr):
     """Time the oracle (as it stands) on the first `sample` elements of the workload: one
     compensate-quantize step from a zero state, then the reduce over the W resident payloads."""
@@ -126,6 +137,8 @@ def cpu_baseline(form, w, grads, recv_codes, cstride, recv_scales, nb_full, samp
         "value": step_bytes / (cqm + drm) / 1e9,
         "unit": "GB/s",
         "cores": cores,
+        "cpu_model": cpu_model(),
+        "host_cpus": os.cpu_count(),
         "kind": "oracle",
         "sample": f"first {ns} elements of the shard, one step (compensate-quantize from a zero state + "
                   f"dequant-reduce W={W}), best of 3",
