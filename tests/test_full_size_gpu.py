@@ -247,3 +247,65 @@ def test_full_size_every_element(name, steps, capsys):
     bad = int(np.count_nonzero(got != want))
     assert bad == 0, f"{bad} of {n} averaged values differ"
     print(f"[{name}] reduce over W={W}: identical over {n} elements", flush=True)
+
+
+def test_beyond_two_to_the_32_elements():
+    """64-bit indexing: a shard of 2^32 + 2^20 + 333 elements (element indices, and the byte offsets of
+    every array, pass 2^31, 2^32 and 2^34).  Blocks on both sides of those boundaries, the ragged last
+    block and a few thousand random ones are recomputed by the oracle; the reduce over two payloads is
+    checked on the same blocks and must have written every element."""
+    n, bits, B, W = (1 << 32) + (1 << 20) + 333, 4, 256, 2
+    w = workloads.Workload("beyond_2_32", "gauss", n, torch.bfloat16, bits, B, num_workers=W,
+                           segments=(("all", 0, n),))
+    nb = loco_num_blocks(n, B)
+    cb = loco_code_bytes(n, bits)
+    cstride = (cb + 15) // 16 * 16
+    rs = np.random.default_rng(32)
+    picks = set(rs.integers(0, nb - 1, 3000).tolist())
+    for edge in (1 << 29, 1 << 30, 1 << 31, 1 << 32, 1 << 33):      # element index, or byte offset / 1, 2, 4, 8
+        for el in (edge, edge // 2, edge // 4, edge * 2):
+            b = el // B
+            picks.update(x for x in (b - 1, b, b + 1) if 0 <= x < nb - 1)
+    picks.update(range(0, 3))
+    picks.update(range(nb - 4, nb - 1))
+    blocks = np.array(sorted(picks), dtype=np.int64)                # whole blocks; the ragged last one below
+    eidx, cidx = element_index(blocks, B), code_index(blocks, B, bits)
+    bidx = torch.from_numpy(blocks).to(DEV)
+    tail0 = (nb - 1) * B                                            # first element of the last, partial block
+    recv_codes = torch.zeros(W * cstride, dtype=torch.uint8, device=DEV)
+    recv_scales = torch.zeros(W * nb, dtype=torch.float32, device=DEV)
+    err = torch.empty(n, dtype=torch.float32, device=DEV)
+    ref_codes = np.zeros((W, cidx.numel()), np.uint8)
+    ref_scales = np.zeros((W, blocks.size), np.float32)
+    tail_codes, tail_scales = [], []
+    for k in range(W):
+        g = workloads.gradient(w, 0, worker=k if k else None, device=DEV)
+        loco_error_state_init(err)
+        e_ref = np.zeros(eidx.numel(), np.float32)
+        e_tail = np.zeros(n - tail0, np.float32)
+        codes_k, scales_k = recv_codes[k * cstride:k * cstride + cb], recv_scales[k * nb:(k + 1) * nb]
+        for step in range(2 if k == 0 else 1):
+            loco_compensate_quantize(g, err, bits, B, w.beta, False, codes_k, scales_k)
+            ref_codes[k], ref_scales[k] = oracle.compensate_quantize(host_grad(g[eidx]), e_ref, bits, B, w.beta)
+            c_tail, s_tail = oracle.compensate_quantize(host_grad(g[tail0:]), e_tail, bits, B, w.beta)
+            torch.cuda.synchronize()
+            assert np.array_equal(codes_k[cidx].cpu().numpy(), ref_codes[k]), f"worker {k} step {step}: codes"
+            assert np.array_equal(scales_k[bidx].cpu().numpy().view(np.uint32), ref_scales[k].view(np.uint32))
+            assert np.array_equal(err[eidx].cpu().numpy(), e_ref), f"worker {k} step {step}: state"
+            assert np.array_equal(codes_k[tail0 // 2:].cpu().numpy(), c_tail), "codes of the last, partial block"
+            assert np.array_equal(scales_k[nb - 1:].cpu().numpy().view(np.uint32), s_tail.view(np.uint32))
+            assert np.array_equal(err[tail0:].cpu().numpy(), e_tail)
+        tail_codes.append(c_tail)
+        tail_scales.append(s_tail)
+        del g
+    del err
+    out = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    loco_dequant_reduce(recv_codes, cstride, recv_scales, nb, W, n, bits, B, out)
+    torch.cuda.synchronize()
+    want = oracle.dequant_reduce(ref_codes.reshape(-1), ref_scales.reshape(-1), W, eidx.numel(), bits, B,
+                                 ref_codes.shape[1], ref_scales.shape[1])
+    assert np.array_equal(out[eidx].cpu().numpy(), want)
+    want_tail = oracle.dequant_reduce(np.concatenate(tail_codes), np.concatenate(tail_scales), W, n - tail0, bits, B,
+                                      tail_codes[0].size, 1)
+    assert np.array_equal(out[tail0:].cpu().numpy(), want_tail)
+    assert bool(torch.isfinite(out).all())

@@ -216,6 +216,56 @@ def test_fixed_full_size_every_element(capsys):
     assert int(np.count_nonzero(got != want)) == 0
 
 
+def test_fixed_beyond_two_to_the_32_elements():
+    """64-bit indexing of the fixed-scale kernels: 2^32 + 2^20 + 77 elements; runs of 64 elements on
+    both sides of 2^29 ... 2^33 (element index or byte offset), the ragged end and random runs are
+    recomputed by the oracle, for the compressor (two steps) and for Eq. 8 over two payloads."""
+    n, bits, log2_s, mult, W, beta = (1 << 32) + (1 << 20) + 77, 4, 19, 6, 2, 0.25
+    rs = np.random.default_rng(33)
+    starts = set((rs.integers(0, n // 64 - 2, 3000) * 64).tolist())
+    for edge in (1 << 29, 1 << 30, 1 << 31, 1 << 32, 1 << 33):
+        for el in (edge, edge // 2, edge * 2):
+            starts.update(x for x in (el - 64, el) if 0 <= x <= n - 128)
+    starts.update({0, 64})
+    starts = np.array(sorted(starts), dtype=np.int64)
+    idx = (starts[:, None] + np.arange(64)[None, :]).reshape(-1)
+    eidx = torch.from_numpy(idx).to(DEV)
+    cidx = torch.from_numpy((starts[:, None] // 2 + np.arange(32)[None, :]).reshape(-1)).to(DEV)
+    tail0 = n // 64 * 64 - 64                       # the last whole run and the ragged end behind it
+    cb = loco_code_bytes(n, bits)
+    stride = (cb + 15) // 16 * 16
+    recv = torch.zeros(W * stride, dtype=torch.uint8, device=DEV)
+    err = torch.empty(n, dtype=torch.int8, device=DEV)
+    wl = workloads.Workload("beyond_2_32", "gauss", n, torch.bfloat16, bits, 256, segments=(("all", 0, n),))
+    ref = np.zeros((W, idx.size // 2), np.uint8)
+    tails = []
+    for k in range(W):
+        g = (workloads.gradient(wl, 0, worker=k if k else None, device=DEV) * 1e-2).to(torch.bfloat16)
+        loco_error_state8_init(err)
+        e_ref, e_tail = np.zeros(idx.size, np.int8), np.zeros(n - tail0, np.int8)
+        mine = recv[k * stride:k * stride + cb]
+        for step in range(2 if k == 0 else 1):
+            loco_compensate_quantize_fixed(g, err, bits, log2_s, mult, beta, False, mine)
+            ref[k] = oracle.fixed_compensate_quantize(workloads.as_numpy_grad(g[eidx]), e_ref, bits, log2_s, mult, beta)
+            c_tail = oracle.fixed_compensate_quantize(workloads.as_numpy_grad(g[tail0:]), e_tail, bits, log2_s, mult, beta)
+            torch.cuda.synchronize()
+            assert np.array_equal(mine[cidx].cpu().numpy(), ref[k]), f"worker {k} step {step}: codes"
+            assert np.array_equal(err[eidx].cpu().numpy(), e_ref), f"worker {k} step {step}: state"
+            assert np.array_equal(mine[tail0 // 2:].cpu().numpy(), c_tail) and np.array_equal(err[tail0:].cpu().numpy(), e_tail)
+        tails.append(c_tail)
+        del g
+    del err
+    out = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    loco_dequant_reduce_fixed(recv, stride, W, n, bits, log2_s, out)
+    torch.cuda.synchronize()
+    want = oracle.fixed_dequant_reduce(ref.reshape(-1), W, idx.size, bits, log2_s, code_stride_bytes=idx.size // 2)
+    assert np.array_equal(out[eidx].cpu().numpy(), want)
+    want_tail = oracle.fixed_dequant_reduce(np.concatenate(tails), W, n - tail0, bits, log2_s,
+                                            code_stride_bytes=tails[0].size)
+    assert np.array_equal(out[tail0:].cpu().numpy(), want_tail)
+    assert bool(torch.isfinite(out).all())
+
+
 def test_fixed_argument_errors():
     n = 4096
     g = torch.zeros(n, device=DEV)
