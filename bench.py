@@ -71,6 +71,9 @@ def parse_args():
     ap.add_argument("--clip-abs", type=float, default=None,
                     help="clip the gradient element-wise to [-c, c] before compensation (Sec. 5.2)")
     ap.add_argument("--no-copy-ceiling", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the same steps replayed from a captured HIP graph (two steps per replay); "
+                         "reported as graph_replay beside the eager figures, which stay the headline")
     return ap.parse_args()
 
 
@@ -309,6 +312,31 @@ def main():
 
     total_s = t1 - t0
     ms_per_step = total_s / args.steps * 1e3
+
+    graph_replay = None
+    if args.graph:   # launch-bound sizes: one graph launch instead of two kernel launches per step
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        eager_stream, stream = stream, side
+        with torch.cuda.stream(side):
+            step(0)
+            step(1)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step(0)
+            step(1)
+        stream = eager_stream
+        replays = max(1, args.steps // 2)
+        graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        g1 = time.perf_counter()
+        graph_replay = {"steps": 2 * replays, "ms_per_step": (g1 - g0) / (2 * replays) * 1e3,
+                        "value": (bytes_cq + bytes_dr) * n / ((g1 - g0) / (2 * replays)) / 1e9, "unit": "GB/s"}
     cq_ms = sorted(e[0].elapsed_time(e[1]) for e in events)
     dr_ms = sorted(e[1].elapsed_time(e[2]) for e in events)
     cq_avg, dr_avg = sum(cq_ms) / len(cq_ms), sum(dr_ms) / len(dr_ms)
@@ -387,6 +415,7 @@ def main():
         "roofline": {k: dominant[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
         | {"kernel": dominant["kernel"]},
         "kernels": [k_cq, k_dr],
+        "graph_replay": graph_replay,
         "copy_ceiling_GBps": copy_gbps,
         "stream_ceilings_GBps": ceilings,
         "device": device_report(loco_device_info()),
