@@ -57,6 +57,7 @@ def _bind(lib):
     lib.loco_ref_dequant_reduce_mt.argtypes = [vp, sz, vp, sz, i, sz, i, i, vp, i]
     lib.loco_ref_fixed_compensate_quantize.argtypes = [vp, i, vp, sz, i, i, i, f, i, vp]
     lib.loco_ref_fixed_compensate_quantize_mt.argtypes = [vp, i, vp, sz, i, i, i, f, i, vp, i]
+    lib.loco_ref_fixed_compensate_quantize_f32state.argtypes = [vp, i, vp, sz, i, i, f, i, vp]
     lib.loco_ref_fixed_dequant_reduce.argtypes = [vp, sz, i, sz, i, i, vp]
     lib.loco_ref_fixed_dequant_reduce_mt.argtypes = [vp, sz, i, sz, i, i, vp, i]
     lib.loco_ref_compensate_quantize_bf16_scales.argtypes = [vp, i, vp, sz, i, i, f, i, vp, vp]
@@ -74,6 +75,7 @@ def _bind(lib):
         "loco_ref_clip_gradient",
         "loco_ref_fixed_compensate_quantize",
         "loco_ref_fixed_compensate_quantize_mt",
+        "loco_ref_fixed_compensate_quantize_f32state",
         "loco_ref_fixed_dequant_reduce",
         "loco_ref_fixed_dequant_reduce_mt",
         "loco_ref_error_state_init",
@@ -203,6 +205,22 @@ def fixed_compensate_quantize(grad, err_state8, bits, log2_s, se_mult, beta, res
         rc = lib.loco_ref_fixed_compensate_quantize(*args)
     if rc:
         raise ValueError("loco_ref_fixed_compensate_quantize: status %d" % rc)
+    return codes
+
+
+def fixed_compensate_quantize_f32state(grad, err_state, bits, log2_s, beta, reset=0, lib=None):
+    """Alg. 1 steps 1-2 with the global scale s = 2^log2_s and the compensation error kept in
+    float32 (the paper's ablation row without error compression).  err_state is updated in place;
+    returns the codes."""
+    lib = lib or load()
+    grad = np.ascontiguousarray(grad)
+    assert err_state.dtype == np.float32 and err_state.flags.c_contiguous and err_state.size == grad.size
+    n = grad.size
+    codes = np.zeros(code_bytes(n, bits), dtype=np.uint8)
+    rc = lib.loco_ref_fixed_compensate_quantize_f32state(_ptr(grad), _grad_dtype(grad), _ptr(err_state), n,
+                                                         int(bits), int(log2_s), float(beta), int(reset), _ptr(codes))
+    if rc:
+        raise ValueError("loco_ref_fixed_compensate_quantize_f32state: status %d" % rc)
     return codes
 
 

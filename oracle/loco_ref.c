@@ -378,6 +378,50 @@ int loco_ref_fixed_compensate_quantize(const void *grad, int grad_dtype, int8_t 
                                                     se_mult, beta, reset, codes_out, 0, n);
 }
 
+/* ------------------------------------------------------------------------------------
+ * The global scale s of Eq. 1 with the compensation error kept in high precision: the
+ * ablation row without error compression (Table 9, Sec. 5.4 "Error compression").  Alg. 1
+ * with decompressor(e; s_e) and compressor(.; s_e, 8) taken out:
+ *   h    = g + e~                                              (Eq. 2)
+ *   q    = round_p-bit(h * s), clamped                         (Eq. 1, 3)
+ *   d    = float(q) / s
+ *   e~'  = (1-beta) e~ + beta (h - d), or 0 on a reset step    (Eq. 5, Eq. 7)
+ * Same readings as above (s a power of two, clamp on the rounded float, ties to even).
+ * The payload is that of the 8-bit-state form, so Eq. 8 is loco_ref_fixed_dequant_reduce.
+ * ---------------------------------------------------------------------------------- */
+int loco_ref_fixed_compensate_quantize_f32state(const void *grad, int grad_dtype, float *err_state,
+                                                size_t n, int bits, int log2_s, float beta, int reset,
+                                                uint8_t *codes_out)
+{
+    if (!fixed_args_ok(bits, log2_s, 1) || !(beta >= 0.0f && beta <= 1.0f))
+        return LOCO_REF_BAD_ARG;
+    if (grad_dtype != LOCO_REF_F32 && grad_dtype != LOCO_REF_BF16)
+        return LOCO_REF_BAD_ARG;
+    if (n && (!grad || !err_state || !codes_out))
+        return LOCO_REF_BAD_ARG;
+    const int qmax = (1 << (bits - 1)) - 1;
+    const int qmin = -(1 << (bits - 1));
+    const float s = ldexpf(1.0f, log2_s);
+    const float one_minus_beta = 1.0f - beta;
+    for (size_t i = 0; i < n; ++i) {
+        float e_old = err_state[i];                          /* high-precision e~_k, no decompression */
+        float h = grad_at(grad, grad_dtype, i) + e_old;      /* Eq. 2 with the uncompressed state */
+        int q = (int)clamp_round(h * s, qmin, qmax);         /* Eq. 1, 3 */
+        float d_own = (float)q / s;                          /* own decompressor */
+        float raw_err = h - d_own;                           /* Eq. 4 */
+        float weighted = beta * raw_err;
+        err_state[i] = reset ? 0.0f : fmaf(one_minus_beta, e_old, weighted);   /* Eq. 5, Eq. 7 */
+        if (bits == 8) {
+            codes_out[i] = (uint8_t)(int8_t)q;
+        } else if ((i & 1) == 0) {
+            codes_out[i >> 1] = (uint8_t)(q & 15);
+        } else {
+            codes_out[i >> 1] = (uint8_t)(codes_out[i >> 1] | ((q & 15) << 4));
+        }
+    }
+    return LOCO_REF_OK;
+}
+
 /* Eq. 8 with the global scale: out = (sum_w float(q^w) / s) * (1/W), in worker order. */
 int loco_ref_fixed_dequant_reduce_range(const uint8_t *codes, size_t code_stride_bytes, int num_workers,
                                         size_t n, int bits, int log2_s, float *grad_out,

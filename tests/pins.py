@@ -680,6 +680,112 @@ def check_fixed_edges(lib):
     assert np.array_equal(o1, o4)
 
 
+def fcq32(lib, g, e, bits, log2_s, beta, reset=0):
+    return oracle.fixed_compensate_quantize_f32state(g, e, bits, log2_s, beta, reset, lib=lib)
+
+
+def check_fixed_f32state(lib):
+    """The global scale of Eq. 1 with the compensation error kept in high precision (Table 9, the
+    row without error compression): Alg. 1 with the 8-bit round trip of the state taken out."""
+    # hand-worked dyadic example (Eq. 1-5): every code byte and state value
+    rows = {}
+    with open(os.path.join(GOLDEN, "worked_example_fixed_scale_f32_state_p4.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                key, *vals = line.split()
+                rows[key] = vals
+    bits, log2_s, beta = int(rows["bits"][0]), int(rows["log2_s"][0]), float(rows["beta"][0])
+    g = np.array([float(v) for v in rows["g"]], np.float32)
+    e = np.zeros(g.size, np.float32)
+    for step in (0, 1):
+        codes = fcq32(lib, g, e, bits, log2_s, beta)
+        assert np.array_equal(codes, np.array([int(b, 16) for b in rows[f"bytes{step}"]], np.uint8)), (step, codes)
+        assert unpack(codes, g.size, bits).tolist() == [int(v) for v in rows[f"q{step}"]]
+        assert e.tolist() == [float(v) for v in rows[f"e{step + 1}"]], (step, e)
+
+    rng = np.random.default_rng(71)
+    for trial in range(200):
+        bits = (4, 8)[trial & 1]
+        qmin, qmax = qrange(bits)
+        log2_s = int(rng.choice([19, 17, 10, 3, -2]))
+        beta = float(rng.choice([0.25, 0.5, 1.0, 0.3, 0.9, 0.0]))
+        s = 2.0 ** log2_s
+        n = int(rng.integers(1, 300))
+        g = (rng.standard_normal(n) * rng.choice([0.3, 1, 3, 30]) * qmax / s).astype(np.float32)
+        e0 = (rng.standard_normal(n) * 0.4 / s).astype(np.float32) if trial % 3 else np.zeros(n, np.float32)
+        e = e0.copy()
+        codes = fcq32(lib, g, e, bits, log2_s, beta)
+        q = unpack(codes, n, bits)
+        h = g.astype(np.float64) + e0                                   # Eq. 2
+        h32 = (g + e0).astype(np.float64)                               # the binary32 sum the oracle forms
+        x = h32 * s                                                     # exact: s is a power of two
+        want_q = np.clip(np.rint(x), qmin, qmax)                        # Eq. 1: nearest level, ties to even
+        assert np.array_equal(q, want_q), (trial, x[q != want_q], q[q != want_q])
+        assert np.all(np.abs(h32 - h) <= np.abs(h) * 2.0 ** -24 + 1e-300)
+        unsat = np.abs(x) <= qmax + 0.5
+        assert np.all(np.abs(h32 - q / s)[unsat] <= 0.5 / s)            # Lemma 5: |h - d| <= 1/(2s)
+        b32 = np.float64(np.float32(beta))
+        omb = np.float64(np.float32(1.0) - np.float32(beta))
+        want_e = omb * e0 + b32 * (h32 - q / s)                         # Eq. 5 in binary64
+        assert np.all(np.abs(e - want_e) <= np.abs(want_e) * 2.0 ** -23 + np.abs(b32 * (h32 - q / s)) * 2.0 ** -23 + 1e-45)
+        if beta == 0.0:
+            assert np.array_equal(e, e0)                                # the state never moves
+        if beta == 1.0:
+            assert np.array_equal(e.astype(np.float64), h32 - q / s)    # classic error feedback, Eq. 4 (exact)
+        e_r = e0.copy()
+        codes_r = fcq32(lib, g, e_r, bits, log2_s, beta, reset=1)       # Eq. 7: same payload, state 0
+        assert np.array_equal(codes_r, codes) and not e_r.any()
+
+    # Lemma 1 with an uncompressed state: sum d = sum g - e~_K / beta, up to binary32 rounding
+    for bits, log2_s, beta, K in ((4, 19, 0.5, 12), (4, 17, 0.25, 20), (8, 19, 1.0, 8)):
+        qmin, qmax = qrange(bits)
+        s = 2.0 ** log2_s
+        n = 4000
+        e = np.zeros(n, np.float32)
+        sum_d, sum_g = np.zeros(n), np.zeros(n)
+        for _ in range(K):
+            g = (rng.uniform(-(qmax - 1), qmax - 1, n) / s).astype(np.float32)          # never clamps
+            codes = fcq32(lib, g, e, bits, log2_s, beta)
+            sum_d += unpack(codes, n, bits) / s
+            sum_g += g
+        assert np.abs(e).max() > 0
+        assert np.abs(sum_d - (sum_g - e.astype(np.float64) / beta)).max() <= 8 * K * 2.0 ** -24 * qmax / s / beta
+        assert np.abs(sum_d - sum_g).max() <= 0.5 / s / beta * (1 + 1e-6)                # and it never accumulates
+
+    # one step from a zero state is one step of the block-scaled form whose blocks all peak at qmax/s,
+    # and of the 8-bit-state form wherever s_e e~' is an integer in range
+    for bits, log2_s, B in ((4, 19, 256), (8, 17, 64)):
+        qmin, qmax = qrange(bits)
+        s = 2.0 ** log2_s
+        n = 20 * B
+        g = (rng.uniform(-qmax, qmax, n) / s).astype(np.float32)
+        g[np.arange(0, n, B) + rng.integers(0, B, n // B)] = np.float32(qmax / s)
+        e_f, e_b = np.zeros(n, np.float32), np.zeros(n, np.float32)
+        c_f = fcq32(lib, g, e_f, bits, log2_s, 0.25)
+        c_b, _ = cq(lib, g, e_b, bits, B, 0.25)
+        assert np.array_equal(c_f, c_b) and np.array_equal(e_f, e_b)
+    m = rng.integers(-40, 41, 2000)                                     # g = m/16 with s = 8: h*s on half integers
+    g = (m / 16.0).astype(np.float32)
+    e32, e8 = np.zeros(g.size, np.float32), np.zeros(g.size, np.int8)
+    c32 = fcq32(lib, g, e32, 4, 3, 0.5)
+    c8 = fcq(lib, g, e8, 4, 3, 4, 0.5)
+    fits = np.abs(e32 * 32) <= 127
+    assert np.array_equal(c32, c8) and np.array_equal((e32 * 32)[fits], e8[fits].astype(np.float32)) and fits.mean() > 0.5
+
+    # edges: empty, odd length, bf16 widening, clamp on huge values
+    assert fcq32(lib, np.zeros(0, np.float32), np.zeros(0, np.float32), 4, 19, 0.25).size == 0
+    n = 777
+    gb = to_bf16_bits((rng.standard_normal(n) * 4 / 2.0 ** 19).astype(np.float32))
+    ea, eb = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    ca, cb_ = fcq32(lib, gb, ea, 4, 19, 0.25), fcq32(lib, bf16_bits_to_f32(gb), eb, 4, 19, 0.25)
+    assert np.array_equal(ca, cb_) and np.array_equal(ea, eb) and ca.size == (n + 1) // 2 and (ca[-1] >> 4) == 0
+    big = np.array([3e38, -3e38, 1.0, -1.0], np.float32)
+    e = np.zeros(4, np.float32)
+    assert unpack(fcq32(lib, big, e, 4, 19, 1.0), 4, 4).tolist() == [7, -8, 7, -8]
+    assert e[2] == np.float32(1.0 - 7 / 2.0 ** 19) and e[3] == np.float32(-1.0 + 8 / 2.0 ** 19)
+
+
 def check_clip(lib):
     """Clipping to [-c, c]: values inside are untouched, values outside land on +-c with their
     sign, c = inf is the identity, the map is idempotent, and bf16 input is widened first."""
@@ -892,5 +998,6 @@ FIXED_CHECKS = [
     check_fixed_matches_block_form,
     check_fixed_dequant_reduce,
     check_fixed_edges,
+    check_fixed_f32state,
 ]
 ALL_CHECKS = ALL_CHECKS + FIXED_CHECKS

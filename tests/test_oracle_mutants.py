@@ -53,6 +53,16 @@ MUTANTS = [
      "float d = (float)q / s_e;"),
     ("fixed_reset_ignored", "int e8 = reset ? 0 :", "int e8 = 0 ? 0 :"),
     ("fixed_reduce_no_average", "grad_out[i] = acc * inv;", "grad_out[i] = acc;", 1),
+    # global scale with the state kept in high precision
+    ("f32state_compensation_dropped", "grad_at(grad, grad_dtype, i) + e_old;", "grad_at(grad, grad_dtype, i);"),
+    ("f32state_error_sign", "float raw_err = h - d_own;", "float raw_err = d_own - h;"),
+    ("f32state_ema_not_weighted", "float weighted = beta * raw_err;", "float weighted = raw_err;"),
+    ("f32state_ema_history_dropped", "fmaf(one_minus_beta, e_old, weighted)", "weighted"),
+    ("f32state_ema_weights_swapped", "fmaf(one_minus_beta, e_old, weighted)", "fmaf(beta, e_old, one_minus_beta * raw_err)"),
+    ("f32state_reset_ignored", "err_state[i] = reset ? 0.0f : fmaf(one_minus_beta, e_old", "err_state[i] = 0 ? 0.0f : fmaf(one_minus_beta, e_old"),
+    ("f32state_decode_not_scaled", "float d_own = (float)q / s;", "float d_own = (float)q;"),
+    ("f32state_scale_inverted", "int q = (int)clamp_round(h * s, qmin, qmax);         /* Eq. 1, 3 */\n        float d_own",
+     "int q = (int)clamp_round(h / s, qmin, qmax);\n        float d_own"),
     ("clip_one_sided", "if (g < -clip_abs)\n            g = -clip_abs;", ""),
     ("clip_sign_lost", "            g = -clip_abs;", "            g = clip_abs;"),
     ("sgd_ascent", "theta[i] = theta[i] - step;\n    }\n    return LOCO_REF_OK;\n}\n\nint loco_ref_adam_update",
