@@ -40,6 +40,7 @@ MEASURED_TRAFFIC = {
     ("dense70b_shard_4bit_b256", "loco_compensate_quantize"): 2.31829e10,
     ("dense70b_shard_4bit_b256", "loco_dequant_reduce"): 2.76200e10,
     ("llama7b_shard_4bit_b256", "loco_compensate_quantize_fixed"): 3.7904e9,
+    ("llama7b_shard_4bit_b256", "loco_compensate_quantize_fixed_f32state"): 8.8441e9,
     ("llama7b_shard_4bit_b256", "loco_dequant_reduce_fixed"): 6.7384e9,
     ("llama7b_shard_4bit_b256", "loco_compensate_quantize_clip"): 8.8752e9,
     ("llama7b_shard_4bit_b256", "loco_dequant_reduce_sgd"): 1.03411e10,
@@ -62,6 +63,9 @@ def parse_args():
     ap.add_argument("--form", choices=["block", "fixed"], default="block",
                     help="block: per-block scales, fp32 error state (the headline path); fixed: Algorithm 1 as "
                          "printed, global scale s = 2^19 and 8-bit error state with s_e = 4s")
+    ap.add_argument("--state", choices=["int8", "f32"], default="int8",
+                    help="fixed form only: keep the compensation error as 8-bit codes (Algorithm 1 as printed) or "
+                         "in fp32 (the paper's ablation row without error compression)")
     ap.add_argument("--optimizer", choices=["none", "sgd", "adam"], default="none",
                     help="fuse the optimizer step of Eq. 9 / Eq. 10 into the reduce (theta, m, v fp32 in place)")
     ap.add_argument("--out", choices=["f32", "bf16"], default="f32",
@@ -175,7 +179,7 @@ def main():
                                       loco_dequant_reduce_fixed_adam, loco_dequant_reduce_fixed_sgd,
                                       loco_dequant_reduce_sgd, loco_error_state8_init, loco_error_state_init,
                                       loco_num_blocks, workloads)
-    from paper_2407_04480_amd.binding import (loco_stream_copy, loco_stream_read, loco_stream_fill, loco_stream_sum2, loco_device_info, loco_compensate_quantize_clip,
+    from paper_2407_04480_amd.binding import (loco_compensate_quantize_fixed_f32state, loco_stream_copy, loco_stream_read, loco_stream_fill, loco_stream_sum2, loco_device_info, loco_compensate_quantize_clip,
                                               loco_compensate_quantize_fixed_clip,
                                               loco_compensate_quantize_bf16_scales,
                                               loco_dequant_reduce_bf16_scales)
@@ -188,13 +192,18 @@ def main():
     w = workloads.by_name(args.workload)
     n, bits, B, W = w.n, w.bits, w.block_size, w.num_workers
     form = args.form
+    if args.state == "f32" and (form != "fixed" or args.clip_abs is not None):
+        print("bench.py: --state f32 goes with --form fixed and no clipping", file=sys.stderr)
+        return 2
     gsz = 2 if w.grad_dtype == torch.bfloat16 else 4
     if form == "block":
         bytes_cq, bytes_dr = workloads.algorithmic_bytes(w)
         names = ("loco_compensate_quantize", "loco_dequant_reduce")
     else:  # gradient + 8-bit state in and out + codes; W payloads of codes + fp32 out
-        bytes_cq, bytes_dr = gsz + 1 + 1 + bits / 8.0, W * bits / 8.0 + 4
-        names = ("loco_compensate_quantize_fixed", "loco_dequant_reduce_fixed")
+        state_bytes = 1 if args.state == "int8" else 4
+        bytes_cq, bytes_dr = gsz + 2 * state_bytes + bits / 8.0, W * bits / 8.0 + 4
+        names = ("loco_compensate_quantize_fixed" + ("" if args.state == "int8" else "_f32state"),
+                 "loco_dequant_reduce_fixed")
     opt = args.optimizer
     if opt != "none":   # g~ is not written; theta (and m, v) are read and written in place
         bytes_dr += {"sgd": 8, "adam": 24}[opt] - 4
@@ -259,10 +268,15 @@ def main():
         err = torch.empty(n, dtype=torch.float32, device=dev)
     else:
         def state_init(e):
-            loco_error_state8_init(e, stream)
+            if args.state == "int8":
+                loco_error_state8_init(e, stream)
+            else:
+                loco_error_state_init(e, stream)
 
         def cq(g, e, codes, scales):
-            if clip is not None:
+            if args.state == "f32":
+                loco_compensate_quantize_fixed_f32state(g, e, bits, FIXED_LOG2_S, w.beta, False, codes, stream)
+            elif clip is not None:
                 loco_compensate_quantize_fixed_clip(g, clip, e, bits, FIXED_LOG2_S, FIXED_SE_MULT, w.beta, False,
                                                     codes, stream)
             else:
@@ -278,7 +292,7 @@ def main():
             else:
                 loco_dequant_reduce_fixed_adam(recv_codes, cstride, W, n, bits, FIXED_LOG2_S, ETA, BETA1, BETA2,
                                                DELTA, mom, var, theta, stream)
-        err = torch.empty(n, dtype=torch.int8, device=dev)
+        err = torch.empty(n, dtype=torch.int8 if args.state == "int8" else torch.float32, device=dev)
     state_init(err)
     tmp_err = torch.empty_like(err)
     for k in range(1, W):
@@ -385,7 +399,8 @@ def main():
         del src, src2, dst, sink
 
     cpu = None
-    if args.cpu_sample > 0 and opt == "none" and args.out == "f32" and not bf16_steps and clip is None:
+    if args.cpu_sample > 0 and opt == "none" and args.out == "f32" and not bf16_steps and clip is None \
+            and args.state == "int8":
         # own payload for the sample: one compensate-quantize step from a zero state
         state_init(err)
         cq(grads[0], err, own_codes, own_scales)
@@ -408,7 +423,8 @@ def main():
         "config": {"workload": w.name, "n": n, "grad_dtype": str(w.grad_dtype).replace("torch.", ""),
                    "bits": bits, "beta": w.beta, "num_workers": W, "form": form, "optimizer": opt, "out": args.out, "scales": args.scales, "clip_abs": clip,
                    **({"block_size": B} if form == "block" else
-                      {"log2_s": FIXED_LOG2_S, "se_mult": FIXED_SE_MULT, "state": "int8"}),
+                      {"log2_s": FIXED_LOG2_S, "se_mult": FIXED_SE_MULT if args.state == "int8" else None,
+                       "state": args.state}),
                    "step": " + ".join(n_[5:] for n_ in names)},
         "elements_per_s": n / (total_s / args.steps),
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,

@@ -154,6 +154,20 @@ loco_status_t loco_compensate_quantize_fixed(const void *grad, loco_dtype_t grad
                                              void *stream);
 
 /*
+ * The same compressor with the compensation error kept in high precision: Algorithm 1 without
+ * decompressor(e; s_e) and compressor(.; s_e, 8), which is the paper's ablation row without error
+ * compression (Table 9, Sec. 5.4):
+ *   h = g + e~;  q, d as above;  e~' = (1-beta) e~ + beta (h - d), or 0 when reset != 0.
+ *   err_state    [n] fp32 device, read and overwritten in place, 16-byte aligned
+ * Other arguments as for loco_compensate_quantize_fixed; the payload is the same, so the receive
+ * side is loco_dequant_reduce_fixed.  State of the same type as loco_error_state_init writes.
+ */
+loco_status_t loco_compensate_quantize_fixed_f32state(const void *grad, loco_dtype_t grad_dtype,
+                                                      float *err_state, size_t n, int bits, int log2_s,
+                                                      float beta, int reset, uint8_t *codes_out,
+                                                      void *stream);
+
+/*
  * Algorithm 1, step 3 / Eq. 8 with the global scale:
  *   out_i = (sum_{w=0}^{W-1} float(q^w_i) / s) * (1/W)
  * Payload w is at codes + w*code_stride_bytes (a multiple of 16, >= loco_code_bytes(n, bits);

@@ -38,6 +38,7 @@ EXPORTS = (
     "loco_reset_due",
     "loco_error_state8_init",
     "loco_compensate_quantize_fixed",
+    "loco_compensate_quantize_fixed_f32state",
     "loco_dequant_reduce_fixed",
     "loco_compensate_quantize_clip",
     "loco_compensate_quantize_fixed_clip",
@@ -97,6 +98,8 @@ def load_library(path: Optional[str] = None):
     lib.loco_error_state8_init.argtypes, lib.loco_error_state8_init.restype = [vp, sz, vp], i
     lib.loco_compensate_quantize_fixed.argtypes = [vp, i, vp, sz, i, i, i, f, i, vp, vp]
     lib.loco_compensate_quantize_fixed.restype = i
+    lib.loco_compensate_quantize_fixed_f32state.argtypes = [vp, i, vp, sz, i, i, f, i, vp, vp]
+    lib.loco_compensate_quantize_fixed_f32state.restype = i
     lib.loco_dequant_reduce_fixed.argtypes = [vp, sz, i, sz, i, i, vp, vp]
     lib.loco_dequant_reduce_fixed.restype = i
     lib.loco_compensate_quantize_clip.argtypes = [vp, i, f, vp, sz, i, i, f, i, vp, vp, vp]
@@ -310,6 +313,30 @@ def loco_error_state8_init(err_state8: torch.Tensor, stream=None) -> None:
     lib = load_library()
     p = _dev_ptr(err_state8, "err_state8", torch.int8)
     _check("loco_error_state8_init", lib.loco_error_state8_init(p, err_state8.numel(), _stream_handle(stream)))
+
+
+def loco_compensate_quantize_fixed_f32state(grad: torch.Tensor, err_state: torch.Tensor, bits: int, log2_s: int,
+                                            beta: float, reset: bool, codes_out: torch.Tensor, stream=None) -> None:
+    """Algorithm 1 steps 1-2 with the global scale s = 2^log2_s and the compensation error kept
+    in float32 (the ablation row without error compression): err_state is updated in place."""
+    lib = load_library()
+    if grad.dtype == torch.float32:
+        gd = LOCO_F32
+    elif grad.dtype == torch.bfloat16:
+        gd = LOCO_BF16
+    else:
+        raise TypeError(f"grad must be float32 or bfloat16, got {grad.dtype}")
+    n = grad.numel()
+    pg = _dev_ptr(grad, "grad")
+    pe = _dev_ptr(err_state, "err_state", torch.float32)
+    pc = _dev_ptr(codes_out, "codes_out", torch.uint8)
+    if err_state.numel() != n:
+        raise ValueError("err_state must have as many elements as grad")
+    if bits in (4, 8) and codes_out.numel() < (n * bits + 7) // 8:
+        raise ValueError("codes_out too small")
+    st = lib.loco_compensate_quantize_fixed_f32state(pg, gd, pe, n, int(bits), int(log2_s), float(beta),
+                                                     1 if reset else 0, pc, _stream_handle(stream))
+    _check("loco_compensate_quantize_fixed_f32state", st)
 
 
 def loco_compensate_quantize_fixed(grad: torch.Tensor, err_state8: torch.Tensor, bits: int, log2_s: int,

@@ -5,6 +5,7 @@
 //   fixed_cq_kernel  e^ = float(e)/s_e; h = g + e^; q = clamp(rint(h s)); d = float(q)/s;
 //                    e~' = (1-beta) e^ + beta (h - d); e' = clamp(rint(e~' s_e)) or 0 on reset
 //   fixed_dr_kernel  out = (sum_w float(q^w)/s) * (1/W)                          (Eq. 8)
+//   fixed_f32_cq_kernel  the same compressor with the state kept in fp32 (no s_e)
 //
 // 4.5 bytes move per element (bf16 gradient, 8-bit state in and out, 4-bit codes) against
 // about 20 VALU operations, so fixed_cq_kernel sits where the HBM and the VALU limits of
@@ -152,6 +153,87 @@ fixed_cq_kernel(const void* __restrict__ grad, int8_t* __restrict__ err8, size_t
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
                     if (i + j < n) codes[i + j] = (uint8_t)(c[j >> 2] >> (8 * (j & 3)));
+            }
+        }
+    }
+}
+
+// ---- global scale, compensation error kept in fp32 ----
+// Algorithm 1 without the 8-bit round trip of the state (the paper's ablation row without error
+// compression, Table 9): h = g + e~; q = clamp(rint(h s)); d = float(q)/s;
+// e~' = (1-beta) e~ + beta (h - d), or 0 on a reset step.  The fp32 state makes the traffic mix
+// that of cq_kernel without the block steps, so the decomposition is cq_kernel's: a lane owns
+// a quad per slot (16 B of state, 8 B of bf16 gradient, 2 or 4 B of codes).
+template <int BITS>
+__device__ __forceinline__ uint32_t fixed_f32_quad(const float (&h)[4], float (&e)[4], const FixedScales& k,
+                                                   bool reset) {
+    constexpr float QMAX = (float)((1 << (BITS - 1)) - 1);
+    constexpr float QMIN = -(float)(1 << (BITS - 1));
+    uint32_t pk = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float qf = fminf(fmaxf(rintf(h[j] * k.s), QMIN), QMAX);    // Eq. 1, 3
+        const float d = qf * k.inv_s;                                     // float(q) / s, exact
+        const float delta = h[j] - d;                                     // Eq. 4
+        const float bd = k.beta * delta;
+        e[j] = reset ? 0.0f : __builtin_fmaf(k.one_minus_beta, e[j], bd); // Eq. 5 / Eq. 7
+        pk |= ((uint32_t)(int)qf & (BITS == 4 ? 15u : 255u)) << (BITS * j);
+    }
+    return pk;
+}
+
+template <typename G, int BITS, int SLOTS, int THREADS, bool NT>
+__global__ void __launch_bounds__(THREADS)
+fixed_f32_cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, FixedScales k, int reset,
+                    uint8_t* __restrict__ codes) {
+    constexpr size_t TILE = (size_t)kSlot * SLOTS;
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const size_t tile0 = wave_tile_index<THREADS, 0>() * TILE;
+    const bool rst = reset != 0;
+    if (tile0 >= n) return;
+
+    if (tile0 + TILE <= n) {
+        float h[SLOTS][4], e[SLOTS][4];
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
+            Grad<G>::template load4<NT>(grad, i, h[s]);
+            const f32x4 v = vload<NT>(reinterpret_cast<const f32x4*>(err + i));
+            e[s][0] = v.x; e[s][1] = v.y; e[s][2] = v.z; e[s][3] = v.w;
+        }
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) h[s][j] = h[s][j] + e[s][j];   // Eq. 2
+            const uint32_t pk = fixed_f32_quad<BITS>(h[s], e[s], k, rst);
+            vstore<NT>(reinterpret_cast<f32x4*>(err + i), f32x4{e[s][0], e[s][1], e[s][2], e[s][3]});
+            if constexpr (BITS == 4) vstore<NT>(reinterpret_cast<uint16_t*>(codes + (i >> 1)), (uint16_t)pk);
+            else vstore<NT>(reinterpret_cast<uint32_t*>(codes + i), pk);
+        }
+    } else {
+#pragma unroll 1
+        for (int s = 0; s < SLOTS; ++s) {
+            const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
+            if (i >= n) continue;
+            float h[4], e[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool in = i + j < n;
+                e[j] = in ? err[i + j] : 0.0f;
+                h[j] = (in ? Grad<G>::load1(grad, i + j) : 0.0f) + e[j];   // past n: code 0
+            }
+            const uint32_t pk = fixed_f32_quad<BITS>(h, e, k, rst);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (i + j < n) err[i + j] = e[j];
+            if constexpr (BITS == 4) {
+                codes[i >> 1] = (uint8_t)pk;
+                if (i + 2 < n) codes[(i >> 1) + 1] = (uint8_t)(pk >> 8);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (i + j < n) codes[i + j] = (uint8_t)(pk >> (8 * j));
             }
         }
     }

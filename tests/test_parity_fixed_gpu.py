@@ -288,3 +288,79 @@ def test_fixed_argument_errors():
         loco_dequant_reduce_fixed(codes, 8, 2, 64, 4, 19, out)      # stride shorter than a payload
     assert ei.value.status == 1
     torch.cuda.synchronize()
+
+
+# ---- global scale with the compensation error kept in fp32 (ablation row without error compression) ----
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_fixed_f32state_small_and_ragged_shapes(bits, dtype):
+    from paper_2407_04480_amd import loco_compensate_quantize_fixed_f32state, loco_error_state_init
+    rng = torch.Generator(device="cpu").manual_seed(500 + bits + (dtype == torch.bfloat16))
+    qmax = (1 << (bits - 1)) - 1
+    for n in SHAPES + [6 * 2048 + 1031]:
+        for log2_s, beta in ((19, 0.25), (17, 1.0), (3, 0.3)):
+            e_t = torch.full((n,), 3.0, dtype=torch.float32, device=DEV)
+            loco_error_state_init(e_t)
+            e_host = np.zeros(n, np.float32)
+            for step in range(3):
+                g = (torch.randn(n, generator=rng) * (0.6 * qmax / 2.0 ** log2_s)).to(dtype)   # some clamp
+                codes_t = torch.full((loco_code_bytes(n, bits),), 0x5A, dtype=torch.uint8, device=DEV)
+                reset = step == 1 and beta == 0.3
+                loco_compensate_quantize_fixed_f32state(g.to(DEV), e_t, bits, log2_s, beta, reset, codes_t)
+                c_ref = oracle.fixed_compensate_quantize_f32state(workloads.as_numpy_grad(g), e_host, bits, log2_s, beta,
+                                                                  int(reset))
+                torch.cuda.synchronize()
+                tag = f"n={n} bits={bits} {dtype} s=2^{log2_s} beta={beta} step={step}"
+                assert np.array_equal(codes_t.cpu().numpy(), c_ref), f"{tag}: codes differ"
+                e_gpu = e_t.cpu().numpy()
+                assert np.array_equal(e_gpu, e_host), f"{tag}: {np.count_nonzero(e_gpu != e_host)} state values differ"
+
+
+def test_fixed_f32state_full_size_every_element(capsys):
+    """The 7B shard, whole array, two steps; then Eq. 8 over payloads of this form."""
+    from paper_2407_04480_amd import loco_compensate_quantize_fixed_f32state, loco_error_state_init
+    w = workloads.by_name("llama7b_shard_4bit_b256")
+    n, bits, log2_s, W = w.n, 4, 19, 3
+    cb = loco_code_bytes(n, bits)
+    stride = (cb + 15) // 16 * 16
+    recv = torch.zeros(W * stride, dtype=torch.uint8, device=DEV)
+    ref = np.zeros((W, stride), np.uint8)
+    err = torch.empty(n, dtype=torch.float32, device=DEV)
+    e_ref = np.zeros(n, np.float32)
+    for k in range(W):
+        loco_error_state_init(err)
+        e_ref[:] = 0
+        for step in range(2 if k == 0 else 1):
+            g = (workloads.gradient(w, step, worker=None if k == 0 else k, device=DEV) * 1e-2).to(torch.bfloat16)
+            loco_compensate_quantize_fixed_f32state(g, err, bits, log2_s, w.beta, False, recv[k * stride:k * stride + cb])
+            ref[k, :cb] = oracle.fixed_compensate_quantize_f32state(workloads.as_numpy_grad(g), e_ref, bits, log2_s, w.beta)
+            torch.cuda.synchronize()
+            del g
+            assert np.array_equal(recv[k * stride:k * stride + cb].cpu().numpy(), ref[k, :cb]), f"w={k} step={step}: codes"
+            e_gpu = err.cpu().numpy()
+            assert np.array_equal(e_gpu, e_ref), f"w={k} step={step}: {np.count_nonzero(e_gpu != e_ref)} state values"
+            with capsys.disabled():
+                print(f"[fixed, fp32 state, whole array] worker {k} step {step}: identical over {n} elements", flush=True)
+    out = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    loco_dequant_reduce_fixed(recv, stride, W, n, bits, log2_s, out)
+    want = oracle.fixed_dequant_reduce(ref.reshape(-1), W, n, bits, log2_s, code_stride_bytes=stride, threads=16)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want)
+
+
+def test_fixed_f32state_argument_errors():
+    from paper_2407_04480_amd import loco_compensate_quantize_fixed_f32state
+    n = 4096
+    g = torch.zeros(n, device=DEV)
+    e = torch.zeros(n, device=DEV)
+    codes = torch.zeros(n // 2, dtype=torch.uint8, device=DEV)
+    for kw, status in ((dict(bits=5), 2), (dict(log2_s=65), 2), (dict(beta=1.5), 1), (dict(beta=float("nan")), 1)):
+        a = dict(bits=4, log2_s=19, beta=0.25)
+        a.update(kw)
+        with pytest.raises(LocoError) as ei:
+            loco_compensate_quantize_fixed_f32state(g, e, a["bits"], a["log2_s"], a["beta"], False, codes)
+        assert ei.value.status == status
+    with pytest.raises(LocoError) as ei:
+        loco_compensate_quantize_fixed_f32state(g[1:], e[1:], 4, 19, 0.25, False, codes)
+    assert ei.value.status == 3
+    torch.cuda.synchronize()
