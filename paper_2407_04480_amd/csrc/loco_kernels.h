@@ -473,8 +473,17 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __rest
 #pragma unroll
                     for (int s = 0; s < SLOTS; ++s) {
                         c[u][s] = load_quad_codes<BITS, NT>(cbase + (size_t)(s * SLOT_CODE_BYTES + code_off));
-                        if constexpr (UNIFORM_STEP) D[u][s] = load_uniform_step(scales, sidx + (s * kSlot) / BLOCK);
-                        else D[u][s] = step_from_storage(scales[sidx + (size_t)(s * (kSlot / BLOCK) + step_off)]);
+                        if constexpr (UNIFORM_STEP) {
+                            D[u][s] = load_uniform_step(scales, sidx + (s * kSlot) / BLOCK);
+                        } else if constexpr (BLOCK * 2 == kSlot) {
+                            // two blocks per slot: two scalar loads and a select by half-wavefront measured
+                            // 1-4 % faster than a vector load (with 4 or 8 blocks per slot it is slower)
+                            const float lo = load_uniform_step(scales, sidx + (size_t)(s * 2));
+                            const float hi = load_uniform_step(scales, sidx + (size_t)(s * 2 + 1));
+                            D[u][s] = step_off ? hi : lo;
+                        } else {
+                            D[u][s] = step_from_storage(scales[sidx + (size_t)(s * (kSlot / BLOCK) + step_off)]);
+                        }
                     }
                     cbase += code_stride;
                     sidx += scale_stride;
