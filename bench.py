@@ -36,7 +36,7 @@ MEASURED_TRAFFIC = {
     ("llama7b_shard_8bit_b64", "loco_compensate_quantize"): 9.3179e9,
     ("llama7b_shard_8bit_b64", "loco_dequant_reduce"): 1.05485e10,
     ("mixtral_moe_shard_4bit_b128", "loco_compensate_quantize"): 1.48414e10,
-    ("mixtral_moe_shard_4bit_b128", "loco_dequant_reduce"): 6.3858e9,
+    ("mixtral_moe_shard_4bit_b128", "loco_dequant_reduce"): 6.4299e9,
     ("dense70b_shard_4bit_b256", "loco_compensate_quantize"): 2.31829e10,
     ("dense70b_shard_4bit_b256", "loco_dequant_reduce"): 2.76200e10,
     ("llama7b_shard_4bit_b256", "loco_compensate_quantize_fixed"): 3.7904e9,
