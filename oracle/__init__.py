@@ -50,6 +50,8 @@ def _bind(lib):
     c = ctypes
     vp, sz, i, f = c.c_void_p, c.c_size_t, c.c_int, c.c_float
     lib.loco_ref_error_state_init.argtypes = [vp, sz]
+    lib.loco_ref_reset_due.argtypes = [c.c_longlong, c.c_longlong]
+    lib.loco_ref_reset_due.restype = c.c_int
     lib.loco_ref_compensate_quantize.argtypes = [vp, i, vp, sz, i, i, f, i, vp, vp]
     lib.loco_ref_compensate_quantize_blocks.argtypes = [vp, i, vp, sz, i, i, f, i, vp, vp, sz, sz]
     lib.loco_ref_compensate_quantize_mt.argtypes = [vp, i, vp, sz, i, i, f, i, vp, vp, i]
@@ -130,6 +132,12 @@ def error_state_init(err_state: np.ndarray, lib=None) -> None:
     rc = lib.loco_ref_error_state_init(_ptr(err_state), err_state.size)
     if rc:
         raise ValueError("loco_ref_error_state_init: status %d" % rc)
+
+
+def reset_due(step_index: int, reset_period: int, lib=None) -> bool:
+    """Eq. 7 / Alg. 1: step k resets the state when k % T_c == 0 (never for T_c <= 0)."""
+    lib = lib or load()
+    return bool(lib.loco_ref_reset_due(int(step_index), int(reset_period)))
 
 
 def compensate_quantize(grad, err_state, bits, block_size, beta, reset=0, threads=1, lib=None,

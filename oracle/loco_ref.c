@@ -80,6 +80,18 @@ int loco_ref_error_state_init(float *err_state, size_t n)
 }
 
 /*
+ * Eq. 7 / Alg. 1 ("e_{k+1} = 0 if k % T_c = 0"): is step k one whose new state is zero?
+ * The rule as printed fires at k = 0, T_c, 2 T_c, ...; a period of 0 or less never resets.
+ */
+int loco_ref_reset_due(long long step_index, long long reset_period)
+{
+    if (reset_period <= 0)
+        return 0;
+    long long remainder = step_index % reset_period;
+    return remainder == 0;
+}
+
+/*
  * Alg. 1 steps 1-2 on the blocks [block_lo, block_hi) of one shard of n elements.
  * Blocks are independent, so any split into block ranges gives the same bytes;
  * with 4-bit codes a range must start at an even element index.

@@ -331,6 +331,35 @@ def check_reset(lib):
     assert np.all(np.signbit(eb) == False)  # noqa: E712
 
 
+def check_reset_schedule(lib):
+    """Eq. 7 / Alg. 1 as printed: the state written by step k is zero exactly when k % T_c = 0,
+    i.e. at k = 0, T_c, 2 T_c, ... (T_c = 512 or 1024 in Sec. 3.2); composed with the step itself,
+    the state after a reset step is zero and the steps between resets follow Eq. 5."""
+    for T in (2, 3, 7, 128, 512, 1024):
+        got = [k for k in range(0, 3 * T + 2) if lib.loco_ref_reset_due(k, T)]
+        assert got == [0, T, 2 * T, 3 * T], (T, got)
+    assert all(lib.loco_ref_reset_due(k, 1) for k in range(0, 10))
+    assert not any(lib.loco_ref_reset_due(k, 0) for k in range(0, 2000))
+    assert not any(lib.loco_ref_reset_due(k, -4) for k in range(0, 20))
+    assert lib.loco_ref_reset_due(1 << 40, 1 << 20) and not lib.loco_ref_reset_due((1 << 40) + 1, 1 << 20)
+    assert lib.loco_ref_reset_due(3 * ((1 << 33) + 1), (1 << 33) + 1)
+    # composed with the step: T_c = 3 over 8 steps, beta = 1 makes the state the raw error of the step
+    rng = np.random.default_rng(77)
+    bits, B, n, T = 4, 64, 64 * 5 + 9, 3
+    e = np.zeros(n, np.float32)
+    for k in range(8):
+        g = rng_grad(rng, n)
+        h = g + e
+        due = lib.loco_ref_reset_due(k, T)
+        codes, scales = cq(lib, g, e, bits, B, 1.0, reset=due)
+        if k % T == 0:
+            assert due and not e.any()
+        else:
+            assert not due
+            d = decode1(lib, codes, scales, n, bits, B)
+            assert np.array_equal(e, h - d)
+
+
 def check_dequant_reduce(lib):
     """Eq. 8: N = 1 returns float(q)/s; N equal payloads return that value again (exactly
     for N = 2); a general N is the mean of the decoded payloads."""
@@ -464,6 +493,7 @@ ALL_CHECKS = [
     check_telescoping,
     check_fixed_scale_form,
     check_reset,
+    check_reset_schedule,
     check_dequant_reduce,
     check_bf16_widening,
     check_edges,

@@ -29,6 +29,9 @@ MUTANTS = [
     ("unsigned_nibble_decode", "return (nib ^ 8) - 8;", "return nib;"),
     ("no_average", "grad_out[i] = acc * inv;", "grad_out[i] = acc;"),
     ("reset_ignored", "reset ? 0.0f : fmaf", "0 ? 0.0f : fmaf"),
+    ("reset_schedule_off_by_one", "return remainder == 0;", "return remainder == reset_period - 1;"),
+    ("reset_schedule_skips_step_zero", "return remainder == 0;", "return remainder == 0 && step_index != 0;"),
+    ("reset_schedule_every_step", "long long remainder = step_index % reset_period;", "long long remainder = 0;"),
     ("bf16_shift", "[i] << 16;", "[i] << 15;"),
     ("worker_scale_stride", "scales[(size_t)w * scale_stride_elems + b]", "scales[b]"),
     ("worker_code_stride", "codes + (size_t)w * code_stride_bytes", "codes"),
