@@ -47,7 +47,7 @@ extern "C" {
 typedef enum {
     LOCO_OK = 0,
     LOCO_ERR_INVALID_ARG = 1, /* NULL pointer, beta outside [0,1] or NaN, W < 1, stride too small */
-    LOCO_ERR_UNSUPPORTED = 2, /* bits, block_size or dtype outside the supported sets */
+    LOCO_ERR_UNSUPPORTED = 2, /* bits, block_size, dtype, worker count or decomposition outside the supported sets */
     LOCO_ERR_ALIGNMENT = 3,   /* a pointer or stride breaks the alignment rule of the call */
     LOCO_ERR_LAUNCH = 4,      /* the HIP runtime refused the launch */
     LOCO_ERR_BAD_POINTER = 5  /* a buffer is not device memory, or too small for the call */
@@ -119,6 +119,34 @@ loco_status_t loco_dequant_reduce(const uint8_t *codes, size_t code_stride_bytes
                                   int num_workers, size_t n, int bits, int block_size,
                                   float *grad_out, void *stream);
 
+/*
+ * Algorithm 1, steps 1 and 2, with the reset schedule of Eq. 7 evaluated on the device:
+ * the kernel reads the step index k from device memory and zeroes the state when
+ * reset_period > 0 and k % reset_period == 0 (Algorithm 1: "e_{k+1} = 0 if k % T_c = 0";
+ * T_c = 512 or 1024 in Sec. 3.2).  Nothing about the step is baked into the launch, so one
+ * captured HIP graph of a training step can be replayed across reset steps while another
+ * node advances the counter (loco_step_index_advance).
+ *   step_index_dev  one int64 in device memory, 8-byte aligned, read only; k >= 0
+ *   reset_period    T_c >= 0; 0 means the state is never reset
+ * Everything else as loco_compensate_quantize; the step index must not change while the
+ * call's kernel runs (stream order with the call that advances it is enough).
+ */
+loco_status_t loco_compensate_quantize_scheduled(const void *grad, loco_dtype_t grad_dtype,
+                                                 float *err_state, size_t n, int bits, int block_size,
+                                                 float beta, const int64_t *step_index_dev,
+                                                 int64_t reset_period, uint8_t *codes_out,
+                                                 float *scales_out, void *stream);
+
+/*
+ * The step counter k of Algorithm 1 kept in device memory for the _scheduled calls.
+ *   loco_step_index_set      k = value
+ *   loco_step_index_advance  k = k + 1
+ * One small kernel each (no memset, no host write), so both may be captured into a HIP
+ * graph.  step_index_dev: one int64, device, 8-byte aligned.
+ */
+loco_status_t loco_step_index_set(int64_t *step_index_dev, int64_t value, void *stream);
+loco_status_t loco_step_index_advance(int64_t *step_index_dev, void *stream);
+
 /* ------------------------------------------------------------------------------------
  * Algorithm 1 exactly as printed: one global scale s for the gradient codes and the error
  * state itself kept as 8-bit codes (Eq. 1-3, 5, 7; s = 2^19 or 2^17, s_e = 4s or 6s in
@@ -168,10 +196,29 @@ loco_status_t loco_compensate_quantize_fixed_f32state(const void *grad, loco_dty
                                                       void *stream);
 
 /*
+ * The two calls above with Eq. 7's schedule read from device memory, as
+ * loco_compensate_quantize_scheduled: reset when reset_period > 0 and k % reset_period == 0.
+ */
+loco_status_t loco_compensate_quantize_fixed_scheduled(const void *grad, loco_dtype_t grad_dtype,
+                                                       int8_t *err_state8, size_t n, int bits, int log2_s,
+                                                       int se_mult, float beta, const int64_t *step_index_dev,
+                                                       int64_t reset_period, uint8_t *codes_out, void *stream);
+loco_status_t loco_compensate_quantize_fixed_f32state_scheduled(const void *grad, loco_dtype_t grad_dtype,
+                                                                float *err_state, size_t n, int bits,
+                                                                int log2_s, float beta,
+                                                                const int64_t *step_index_dev,
+                                                                int64_t reset_period, uint8_t *codes_out,
+                                                                void *stream);
+
+/*
  * Algorithm 1, step 3 / Eq. 8 with the global scale:
  *   out_i = (sum_{w=0}^{W-1} float(q^w_i) / s) * (1/W)
  * Payload w is at codes + w*code_stride_bytes (a multiple of 16, >= loco_code_bytes(n, bits);
  * ignored when W == 1).  grad_out: [n] fp32 device, 16-byte aligned.
+ * The codes are summed as integers and converted once, which equals the binary32 sum in
+ * worker order as long as every partial sum stays below 2^24: num_workers <= 2^21 (4 bits)
+ * or 2^17 (8 bits); more is LOCO_ERR_UNSUPPORTED.  The same bound holds for the _bf16, _sgd
+ * and _adam forms of this call.
  */
 loco_status_t loco_dequant_reduce_fixed(const uint8_t *codes, size_t code_stride_bytes, int num_workers,
                                         size_t n, int bits, int log2_s, float *grad_out, void *stream);
@@ -242,6 +289,9 @@ loco_status_t loco_dequant_reduce_fixed_bf16(const uint8_t *codes, size_t code_s
  * steps are uint16_t bf16 bit patterns (scales_out_bf16 2-byte aligned, so a
  * payload may be written anywhere into a receive buffer; the reduce wants the
  * base of that buffer 4-byte aligned, stride in elements of any parity).
+ * The reduce may read the whole aligned 32-bit word that holds a step, i.e. up to 2 bytes
+ * past an array with an odd number of steps; it never writes there, and the word lies in
+ * the same allocation granule as the last step.
  */
 loco_status_t loco_compensate_quantize_bf16_scales(const void *grad, loco_dtype_t grad_dtype, float *err_state,
                                                    size_t n, int bits, int block_size, float beta, int reset,
@@ -250,6 +300,25 @@ loco_status_t loco_dequant_reduce_bf16_scales(const uint8_t *codes, size_t code_
                                               const uint16_t *scales_bf16, size_t scale_stride_elems,
                                               int num_workers, size_t n, int bits, int block_size,
                                               float *grad_out, void *stream);
+
+/*
+ * Measurement and tuning aid: loco_dequant_reduce with the work decomposition chosen by the
+ * caller instead of by the library (same arithmetic, same result bit for bit):
+ *   0  what loco_dequant_reduce picks (see loco_dequant_reduce_decomposition)
+ *   1  a lane owns 4 consecutive elements; block steps by scalar loads (B >= 128) or one
+ *      vector load per payload (B <= 64)
+ *   2  as 1, block steps of a group of payloads by one vector load (B >= 128 only)
+ *   3, 4, 5  a lane loads 4, 8, 16 bytes of codes per payload (8 .. 32 consecutive elements;
+ *      3 is for 4-bit codes only) and the sums are transposed through LDS before the stores
+ * A decomposition that does not exist for (bits, block_size) is LOCO_ERR_UNSUPPORTED.
+ * loco_dequant_reduce_decomposition returns the library's own choice (1..5) for a worker
+ * count, bit width and block size, or -1 for arguments outside the supported sets.
+ */
+loco_status_t loco_dequant_reduce_decomposed(const uint8_t *codes, size_t code_stride_bytes,
+                                             const float *scales, size_t scale_stride_elems,
+                                             int num_workers, size_t n, int bits, int block_size,
+                                             float *grad_out, int decomposition, void *stream);
+int loco_dequant_reduce_decomposition(int num_workers, int bits, int block_size);
 
 /*
  * Measurement aids, not part of the method: plain streaming kernels with the same
@@ -264,11 +333,14 @@ loco_status_t loco_dequant_reduce_bf16_scales(const uint8_t *codes, size_t code_
  *                     keeps the loads alive without a store stream)
  *   loco_stream_fill  dst[i] = 0
  *   loco_stream_sum2  dst[i] = src_a[i] + src_b[i] on 32-bit words (wrapping)
+ * loco_runtime_copy is the HIP runtime's own device-to-device copy (hipMemcpyDtoDAsync) on
+ * the same stream, as an independent figure beside loco_stream_copy; any size and alignment.
  */
 loco_status_t loco_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
 loco_status_t loco_stream_read(const void *src, size_t bytes, void *sink16, void *stream);
 loco_status_t loco_stream_fill(void *dst, size_t bytes, void *stream);
 loco_status_t loco_stream_sum2(void *dst, const void *src_a, const void *src_b, size_t bytes, void *stream);
+loco_status_t loco_runtime_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 /*
  * Measurement aid, not part of the method: what the current device reports

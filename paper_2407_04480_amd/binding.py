@@ -48,6 +48,14 @@ EXPORTS = (
     "loco_dequant_reduce_fixed_adam",
     "loco_dequant_reduce_bf16",
     "loco_dequant_reduce_fixed_bf16",
+    "loco_compensate_quantize_scheduled",
+    "loco_compensate_quantize_fixed_scheduled",
+    "loco_compensate_quantize_fixed_f32state_scheduled",
+    "loco_step_index_set",
+    "loco_step_index_advance",
+    "loco_dequant_reduce_decomposed",
+    "loco_dequant_reduce_decomposition",
+    "loco_runtime_copy",
 )
 
 _lib = None
@@ -114,6 +122,19 @@ def load_library(path: Optional[str] = None):
     lib.loco_dequant_reduce_bf16.restype = i
     lib.loco_dequant_reduce_fixed_bf16.argtypes = [vp, sz, i, sz, i, i, vp, vp]
     lib.loco_dequant_reduce_fixed_bf16.restype = i
+    i64 = c.c_int64
+    lib.loco_compensate_quantize_scheduled.argtypes = [vp, i, vp, sz, i, i, f, vp, i64, vp, vp, vp]
+    lib.loco_compensate_quantize_scheduled.restype = i
+    lib.loco_compensate_quantize_fixed_scheduled.argtypes = [vp, i, vp, sz, i, i, i, f, vp, i64, vp, vp]
+    lib.loco_compensate_quantize_fixed_scheduled.restype = i
+    lib.loco_compensate_quantize_fixed_f32state_scheduled.argtypes = [vp, i, vp, sz, i, i, f, vp, i64, vp, vp]
+    lib.loco_compensate_quantize_fixed_f32state_scheduled.restype = i
+    lib.loco_step_index_set.argtypes, lib.loco_step_index_set.restype = [vp, i64, vp], i
+    lib.loco_step_index_advance.argtypes, lib.loco_step_index_advance.restype = [vp, vp], i
+    lib.loco_dequant_reduce_decomposed.argtypes = [vp, sz, vp, sz, i, sz, i, i, vp, i, vp]
+    lib.loco_dequant_reduce_decomposed.restype = i
+    lib.loco_dequant_reduce_decomposition.argtypes, lib.loco_dequant_reduce_decomposition.restype = [i, i, i], i
+    lib.loco_runtime_copy.argtypes, lib.loco_runtime_copy.restype = [vp, vp, sz, vp], i
     for _n in ("loco_dequant_reduce_sgd", "loco_dequant_reduce_adam", "loco_dequant_reduce_fixed_sgd",
                "loco_dequant_reduce_fixed_adam"):
         getattr(lib, _n).restype = i
@@ -464,3 +485,121 @@ def loco_dequant_reduce_fixed_bf16(codes, code_stride_bytes, num_workers, n, bit
                                             int(num_workers), int(n), int(bits), int(log2_s), po,
                                             _stream_handle(stream))
     _check("loco_dequant_reduce_fixed_bf16", st)
+
+
+def _grad_dtype_code(grad: torch.Tensor) -> int:
+    if grad.dtype == torch.float32:
+        return LOCO_F32
+    if grad.dtype == torch.bfloat16:
+        return LOCO_BF16
+    raise TypeError(f"grad must be float32 or bfloat16, got {grad.dtype}")
+
+
+def _step_index_ptr(step_index: torch.Tensor) -> int:
+    p = _dev_ptr(step_index, "step_index", torch.int64)
+    if step_index.numel() != 1:
+        raise ValueError("step_index must hold exactly one int64")
+    return p
+
+
+def loco_step_index_set(step_index: torch.Tensor, value: int, stream=None) -> None:
+    """k = value for the step counter of the _scheduled calls (one int64 on the GPU)."""
+    lib = load_library()
+    _check("loco_step_index_set", lib.loco_step_index_set(_step_index_ptr(step_index), int(value),
+                                                          _stream_handle(stream)))
+
+
+def loco_step_index_advance(step_index: torch.Tensor, stream=None) -> None:
+    """k = k + 1 (a small kernel, so the call can sit inside a captured HIP graph)."""
+    lib = load_library()
+    _check("loco_step_index_advance", lib.loco_step_index_advance(_step_index_ptr(step_index), _stream_handle(stream)))
+
+
+def loco_compensate_quantize_scheduled(grad, err_state, bits, block_size, beta, step_index: torch.Tensor,
+                                       reset_period: int, codes_out, scales_out, stream=None) -> None:
+    """Algorithm 1 steps 1-2 with Eq. 7's reset schedule (k % reset_period == 0) evaluated in the
+    kernel from the step counter in device memory."""
+    lib = load_library()
+    n = grad.numel()
+    if err_state.numel() != n:
+        raise ValueError("err_state must have as many elements as grad")
+    if bits in (4, 8) and block_size >= 1:
+        if codes_out.numel() < (n * bits + 7) // 8:
+            raise ValueError("codes_out too small")
+        if scales_out.numel() < (n + block_size - 1) // block_size:
+            raise ValueError("scales_out too small")
+    st = lib.loco_compensate_quantize_scheduled(
+        _dev_ptr(grad, "grad"), _grad_dtype_code(grad), _dev_ptr(err_state, "err_state", torch.float32), n, int(bits),
+        int(block_size), float(beta), _step_index_ptr(step_index), int(reset_period),
+        _dev_ptr(codes_out, "codes_out", torch.uint8), _dev_ptr(scales_out, "scales_out", torch.float32),
+        _stream_handle(stream))
+    _check("loco_compensate_quantize_scheduled", st)
+
+
+def loco_compensate_quantize_fixed_scheduled(grad, err_state8, bits, log2_s, se_mult, beta, step_index: torch.Tensor,
+                                             reset_period: int, codes_out, stream=None) -> None:
+    """Algorithm 1 as printed (global scale, 8-bit error state) with Eq. 7's schedule on the device."""
+    lib = load_library()
+    n = grad.numel()
+    if err_state8.numel() != n:
+        raise ValueError("err_state8 must have as many elements as grad")
+    if bits in (4, 8) and codes_out.numel() < (n * bits + 7) // 8:
+        raise ValueError("codes_out too small")
+    st = lib.loco_compensate_quantize_fixed_scheduled(
+        _dev_ptr(grad, "grad"), _grad_dtype_code(grad), _dev_ptr(err_state8, "err_state8", torch.int8), n, int(bits),
+        int(log2_s), int(se_mult), float(beta), _step_index_ptr(step_index), int(reset_period),
+        _dev_ptr(codes_out, "codes_out", torch.uint8), _stream_handle(stream))
+    _check("loco_compensate_quantize_fixed_scheduled", st)
+
+
+def loco_compensate_quantize_fixed_f32state_scheduled(grad, err_state, bits, log2_s, beta, step_index: torch.Tensor,
+                                                      reset_period: int, codes_out, stream=None) -> None:
+    """Global scale, fp32 compensation error, Eq. 7's schedule on the device."""
+    lib = load_library()
+    n = grad.numel()
+    if err_state.numel() != n:
+        raise ValueError("err_state must have as many elements as grad")
+    if bits in (4, 8) and codes_out.numel() < (n * bits + 7) // 8:
+        raise ValueError("codes_out too small")
+    st = lib.loco_compensate_quantize_fixed_f32state_scheduled(
+        _dev_ptr(grad, "grad"), _grad_dtype_code(grad), _dev_ptr(err_state, "err_state", torch.float32), n, int(bits),
+        int(log2_s), float(beta), _step_index_ptr(step_index), int(reset_period),
+        _dev_ptr(codes_out, "codes_out", torch.uint8), _stream_handle(stream))
+    _check("loco_compensate_quantize_fixed_f32state_scheduled", st)
+
+
+def loco_dequant_reduce_decomposed(codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n, bits,
+                                   block_size, grad_out, decomposition: int, stream=None) -> None:
+    """loco_dequant_reduce with the work decomposition (0..5, see loco.h) chosen by the caller."""
+    lib = load_library()
+    pc = _dev_ptr(codes, "codes", torch.uint8)
+    ps = _dev_ptr(scales, "scales", torch.float32)
+    po = _dev_ptr(grad_out, "grad_out", torch.float32)
+    if grad_out.numel() < n:
+        raise ValueError("grad_out too small")
+    if bits in (4, 8) and block_size >= 1 and num_workers >= 1 and n > 0:
+        cs = code_stride_bytes if num_workers > 1 else 0
+        ss = scale_stride_elems if num_workers > 1 else 0
+        if codes.numel() < (num_workers - 1) * cs + (n * bits + 7) // 8:
+            raise ValueError("codes too small for num_workers payloads at this stride")
+        if scales.numel() < (num_workers - 1) * ss + (n + block_size - 1) // block_size:
+            raise ValueError("scales too small for num_workers payloads at this stride")
+    st = lib.loco_dequant_reduce_decomposed(pc, int(code_stride_bytes), ps, int(scale_stride_elems), int(num_workers),
+                                            int(n), int(bits), int(block_size), po, int(decomposition),
+                                            _stream_handle(stream))
+    _check("loco_dequant_reduce_decomposed", st)
+
+
+def loco_dequant_reduce_decomposition(num_workers: int, bits: int, block_size: int) -> int:
+    """The decomposition (1..5) loco_dequant_reduce picks for these arguments; -1 if unsupported."""
+    return load_library().loco_dequant_reduce_decomposition(int(num_workers), int(bits), int(block_size))
+
+
+def loco_runtime_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    """The HIP runtime's own device-to-device copy on the stream (measurement aid)."""
+    lib = load_library()
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < nbytes:
+        raise ValueError("dst too small")
+    st = lib.loco_runtime_copy(_dev_ptr(dst, "dst"), _dev_ptr(src, "src"), nbytes, _stream_handle(stream))
+    _check("loco_runtime_copy", st)

@@ -2,8 +2,14 @@
 
 hipcc cross-compiles without a GPU.  The flags matter for correctness, not only for
 speed: -ffp-contract=off keeps one rounding per written operation (the codes must be
-reproducible bit for bit), division stays correctly rounded, and packed-fp32
-instruction selection is switched off.
+reproducible bit for bit), division and square root stay correctly rounded, and the
+target feature "packed-fp32-ops" is taken away from the device pass so that the compiler
+selects no v_pk_add/mul/fma_f32 (tests/test_build_flags.py checks the device assembly).
+
+The feature flag goes to both passes of hipcc; the HOST pass (x86-64) does not know an AMDGPU
+feature and answers with one note per function set, "'-packed-fp32-ops' is not a recognized
+feature for this target (ignoring feature)".  That note says nothing about the device pass,
+where the flag does take effect, so build() drops exactly that line from what it prints.
 """
 from __future__ import annotations
 
@@ -42,6 +48,27 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found: the library cannot be built")
 
 
+HOST_FEATURE_NOTE = "'-packed-fp32-ops' is not a recognized feature for this target (ignoring feature)"
+
+
+def without_host_feature_note(text: str) -> str:
+    """hipcc's output minus the host pass's note about the device-only feature flag."""
+    return "".join(line for line in text.splitlines(keepends=True) if line.strip() != HOST_FEATURE_NOTE)
+
+
+def device_assembly(src: str | None = None) -> str:
+    """The gfx950 assembly of the library's device code, built with the library's flags."""
+    src = src or os.path.join(CSRC, "loco_api.hip")
+    flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    cmd = [hipcc_path(), *flags, "-S", "--cuda-device-only", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+           "-o", "-", src]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stderr)
+        raise RuntimeError("hipcc -S failed (exit %d)" % res.returncode)
+    return res.stdout
+
+
 def build(out: str = LIB, tuning: dict | None = None, verbose: bool = False) -> str:
     """Compile every HIP source into one shared library; always recompiles."""
     defs = dict(TUNING)
@@ -56,8 +83,8 @@ def build(out: str = LIB, tuning: dict | None = None, verbose: bool = False) -> 
     if res.returncode != 0:
         sys.stderr.write(res.stdout + res.stderr)
         raise RuntimeError("hipcc failed (exit %d)" % res.returncode)
-    if verbose and res.stderr.strip():
-        sys.stderr.write(res.stderr)
+    if verbose:
+        sys.stderr.write(without_host_feature_note(res.stderr))
     os.replace(tmp, out)
     return out
 

@@ -7,7 +7,9 @@
 
 #include <atomic>
 #include <cmath>
+#include <tuple>
 #include <type_traits>
+#include <utility>
 
 namespace {
 
@@ -84,7 +86,22 @@ loco_status_t grid_for(size_t units, size_t per_group, unsigned* grid, size_t ro
     return LOCO_OK;
 }
 
-loco_status_t launched() { return hipGetLastError() == hipSuccess ? LOCO_OK : LOCO_ERR_LAUNCH; }
+// One kernel launch through the runtime's C entry point, which returns the status of THIS
+// launch: an error some earlier call of the caller's left behind is neither reported as ours
+// nor cleared.  The arguments are converted to the kernel's exact parameter types first.
+template <typename... P, size_t... I>
+loco_status_t launch_packed(void (*kernel)(P...), unsigned grid, unsigned threads, hipStream_t s,
+                            std::tuple<P...>& vals, std::index_sequence<I...>) {
+    void* ptrs[] = {static_cast<void*>(&std::get<I>(vals))...};
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kernel), dim3(grid), dim3(threads), ptrs, 0, s);
+    return e == hipSuccess ? LOCO_OK : LOCO_ERR_LAUNCH;
+}
+template <typename... P, typename... A>
+loco_status_t launch(void (*kernel)(P...), unsigned grid, unsigned threads, hipStream_t s, A... args) {
+    static_assert(sizeof...(P) == sizeof...(A), "one argument per kernel parameter");
+    std::tuple<P...> vals(static_cast<P>(args)...);
+    return launch_packed(kernel, grid, threads, s, vals, std::index_sequence_for<P...>{});
+}
 
 struct CqArgs {
     const void* grad;
@@ -92,6 +109,8 @@ struct CqArgs {
     size_t n;
     float beta;
     int reset;
+    const long long* step_index;   // device; nullptr: `reset` decides
+    long long reset_period;
     float clip;   // +inf: no clipping
     uint8_t* codes;
     void* scales;      // float[nb], or uint16_t[nb] holding bf16 steps
@@ -99,32 +118,31 @@ struct CqArgs {
 };
 
 template <typename G, int BITS, int BLOCK>
-void launch_cq(unsigned grid, hipStream_t s, const CqArgs& a) {
+loco_status_t launch_cq(unsigned grid, hipStream_t s, const CqArgs& a) {
     const float one_minus_beta = 1.0f - a.beta;
     using Shape = CqShape<BITS>;
     if (a.scales_bf16)   // offered without clipping only
-        cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, uint16_t>
-            <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset,
-                                                          a.clip, a.codes, static_cast<uint16_t*>(a.scales));
-    else if (std::isinf(a.clip))
-        cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, float>
-            <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset,
-                                                          a.clip, a.codes, static_cast<float*>(a.scales));
-    else
-        cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, true, float>
-            <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset,
-                                                          a.clip, a.codes, static_cast<float*>(a.scales));
+        return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, uint16_t>,
+                      grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
+                      a.reset_period, a.clip, a.codes, static_cast<uint16_t*>(a.scales));
+    if (std::isinf(a.clip))
+        return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, float>,
+                      grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
+                      a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
+    return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, true, float>,
+                  grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
+                  a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
 }
 
 template <typename G, int BITS>
-bool dispatch_cq_block(int block, unsigned grid, hipStream_t s, const CqArgs& a) {
+loco_status_t dispatch_cq_block(int block, unsigned grid, hipStream_t s, const CqArgs& a) {
     switch (block) {
-        case 32: launch_cq<G, BITS, 32>(grid, s, a); return true;
-        case 64: launch_cq<G, BITS, 64>(grid, s, a); return true;
-        case 128: launch_cq<G, BITS, 128>(grid, s, a); return true;
-        case 256: launch_cq<G, BITS, 256>(grid, s, a); return true;
-        case 512: launch_cq<G, BITS, 512>(grid, s, a); return true;
-        default: return false;
+        case 32: return launch_cq<G, BITS, 32>(grid, s, a);
+        case 64: return launch_cq<G, BITS, 64>(grid, s, a);
+        case 128: return launch_cq<G, BITS, 128>(grid, s, a);
+        case 256: return launch_cq<G, BITS, 256>(grid, s, a);
+        case 512: return launch_cq<G, BITS, 512>(grid, s, a);
+        default: return LOCO_ERR_UNSUPPORTED;
     }
 }
 
@@ -144,59 +162,100 @@ constexpr bool dr_updates_in_place(Epilogue e) { return e == Epilogue::kSgd || e
 template <int BITS, Epilogue EPI>
 using DrShapeFor = std::conditional_t<dr_updates_in_place(EPI), DrShape<8>, DrShape<BITS>>;
 
-// Elements per workgroup of the shape launch_dr picks.
-size_t dr_elements_per_group(int bits, Epilogue kind, int W) {
-    if (dr_updates_in_place(kind) || (bits == 8 && !dr_few_workers(bits, W)))
-        return (size_t)kSlot * DrShape<8>::kSlots * (DrShape<8>::kThreads / kWave);
-    if (dr_few_workers(bits, W))
-        return (size_t)kSlot * DrFewWorkersShape::kSlots * (DrFewWorkersShape::kThreads / kWave);
-    return (size_t)kSlot * DrShape<4>::kSlots * (DrShape<4>::kThreads / kWave);
+// Decompositions of the reduce.  kQuad is dr_kernel as described in loco_kernels.h;
+// kQuadLaneSteps the same with the block steps of a chunk of workers fetched by one vector
+// load (blocks of 128 elements and more); kWide4/8/16 is dr_wide_kernel with that many code
+// bytes per lane and worker.  Measured on MI355X (2^26 .. 2.2e9 elements):
+//   - at the usual worker counts (W <= 16) the quad layout is the fastest at every block size;
+//   - with many workers the code loads of the quad layout (2 bytes per lane at 4 bits) become
+//     the limit: W >= 32 with blocks of 32..128 elements gains 6-10 points of HBM peak from
+//     wide loads, W >= 96 with larger blocks 4 points;
+//   - lane-loaded steps remove the doubled fetch of step lines that the scalar cache causes
+//     (read traffic 1.037x -> 1.001x of the algorithmic bytes at 4 bits, B = 256) but cost
+//     1-6 % of speed at 4 bits; at 8 bits with B >= 256 they are 1.6 points faster.
+enum DrDecomposition { kDrAuto = 0, kDrQuad = 1, kDrQuadLaneSteps = 2, kDrWide4 = 3, kDrWide8 = 4, kDrWide16 = 5 };
+template <int CB> struct DrWideShape { static constexpr int kThreads = CB == 16 ? 128 : 256, kInFlight = 4; };
+
+int dr_auto_decomposition(int bits, int block, int W, Epilogue kind, bool scales_bf16) {
+    if (kind != Epilogue::kStore || scales_bf16) return kDrQuad;
+    if (bits == 4) {
+        if (block <= 128 && W >= 64) return kDrWide16;
+        if (block <= 128 && W >= 32) return kDrWide8;
+        if (block >= 256 && W >= 96) return kDrWide16;
+        return kDrQuad;
+    }
+    return block >= 256 && !dr_few_workers(bits, W) ? kDrQuadLaneSteps : kDrQuad;
 }
 
-template <int BITS, int BLOCK, Epilogue EPI, typename Shape>
-void launch_dr_shape(unsigned grid, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
-    const float inv_w = 1.0f / (float)a.W;
-    if constexpr (EPI == Epilogue::kStore) {   // bf16 steps are offered with the plain fp32 output only
-        if (a.scales_bf16) {
-            dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun, EPI, uint16_t>
-                <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.codes, a.code_stride,
-                                                              static_cast<const uint16_t*>(a.scales),
-                                                              a.scale_stride, a.W, a.n, inv_w, epi);
-            return;
-        }
-    }
-    dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun, EPI, float>
-        <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(a.codes, a.code_stride, static_cast<const float*>(a.scales),
-                                                      a.scale_stride, a.W, a.n, inv_w, epi);
+template <int BITS, int BLOCK, Epilogue EPI, typename Shape, typename S, bool LANE_STEPS>
+loco_status_t launch_dr_quad(hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
+    unsigned grid;
+    if (loco_status_t st = grid_for(a.n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid,
+                                    kDrXcdRun ? 8 * kDrXcdRun : 1))
+        return st;
+    return launch(dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun, EPI, S,
+                            LANE_STEPS>,
+                  grid, Shape::kThreads, s, a.codes, a.code_stride, static_cast<const S*>(a.scales), a.scale_stride, a.W,
+                  a.n, 1.0f / (float)a.W, epi);
+}
+
+template <int BITS, int BLOCK, int CB>
+loco_status_t launch_dr_wide(hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
+    using Shape = DrWideShape<CB>;
+    constexpr size_t kUnitElems = (size_t)kWave * (CB * 8 / BITS);
+    unsigned grid;
+    if (loco_status_t st = grid_for(a.n, kUnitElems * (Shape::kThreads / kWave), &grid, kDrXcdRun ? 8 * kDrXcdRun : 1))
+        return st;
+    return launch(dr_wide_kernel<BITS, BLOCK, CB, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun,
+                                 Epilogue::kStore, float>,
+                  grid, Shape::kThreads, s, a.codes, a.code_stride, static_cast<const float*>(a.scales), a.scale_stride,
+                  a.W, a.n, 1.0f / (float)a.W, epi);
 }
 
 template <int BITS, int BLOCK, Epilogue EPI>
-void launch_dr(unsigned grid, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
-    if constexpr (!dr_updates_in_place(EPI)) {
-        if (dr_few_workers(BITS, a.W)) {
-            launch_dr_shape<BITS, BLOCK, EPI, DrFewWorkersShape>(grid, s, a, epi);
-            return;
+loco_status_t launch_dr(int how, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
+    if constexpr (EPI == Epilogue::kStore) {   // the other decompositions: plain fp32 output, fp32 steps
+        if (how != kDrQuad && a.scales_bf16) return LOCO_ERR_UNSUPPORTED;
+        if (how == kDrQuadLaneSteps) {
+            if constexpr (BLOCK >= 128) {
+                if (dr_few_workers(BITS, a.W)) return launch_dr_quad<BITS, BLOCK, EPI, DrFewWorkersShape, float, true>(s, a, epi);
+                return launch_dr_quad<BITS, BLOCK, EPI, DrShape<BITS>, float, true>(s, a, epi);
+            }
+            return LOCO_ERR_UNSUPPORTED;
+        }
+        if (how == kDrWide4) {
+            if constexpr (BITS == 4) return launch_dr_wide<BITS, BLOCK, 4>(s, a, epi);
+            return LOCO_ERR_UNSUPPORTED;
+        }
+        if (how == kDrWide8) return launch_dr_wide<BITS, BLOCK, 8>(s, a, epi);
+        if (how == kDrWide16) return launch_dr_wide<BITS, BLOCK, 16>(s, a, epi);
+        if (a.scales_bf16) {
+            if (dr_few_workers(BITS, a.W)) return launch_dr_quad<BITS, BLOCK, EPI, DrFewWorkersShape, uint16_t, false>(s, a, epi);
+            return launch_dr_quad<BITS, BLOCK, EPI, DrShape<BITS>, uint16_t, false>(s, a, epi);
         }
     }
-    launch_dr_shape<BITS, BLOCK, EPI, DrShapeFor<BITS, EPI>>(grid, s, a, epi);
+    if (how != kDrQuad) return LOCO_ERR_UNSUPPORTED;
+    if constexpr (!dr_updates_in_place(EPI)) {
+        if (dr_few_workers(BITS, a.W)) return launch_dr_quad<BITS, BLOCK, EPI, DrFewWorkersShape, float, false>(s, a, epi);
+    }
+    return launch_dr_quad<BITS, BLOCK, EPI, DrShapeFor<BITS, EPI>, float, false>(s, a, epi);
 }
 
 template <int BITS, Epilogue EPI>
-bool dispatch_dr_block(int block, unsigned grid, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
+loco_status_t dispatch_dr_block(int block, int how, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
     switch (block) {
-        case 32: launch_dr<BITS, 32, EPI>(grid, s, a, epi); return true;
-        case 64: launch_dr<BITS, 64, EPI>(grid, s, a, epi); return true;
-        case 128: launch_dr<BITS, 128, EPI>(grid, s, a, epi); return true;
-        case 256: launch_dr<BITS, 256, EPI>(grid, s, a, epi); return true;
-        case 512: launch_dr<BITS, 512, EPI>(grid, s, a, epi); return true;
-        default: return false;
+        case 32: return launch_dr<BITS, 32, EPI>(how, s, a, epi);
+        case 64: return launch_dr<BITS, 64, EPI>(how, s, a, epi);
+        case 128: return launch_dr<BITS, 128, EPI>(how, s, a, epi);
+        case 256: return launch_dr<BITS, 256, EPI>(how, s, a, epi);
+        case 512: return launch_dr<BITS, 512, EPI>(how, s, a, epi);
+        default: return LOCO_ERR_UNSUPPORTED;
     }
 }
 
 template <Epilogue EPI>
-bool dispatch_dr(int bits, int block, unsigned grid, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
-    return bits == 4 ? dispatch_dr_block<4, EPI>(block, grid, s, a, epi)
-                     : dispatch_dr_block<8, EPI>(block, grid, s, a, epi);
+loco_status_t dispatch_dr(int bits, int block, int how, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
+    return bits == 4 ? dispatch_dr_block<4, EPI>(block, how, s, a, epi) : dispatch_dr_block<8, EPI>(block, how, s, a, epi);
 }
 
 // Checks the buffers an epilogue touches (16-byte aligned fp32 arrays of n elements, inside
@@ -241,36 +300,44 @@ bool fixed_args_ok(int bits, int log2_s, int se_mult) {
     return (bits == 4 || bits == 8) && log2_s >= -64 && log2_s <= 64 && se_mult >= 1 && se_mult <= 64;
 }
 
+struct FixedCqArgs {
+    const void* grad;
+    int8_t* err8;
+    size_t n;
+    FixedScales k;
+    int reset;
+    const long long* step_index;   // device; nullptr: `reset` decides
+    long long reset_period;
+    float clip;
+    uint8_t* codes;
+};
+
 template <typename G, int BITS, bool POW2>
-void launch_fixed_cq(unsigned grid, hipStream_t s, const void* grad, int8_t* err8, size_t n,
-                     const FixedScales& k, int reset, float clip, uint8_t* codes) {
-    if (std::isinf(clip))
-        fixed_cq_kernel<G, BITS, POW2, FixedCqShape::kUnits, FixedCqShape::kThreads, kNonTemporal, false>
-            <<<dim3(grid), dim3(FixedCqShape::kThreads), 0, s>>>(grad, err8, n, k, reset, clip, codes);
-    else
-        fixed_cq_kernel<G, BITS, POW2, FixedCqShape::kUnits, FixedCqShape::kThreads, kNonTemporal, true>
-            <<<dim3(grid), dim3(FixedCqShape::kThreads), 0, s>>>(grad, err8, n, k, reset, clip, codes);
+loco_status_t launch_fixed_cq(unsigned grid, hipStream_t s, const FixedCqArgs& a) {
+    if (std::isinf(a.clip))
+        return launch(fixed_cq_kernel<G, BITS, POW2, FixedCqShape::kUnits, FixedCqShape::kThreads, kNonTemporal, false>,
+                      grid, FixedCqShape::kThreads, s, a.grad, a.err8, a.n, a.k, a.reset, a.step_index, a.reset_period,
+                      a.clip, a.codes);
+    return launch(fixed_cq_kernel<G, BITS, POW2, FixedCqShape::kUnits, FixedCqShape::kThreads, kNonTemporal, true>,
+                  grid, FixedCqShape::kThreads, s, a.grad, a.err8, a.n, a.k, a.reset, a.step_index, a.reset_period,
+                  a.clip, a.codes);
 }
 
 template <typename G>
-void dispatch_fixed_cq(int bits, bool pow2, unsigned grid, hipStream_t s, const void* grad, int8_t* err8,
-                       size_t n, const FixedScales& k, int reset, float clip, uint8_t* codes) {
-    if (bits == 4) {
-        if (pow2) launch_fixed_cq<G, 4, true>(grid, s, grad, err8, n, k, reset, clip, codes);
-        else launch_fixed_cq<G, 4, false>(grid, s, grad, err8, n, k, reset, clip, codes);
-    } else {
-        if (pow2) launch_fixed_cq<G, 8, true>(grid, s, grad, err8, n, k, reset, clip, codes);
-        else launch_fixed_cq<G, 8, false>(grid, s, grad, err8, n, k, reset, clip, codes);
-    }
+loco_status_t dispatch_fixed_cq(int bits, bool pow2, unsigned grid, hipStream_t s, const FixedCqArgs& a) {
+    if (bits == 4) return pow2 ? launch_fixed_cq<G, 4, true>(grid, s, a) : launch_fixed_cq<G, 4, false>(grid, s, a);
+    return pow2 ? launch_fixed_cq<G, 8, true>(grid, s, a) : launch_fixed_cq<G, 8, false>(grid, s, a);
 }
 
 loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const void* scales,
                            size_t scale_stride_elems, int num_workers, size_t n, int bits, int block_size,
-                           Epilogue kind, const EpilogueArgs& epi, void* stream, bool scales_bf16 = false) {
+                           Epilogue kind, const EpilogueArgs& epi, void* stream, bool scales_bf16 = false,
+                           int decomposition = kDrAuto) {
     if (scales_bf16 && kind != Epilogue::kStore) return LOCO_ERR_UNSUPPORTED;
     const size_t step_bytes = scales_bf16 ? sizeof(uint16_t) : sizeof(float);
     if (bits != 4 && bits != 8) return LOCO_ERR_UNSUPPORTED;
     if (!block_size_ok(block_size)) return LOCO_ERR_UNSUPPORTED;
+    if (decomposition < kDrAuto || decomposition > kDrWide16) return LOCO_ERR_UNSUPPORTED;
     if (num_workers < 1) return LOCO_ERR_INVALID_ARG;
     if (n == 0) return LOCO_OK;
     if (!codes || !scales) return LOCO_ERR_INVALID_ARG;
@@ -288,39 +355,39 @@ loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const
     if (loco_status_t st = check_device_range(scales, ((W - 1) * scale_stride_elems + nb) * step_bytes))
         return st;
     if (loco_status_t st = check_epilogue(kind, epi, n)) return st;
-    unsigned grid;
-    if (loco_status_t st = grid_for(n, dr_elements_per_group(bits, kind, num_workers), &grid,
-                                    kDrXcdRun ? 8 * kDrXcdRun : 1))
-        return st;
+    const int how = decomposition == kDrAuto ? dr_auto_decomposition(bits, block_size, num_workers, kind, scales_bf16)
+                                             : decomposition;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const DrArgs a{codes, code_stride_bytes, scales, scales_bf16, scale_stride_elems, num_workers, n};
-    bool ok = false;
     switch (kind) {
-        case Epilogue::kStore: ok = dispatch_dr<Epilogue::kStore>(bits, block_size, grid, s, a, epi); break;
-        case Epilogue::kStoreBf16: ok = dispatch_dr<Epilogue::kStoreBf16>(bits, block_size, grid, s, a, epi); break;
-        case Epilogue::kSgd: ok = dispatch_dr<Epilogue::kSgd>(bits, block_size, grid, s, a, epi); break;
-        case Epilogue::kAdam: ok = dispatch_dr<Epilogue::kAdam>(bits, block_size, grid, s, a, epi); break;
+        case Epilogue::kStore: return dispatch_dr<Epilogue::kStore>(bits, block_size, how, s, a, epi);
+        case Epilogue::kStoreBf16: return dispatch_dr<Epilogue::kStoreBf16>(bits, block_size, how, s, a, epi);
+        case Epilogue::kSgd: return dispatch_dr<Epilogue::kSgd>(bits, block_size, how, s, a, epi);
+        case Epilogue::kAdam: return dispatch_dr<Epilogue::kAdam>(bits, block_size, how, s, a, epi);
     }
-    if (!ok) return LOCO_ERR_UNSUPPORTED;
-    return launched();
+    return LOCO_ERR_UNSUPPORTED;
 }
 
 template <Epilogue EPI>
-void launch_fixed_dr(int bits, unsigned grid, hipStream_t s, const uint8_t* codes, size_t cs, int W,
-                            size_t n, float inv_s, float inv_w, const EpilogueArgs& epi) {
+loco_status_t launch_fixed_dr(int bits, unsigned grid, hipStream_t s, const uint8_t* codes, size_t cs, int W,
+                              size_t n, float inv_s, float inv_w, const EpilogueArgs& epi) {
     using Shape = FixedDrShapeFor<EPI>;
     if (bits == 4)
-        fixed_dr_kernel<4, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI>
-            <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(codes, cs, W, n, inv_s, inv_w, epi);
-    else
-        fixed_dr_kernel<8, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI>
-            <<<dim3(grid), dim3(Shape::kThreads), 0, s>>>(codes, cs, W, n, inv_s, inv_w, epi);
+        return launch(fixed_dr_kernel<4, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI>, grid,
+                      Shape::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
+    return launch(fixed_dr_kernel<8, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI>, grid,
+                  Shape::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
 }
 
+// The reduce kernel sums the integer codes and converts once; every partial sum must stay
+// below 2^24 in magnitude for that to equal the sequential binary32 sum of Eq. 8.
+constexpr int kFixedMaxWorkers4 = (1 << 24) / 8, kFixedMaxWorkers8 = (1 << 24) / 128;
+
 loco_status_t reduce_fixed(const uint8_t* codes, size_t code_stride_bytes, int num_workers, size_t n,
-                                  int bits, int log2_s, Epilogue kind, const EpilogueArgs& epi, void* stream) {
+                           int bits, int log2_s, Epilogue kind, const EpilogueArgs& epi, void* stream) {
     if (!fixed_args_ok(bits, log2_s, 1)) return LOCO_ERR_UNSUPPORTED;
     if (num_workers < 1) return LOCO_ERR_INVALID_ARG;
+    if (num_workers > (bits == 4 ? kFixedMaxWorkers4 : kFixedMaxWorkers8)) return LOCO_ERR_UNSUPPORTED;
     if (n == 0) return LOCO_OK;
     if (!codes) return LOCO_ERR_INVALID_ARG;
     const size_t cb = loco_code_bytes(n, bits);
@@ -342,16 +409,25 @@ loco_status_t reduce_fixed(const uint8_t* codes, size_t code_stride_bytes, int n
     const float inv_s = std::ldexp(1.0f, -log2_s), inv_w = 1.0f / (float)num_workers;
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (kind) {
-        case Epilogue::kStore: launch_fixed_dr<Epilogue::kStore>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi); break;
-        case Epilogue::kStoreBf16: launch_fixed_dr<Epilogue::kStoreBf16>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi); break;
-        case Epilogue::kSgd: launch_fixed_dr<Epilogue::kSgd>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi); break;
-        case Epilogue::kAdam: launch_fixed_dr<Epilogue::kAdam>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi); break;
+        case Epilogue::kStore: return launch_fixed_dr<Epilogue::kStore>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi);
+        case Epilogue::kStoreBf16: return launch_fixed_dr<Epilogue::kStoreBf16>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi);
+        case Epilogue::kSgd: return launch_fixed_dr<Epilogue::kSgd>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi);
+        case Epilogue::kAdam: return launch_fixed_dr<Epilogue::kAdam>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi);
     }
-    return launched();
+    return LOCO_ERR_UNSUPPORTED;
+}
+
+// The step counter of the scheduled calls: 8-byte aligned device memory holding one int64.
+loco_status_t check_step_index(const int64_t* step_index_dev, int64_t reset_period) {
+    if (!step_index_dev) return LOCO_ERR_INVALID_ARG;
+    if (reset_period < 0) return LOCO_ERR_INVALID_ARG;
+    if (!aligned(step_index_dev, 8)) return LOCO_ERR_ALIGNMENT;
+    return check_device_range(step_index_dev, sizeof(int64_t));
 }
 
 loco_status_t compress_block(const void* grad, loco_dtype_t grad_dtype, float clip_abs, float* err_state,
-                             size_t n, int bits, int block_size, float beta, int reset, uint8_t* codes_out,
+                             size_t n, int bits, int block_size, float beta, int reset,
+                             const int64_t* step_index_dev, int64_t reset_period, uint8_t* codes_out,
                              void* scales_out, bool scales_bf16, void* stream) {
     const size_t step_bytes = scales_bf16 ? sizeof(uint16_t) : sizeof(float);
     if (bits != 4 && bits != 8) return LOCO_ERR_UNSUPPORTED;
@@ -374,17 +450,75 @@ loco_status_t compress_block(const void* grad, loco_dtype_t grad_dtype, float cl
                                        : (size_t)kSlot * CqShape<8>::kSlots * (CqShape<8>::kThreads / kWave);
     if (loco_status_t st = grid_for(n, per_group, &grid, kCqXcdRun ? 8 * kCqXcdRun : 1)) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const CqArgs a{grad, err_state, n, beta, reset, clip_abs, codes_out, scales_out, scales_bf16};
-    bool ok;
+    const CqArgs a{grad, err_state, n, beta, reset, reinterpret_cast<const long long*>(step_index_dev),
+                   (long long)reset_period, clip_abs, codes_out, scales_out, scales_bf16};
+    if (grad_dtype == LOCO_BF16)
+        return bits == 4 ? dispatch_cq_block<bf16_t, 4>(block_size, grid, s, a) : dispatch_cq_block<bf16_t, 8>(block_size, grid, s, a);
+    return bits == 4 ? dispatch_cq_block<float, 4>(block_size, grid, s, a) : dispatch_cq_block<float, 8>(block_size, grid, s, a);
+}
+
+loco_status_t compress_fixed(const void* grad, loco_dtype_t grad_dtype, float clip_abs, int8_t* err_state8, size_t n,
+                             int bits, int log2_s, int se_mult, float beta, int reset,
+                             const int64_t* step_index_dev, int64_t reset_period, uint8_t* codes_out, void* stream) {
+    if (!fixed_args_ok(bits, log2_s, se_mult)) return LOCO_ERR_UNSUPPORTED;
+    if (!(clip_abs > 0.0f)) return LOCO_ERR_INVALID_ARG;
+    if (grad_dtype != LOCO_F32 && grad_dtype != LOCO_BF16) return LOCO_ERR_UNSUPPORTED;
+    if (!(beta >= 0.0f && beta <= 1.0f)) return LOCO_ERR_INVALID_ARG;
+    if (n == 0) return LOCO_OK;
+    if (!grad || !err_state8 || !codes_out) return LOCO_ERR_INVALID_ARG;
+    if (!aligned(grad, 16) || !aligned(err_state8, 16) || !aligned(codes_out, 16)) return LOCO_ERR_ALIGNMENT;
+    const size_t gsz = grad_dtype == LOCO_BF16 ? 2 : 4;
+    if (loco_status_t st = check_device_range(grad, n * gsz)) return st;
+    if (loco_status_t st = check_device_range(err_state8, n)) return st;
+    if (loco_status_t st = check_device_range(codes_out, loco_code_bytes(n, bits))) return st;
+    unsigned grid;
+    if (loco_status_t st = grid_for(n, (size_t)kUnit * FixedCqShape::kUnits * (FixedCqShape::kThreads / kWave), &grid))
+        return st;
+    FixedScales k;
+    k.s = std::ldexp(1.0f, log2_s);
+    k.inv_s = std::ldexp(1.0f, -log2_s);
+    k.s_e = (float)se_mult * k.s;
+    k.inv_se = 1.0f / k.s_e;
+    k.beta = beta;
+    k.one_minus_beta = 1.0f - beta;
+    const bool pow2 = (se_mult & (se_mult - 1)) == 0;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const FixedCqArgs a{grad, err_state8, n, k, reset, reinterpret_cast<const long long*>(step_index_dev),
+                        (long long)reset_period, clip_abs, codes_out};
+    return grad_dtype == LOCO_BF16 ? dispatch_fixed_cq<bf16_t>(bits, pow2, grid, s, a)
+                                   : dispatch_fixed_cq<float>(bits, pow2, grid, s, a);
+}
+
+loco_status_t compress_fixed_f32state(const void* grad, loco_dtype_t grad_dtype, float* err_state, size_t n, int bits,
+                                      int log2_s, float beta, int reset, const int64_t* step_index_dev,
+                                      int64_t reset_period, uint8_t* codes_out, void* stream) {
+    if (!fixed_args_ok(bits, log2_s, 1)) return LOCO_ERR_UNSUPPORTED;
+    if (grad_dtype != LOCO_F32 && grad_dtype != LOCO_BF16) return LOCO_ERR_UNSUPPORTED;
+    if (!(beta >= 0.0f && beta <= 1.0f)) return LOCO_ERR_INVALID_ARG;
+    if (n == 0) return LOCO_OK;
+    if (!grad || !err_state || !codes_out) return LOCO_ERR_INVALID_ARG;
+    if (!aligned(grad, 16) || !aligned(err_state, 16) || !aligned(codes_out, 16)) return LOCO_ERR_ALIGNMENT;
+    const size_t gsz = grad_dtype == LOCO_BF16 ? 2 : 4;
+    if (loco_status_t st = check_device_range(grad, n * gsz)) return st;
+    if (loco_status_t st = check_device_range(err_state, n * sizeof(float))) return st;
+    if (loco_status_t st = check_device_range(codes_out, loco_code_bytes(n, bits))) return st;
+    using Shape = FixedF32CqShape;
+    unsigned grid;
+    if (loco_status_t st = grid_for(n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid)) return st;
+    FixedScales k{};
+    k.s = std::ldexp(1.0f, log2_s);
+    k.inv_s = std::ldexp(1.0f, -log2_s);
+    k.beta = beta;
+    k.one_minus_beta = 1.0f - beta;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const long long* si = reinterpret_cast<const long long*>(step_index_dev);
+    const long long period = (long long)reset_period;
     if (grad_dtype == LOCO_BF16) {
-        ok = bits == 4 ? dispatch_cq_block<bf16_t, 4>(block_size, grid, s, a)
-                       : dispatch_cq_block<bf16_t, 8>(block_size, grid, s, a);
-    } else {
-        ok = bits == 4 ? dispatch_cq_block<float, 4>(block_size, grid, s, a)
-                       : dispatch_cq_block<float, 8>(block_size, grid, s, a);
+        if (bits == 4) return launch(fixed_f32_cq_kernel<bf16_t, 4, Shape::kSlots, Shape::kThreads, kNonTemporal>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
+        return launch(fixed_f32_cq_kernel<bf16_t, 8, Shape::kSlots, Shape::kThreads, kNonTemporal>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
     }
-    if (!ok) return LOCO_ERR_UNSUPPORTED;
-    return launched();
+    if (bits == 4) return launch(fixed_f32_cq_kernel<float, 4, Shape::kSlots, Shape::kThreads, kNonTemporal>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
+    return launch(fixed_f32_cq_kernel<float, 8, Shape::kSlots, Shape::kThreads, kNonTemporal>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
 }
 
 template <StreamMode MODE, typename Shape>
@@ -392,11 +526,9 @@ loco_status_t launch_stream(void* dst, const void* src, const void* src2, size_t
     const size_t n16 = bytes / 16;
     unsigned grid;
     if (loco_status_t st = grid_for(n16, (size_t)Shape::kThreads * Shape::kSlots, &grid)) return st;
-    stream_kernel<MODE, Shape::kSlots, Shape::kThreads, kNonTemporal>
-        <<<dim3(grid), dim3(Shape::kThreads), 0, static_cast<hipStream_t>(stream)>>>(
-            static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), static_cast<const u32x4*>(src2), n16,
-            0x9E3779B9u);
-    return launched();
+    return launch(stream_kernel<MODE, Shape::kSlots, Shape::kThreads, kNonTemporal>, grid, Shape::kThreads,
+                  static_cast<hipStream_t>(stream), static_cast<u32x4*>(dst), static_cast<const u32x4*>(src),
+                  static_cast<const u32x4*>(src2), n16, 0x9E3779B9u);
 }
 
 }  // namespace
@@ -407,7 +539,7 @@ const char* loco_status_string(loco_status_t status) {
     switch (status) {
         case LOCO_OK: return "ok";
         case LOCO_ERR_INVALID_ARG: return "invalid argument";
-        case LOCO_ERR_UNSUPPORTED: return "unsupported bits, block size, dtype or size";
+        case LOCO_ERR_UNSUPPORTED: return "unsupported bits, block size, dtype, size, worker count or decomposition";
         case LOCO_ERR_ALIGNMENT: return "pointer or stride not aligned as required";
         case LOCO_ERR_LAUNCH: return "kernel launch failed";
         case LOCO_ERR_BAD_POINTER: return "buffer is not device memory or is too small";
@@ -435,30 +567,39 @@ loco_status_t loco_error_state_init(float* err_state, size_t n, void* stream) {
     if (loco_status_t st = check_device_range(err_state, n * sizeof(float))) return st;
     unsigned grid;
     if (loco_status_t st = grid_for(n, (size_t)FillShape::kThreads * 4 * FillShape::kSlots, &grid)) return st;
-    fill_zero_kernel<FillShape::kSlots, FillShape::kThreads, kNonTemporal>
-        <<<dim3(grid), dim3(FillShape::kThreads), 0, static_cast<hipStream_t>(stream)>>>(err_state, n);
-    return launched();
+    return launch(fill_zero_kernel<FillShape::kSlots, FillShape::kThreads, kNonTemporal>, grid, FillShape::kThreads,
+                  static_cast<hipStream_t>(stream), err_state, n);
 }
 
 loco_status_t loco_compensate_quantize_clip(const void* grad, loco_dtype_t grad_dtype, float clip_abs,
                                             float* err_state, size_t n, int bits, int block_size, float beta,
                                             int reset, uint8_t* codes_out, float* scales_out, void* stream) {
-    return compress_block(grad, grad_dtype, clip_abs, err_state, n, bits, block_size, beta, reset, codes_out,
-                          scales_out, false, stream);
+    return compress_block(grad, grad_dtype, clip_abs, err_state, n, bits, block_size, beta, reset, nullptr, 0,
+                          codes_out, scales_out, false, stream);
 }
 
 loco_status_t loco_compensate_quantize(const void* grad, loco_dtype_t grad_dtype, float* err_state,
                                        size_t n, int bits, int block_size, float beta, int reset,
                                        uint8_t* codes_out, float* scales_out, void* stream) {
-    return compress_block(grad, grad_dtype, INFINITY, err_state, n, bits, block_size, beta, reset, codes_out,
-                          scales_out, false, stream);
+    return compress_block(grad, grad_dtype, INFINITY, err_state, n, bits, block_size, beta, reset, nullptr, 0,
+                          codes_out, scales_out, false, stream);
+}
+
+loco_status_t loco_compensate_quantize_scheduled(const void* grad, loco_dtype_t grad_dtype, float* err_state,
+                                                 size_t n, int bits, int block_size, float beta,
+                                                 const int64_t* step_index_dev, int64_t reset_period,
+                                                 uint8_t* codes_out, float* scales_out, void* stream) {
+    if (n != 0)
+        if (loco_status_t st = check_step_index(step_index_dev, reset_period)) return st;
+    return compress_block(grad, grad_dtype, INFINITY, err_state, n, bits, block_size, beta, 0, step_index_dev,
+                          reset_period, codes_out, scales_out, false, stream);
 }
 
 loco_status_t loco_compensate_quantize_bf16_scales(const void* grad, loco_dtype_t grad_dtype, float* err_state,
                                                    size_t n, int bits, int block_size, float beta, int reset,
                                                    uint8_t* codes_out, uint16_t* scales_out_bf16, void* stream) {
-    return compress_block(grad, grad_dtype, INFINITY, err_state, n, bits, block_size, beta, reset, codes_out,
-                          scales_out_bf16, true, stream);
+    return compress_block(grad, grad_dtype, INFINITY, err_state, n, bits, block_size, beta, reset, nullptr, 0,
+                          codes_out, scales_out_bf16, true, stream);
 }
 
 loco_status_t loco_dequant_reduce_bf16_scales(const uint8_t* codes, size_t code_stride_bytes,
@@ -475,6 +616,19 @@ loco_status_t loco_dequant_reduce(const uint8_t* codes, size_t code_stride_bytes
                                   int block_size, float* grad_out, void* stream) {
     return reduce_block(codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n, bits, block_size,
                         Epilogue::kStore, make_epilogue(grad_out, nullptr, nullptr, nullptr, 0, 0, 0, 0), stream);
+}
+
+loco_status_t loco_dequant_reduce_decomposed(const uint8_t* codes, size_t code_stride_bytes, const float* scales,
+                                             size_t scale_stride_elems, int num_workers, size_t n, int bits,
+                                             int block_size, float* grad_out, int decomposition, void* stream) {
+    return reduce_block(codes, code_stride_bytes, scales, scale_stride_elems, num_workers, n, bits, block_size,
+                        Epilogue::kStore, make_epilogue(grad_out, nullptr, nullptr, nullptr, 0, 0, 0, 0), stream,
+                        false, decomposition);
+}
+
+int loco_dequant_reduce_decomposition(int num_workers, int bits, int block_size) {
+    if ((bits != 4 && bits != 8) || !block_size_ok(block_size) || num_workers < 1) return -1;
+    return dr_auto_decomposition(bits, block_size, num_workers, Epilogue::kStore, false);
 }
 
 loco_status_t loco_dequant_reduce_bf16(const uint8_t* codes, size_t code_stride_bytes, const float* scales,
@@ -508,6 +662,17 @@ loco_status_t loco_stream_copy(void* dst, const void* src, size_t bytes, void* s
     if (loco_status_t st = check_device_range(dst, bytes)) return st;
     if (loco_status_t st = check_device_range(src, bytes)) return st;
     return launch_stream<StreamMode::kCopy, CopyShape>(dst, src, nullptr, bytes, stream);
+}
+
+loco_status_t loco_runtime_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (bytes == 0) return LOCO_OK;
+    if (!dst || !src) return LOCO_ERR_INVALID_ARG;
+    if (loco_status_t st = check_device_range(dst, bytes)) return st;
+    if (loco_status_t st = check_device_range(src, bytes)) return st;
+    const hipError_t e = hipMemcpyDtoDAsync(reinterpret_cast<hipDeviceptr_t>(dst),
+                                            reinterpret_cast<hipDeviceptr_t>(const_cast<void*>(src)), bytes,
+                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LOCO_OK : LOCO_ERR_LAUNCH;
 }
 
 loco_status_t loco_stream_read(const void* src, size_t bytes, void* sink16, void* stream) {
@@ -558,6 +723,18 @@ int loco_reset_due(long long step_index, long long reset_period) {
     return reset_period > 0 && step_index % reset_period == 0;
 }
 
+loco_status_t loco_step_index_set(int64_t* step_index_dev, int64_t value, void* stream) {
+    if (loco_status_t st = check_step_index(step_index_dev, 0)) return st;
+    return launch(step_index_kernel, 1, kWave, static_cast<hipStream_t>(stream),
+                  reinterpret_cast<long long*>(step_index_dev), (long long)value, 0);
+}
+
+loco_status_t loco_step_index_advance(int64_t* step_index_dev, void* stream) {
+    if (loco_status_t st = check_step_index(step_index_dev, 0)) return st;
+    return launch(step_index_kernel, 1, kWave, static_cast<hipStream_t>(stream),
+                  reinterpret_cast<long long*>(step_index_dev), 1LL, 1);
+}
+
 loco_status_t loco_error_state8_init(int8_t* err_state8, size_t n, void* stream) {
     if (n == 0) return LOCO_OK;
     if (!err_state8) return LOCO_ERR_INVALID_ARG;
@@ -565,82 +742,51 @@ loco_status_t loco_error_state8_init(int8_t* err_state8, size_t n, void* stream)
     if (loco_status_t st = check_device_range(err_state8, n)) return st;
     unsigned grid;
     if (loco_status_t st = grid_for(n, (size_t)FillShape::kThreads * 16 * FillShape::kSlots, &grid)) return st;
-    fill_zero_bytes_kernel<FillShape::kSlots, FillShape::kThreads, kNonTemporal>
-        <<<dim3(grid), dim3(FillShape::kThreads), 0, static_cast<hipStream_t>(stream)>>>(
-            reinterpret_cast<uint8_t*>(err_state8), n);
-    return launched();
+    return launch(fill_zero_bytes_kernel<FillShape::kSlots, FillShape::kThreads, kNonTemporal>, grid, FillShape::kThreads,
+                  static_cast<hipStream_t>(stream), reinterpret_cast<uint8_t*>(err_state8), n);
 }
 
 loco_status_t loco_compensate_quantize_fixed(const void* grad, loco_dtype_t grad_dtype, int8_t* err_state8,
                                              size_t n, int bits, int log2_s, int se_mult, float beta,
                                              int reset, uint8_t* codes_out, void* stream) {
-    return loco_compensate_quantize_fixed_clip(grad, grad_dtype, INFINITY, err_state8, n, bits, log2_s, se_mult,
-                                               beta, reset, codes_out, stream);
+    return compress_fixed(grad, grad_dtype, INFINITY, err_state8, n, bits, log2_s, se_mult, beta, reset, nullptr, 0,
+                          codes_out, stream);
 }
 
 loco_status_t loco_compensate_quantize_fixed_clip(const void* grad, loco_dtype_t grad_dtype, float clip_abs,
                                                   int8_t* err_state8, size_t n, int bits, int log2_s,
                                                   int se_mult, float beta, int reset, uint8_t* codes_out,
                                                   void* stream) {
-    if (!fixed_args_ok(bits, log2_s, se_mult)) return LOCO_ERR_UNSUPPORTED;
-    if (!(clip_abs > 0.0f)) return LOCO_ERR_INVALID_ARG;
-    if (grad_dtype != LOCO_F32 && grad_dtype != LOCO_BF16) return LOCO_ERR_UNSUPPORTED;
-    if (!(beta >= 0.0f && beta <= 1.0f)) return LOCO_ERR_INVALID_ARG;
-    if (n == 0) return LOCO_OK;
-    if (!grad || !err_state8 || !codes_out) return LOCO_ERR_INVALID_ARG;
-    if (!aligned(grad, 16) || !aligned(err_state8, 16) || !aligned(codes_out, 16)) return LOCO_ERR_ALIGNMENT;
-    const size_t gsz = grad_dtype == LOCO_BF16 ? 2 : 4;
-    if (loco_status_t st = check_device_range(grad, n * gsz)) return st;
-    if (loco_status_t st = check_device_range(err_state8, n)) return st;
-    if (loco_status_t st = check_device_range(codes_out, loco_code_bytes(n, bits))) return st;
-    unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kUnit * FixedCqShape::kUnits * (FixedCqShape::kThreads / kWave), &grid))
-        return st;
-    FixedScales k;
-    k.s = std::ldexp(1.0f, log2_s);
-    k.inv_s = std::ldexp(1.0f, -log2_s);
-    k.s_e = (float)se_mult * k.s;
-    k.inv_se = 1.0f / k.s_e;
-    k.beta = beta;
-    k.one_minus_beta = 1.0f - beta;
-    const bool pow2 = (se_mult & (se_mult - 1)) == 0;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (grad_dtype == LOCO_BF16) dispatch_fixed_cq<bf16_t>(bits, pow2, grid, s, grad, err_state8, n, k, reset, clip_abs, codes_out);
-    else dispatch_fixed_cq<float>(bits, pow2, grid, s, grad, err_state8, n, k, reset, clip_abs, codes_out);
-    return launched();
+    return compress_fixed(grad, grad_dtype, clip_abs, err_state8, n, bits, log2_s, se_mult, beta, reset, nullptr, 0,
+                          codes_out, stream);
+}
+
+loco_status_t loco_compensate_quantize_fixed_scheduled(const void* grad, loco_dtype_t grad_dtype, int8_t* err_state8,
+                                                       size_t n, int bits, int log2_s, int se_mult, float beta,
+                                                       const int64_t* step_index_dev, int64_t reset_period,
+                                                       uint8_t* codes_out, void* stream) {
+    if (n != 0)
+        if (loco_status_t st = check_step_index(step_index_dev, reset_period)) return st;
+    return compress_fixed(grad, grad_dtype, INFINITY, err_state8, n, bits, log2_s, se_mult, beta, 0, step_index_dev,
+                          reset_period, codes_out, stream);
 }
 
 loco_status_t loco_compensate_quantize_fixed_f32state(const void* grad, loco_dtype_t grad_dtype, float* err_state,
                                                       size_t n, int bits, int log2_s, float beta, int reset,
                                                       uint8_t* codes_out, void* stream) {
-    if (!fixed_args_ok(bits, log2_s, 1)) return LOCO_ERR_UNSUPPORTED;
-    if (grad_dtype != LOCO_F32 && grad_dtype != LOCO_BF16) return LOCO_ERR_UNSUPPORTED;
-    if (!(beta >= 0.0f && beta <= 1.0f)) return LOCO_ERR_INVALID_ARG;
-    if (n == 0) return LOCO_OK;
-    if (!grad || !err_state || !codes_out) return LOCO_ERR_INVALID_ARG;
-    if (!aligned(grad, 16) || !aligned(err_state, 16) || !aligned(codes_out, 16)) return LOCO_ERR_ALIGNMENT;
-    const size_t gsz = grad_dtype == LOCO_BF16 ? 2 : 4;
-    if (loco_status_t st = check_device_range(grad, n * gsz)) return st;
-    if (loco_status_t st = check_device_range(err_state, n * sizeof(float))) return st;
-    if (loco_status_t st = check_device_range(codes_out, loco_code_bytes(n, bits))) return st;
-    using Shape = FixedF32CqShape;
-    unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid)) return st;
-    FixedScales k{};
-    k.s = std::ldexp(1.0f, log2_s);
-    k.inv_s = std::ldexp(1.0f, -log2_s);
-    k.beta = beta;
-    k.one_minus_beta = 1.0f - beta;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 g(grid), b(Shape::kThreads);
-    if (grad_dtype == LOCO_BF16) {
-        if (bits == 4) fixed_f32_cq_kernel<bf16_t, 4, Shape::kSlots, Shape::kThreads, kNonTemporal><<<g, b, 0, s>>>(grad, err_state, n, k, reset, codes_out);
-        else fixed_f32_cq_kernel<bf16_t, 8, Shape::kSlots, Shape::kThreads, kNonTemporal><<<g, b, 0, s>>>(grad, err_state, n, k, reset, codes_out);
-    } else {
-        if (bits == 4) fixed_f32_cq_kernel<float, 4, Shape::kSlots, Shape::kThreads, kNonTemporal><<<g, b, 0, s>>>(grad, err_state, n, k, reset, codes_out);
-        else fixed_f32_cq_kernel<float, 8, Shape::kSlots, Shape::kThreads, kNonTemporal><<<g, b, 0, s>>>(grad, err_state, n, k, reset, codes_out);
-    }
-    return launched();
+    return compress_fixed_f32state(grad, grad_dtype, err_state, n, bits, log2_s, beta, reset, nullptr, 0, codes_out,
+                                   stream);
+}
+
+loco_status_t loco_compensate_quantize_fixed_f32state_scheduled(const void* grad, loco_dtype_t grad_dtype,
+                                                                float* err_state, size_t n, int bits, int log2_s,
+                                                                float beta, const int64_t* step_index_dev,
+                                                                int64_t reset_period, uint8_t* codes_out,
+                                                                void* stream) {
+    if (n != 0)
+        if (loco_status_t st = check_step_index(step_index_dev, reset_period)) return st;
+    return compress_fixed_f32state(grad, grad_dtype, err_state, n, bits, log2_s, beta, 0, step_index_dev, reset_period,
+                                   codes_out, stream);
 }
 
 loco_status_t loco_dequant_reduce_fixed(const uint8_t* codes, size_t code_stride_bytes, int num_workers,

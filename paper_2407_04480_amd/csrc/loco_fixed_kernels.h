@@ -100,12 +100,13 @@ __device__ __forceinline__ void fixed_cq_octet(const float (&g)[8], const uint32
 template <typename G, int BITS, bool POW2, int UNITS, int THREADS, bool NT, bool CLIP>
 __global__ void __launch_bounds__(THREADS)
 fixed_cq_kernel(const void* __restrict__ grad, int8_t* __restrict__ err8, size_t n, FixedScales k,
-                int reset, float clip, uint8_t* __restrict__ codes) {
+                int reset, const long long* __restrict__ step_index, long long reset_period, float clip,
+                uint8_t* __restrict__ codes) {
     constexpr size_t TILE = (size_t)kUnit * UNITS;
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const size_t tile0 = wave_tile_index<THREADS, 0>() * TILE;
-    const bool rst = reset != 0;
     if (tile0 >= n) return;
+    const bool rst = step_index ? reset_step_due(step_index, reset_period) : reset != 0;   // Eq. 7
 
     if (tile0 + TILE <= n) {
         float g[UNITS][8];
@@ -185,12 +186,13 @@ __device__ __forceinline__ uint32_t fixed_f32_quad(const float (&h)[4], float (&
 template <typename G, int BITS, int SLOTS, int THREADS, bool NT>
 __global__ void __launch_bounds__(THREADS)
 fixed_f32_cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, FixedScales k, int reset,
+                    const long long* __restrict__ step_index, long long reset_period,
                     uint8_t* __restrict__ codes) {
     constexpr size_t TILE = (size_t)kSlot * SLOTS;
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const size_t tile0 = wave_tile_index<THREADS, 0>() * TILE;
-    const bool rst = reset != 0;
     if (tile0 >= n) return;
+    const bool rst = step_index ? reset_step_due(step_index, reset_period) : reset != 0;   // Eq. 7
 
     if (tile0 + TILE <= n) {
         float h[SLOTS][4], e[SLOTS][4];

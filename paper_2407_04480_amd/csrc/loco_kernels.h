@@ -56,6 +56,18 @@ __device__ __forceinline__ float clip_grad(float g, float c) {
     else return g;
 }
 
+// Eq. 7 evaluated on the device: step k is a reset step when k % T_c == 0.  k comes from
+// device memory (a plain, wavefront-uniform load), so a step captured into a HIP graph
+// follows the schedule on every replay while another node advances the counter.  The
+// paper's periods (512, 1024; 128 in the ablation) are powers of two and take the mask;
+// any other period takes the 64-bit remainder, once per wavefront.
+__device__ __forceinline__ bool reset_step_due(const long long* step_index, long long period) {
+    if (period <= 0) return false;
+    const long long k = *step_index;
+    if ((period & (period - 1)) == 0) return (k & (period - 1)) == 0;
+    return k % period == 0;
+}
+
 // ---- cross-lane all-reduce (max) over aligned groups of LANES consecutive lanes ----
 // Operands are bit patterns of non-negative floats, which order like unsigned ints.
 template <int CTRL>
@@ -204,22 +216,23 @@ __device__ __forceinline__ void cq_tile(const float (&h)[SLOTS][4], float (&e)[S
 }
 
 // One wavefront per SLOTS*256 elements; THREADS/64 wavefronts per workgroup, each with its
-// own contiguous tile.  grid = ceil(n / (SLOTS*256*THREADS/64)), rounded up to a multiple of 8*XCDK.  A wavefront whose tile
+// own contiguous tile.  step_index == nullptr: `reset` is the caller's flag for this step.  grid = ceil(n / (SLOTS*256*THREADS/64)), rounded up to a multiple of 8*XCDK.  A wavefront whose tile
 // lies inside [0, n) takes the vector path; the last one may take the guarded path, which
 // touches memory element by element and never at or beyond n.
 template <typename G, int BITS, int BLOCK, int SLOTS, int THREADS, bool NT, int XCDK, bool CLIP, typename S>
 __global__ void __launch_bounds__(THREADS)
 cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, float beta,
-          float one_minus_beta, int reset, float clip, uint8_t* __restrict__ codes,
-          S* __restrict__ scales) {
+          float one_minus_beta, int reset, const long long* __restrict__ step_index, long long reset_period,
+          float clip, uint8_t* __restrict__ codes, S* __restrict__ scales) {
     constexpr bool S16 = sizeof(S) == 2;
     constexpr int GROUP = BLOCK >= kSlot ? kWave : BLOCK / kQuad;  // lanes per block within a slot
     constexpr size_t TILE = (size_t)kSlot * SLOTS;
     const int lane = threadIdx.x & (kWave - 1);
     const size_t wave = wave_tile_index<THREADS, XCDK>();
     const size_t tile0 = wave * TILE;
-    const bool rst = reset != 0;
     if (tile0 >= n) return;  // whole wavefront
+    // the caller's flag, or Eq. 7's schedule read from the step counter in device memory
+    const bool rst = step_index ? reset_step_due(step_index, reset_period) : reset != 0;
 
     float h[SLOTS][4], e[SLOTS][4], step[SLOTS];
     uint32_t pk[SLOTS];
@@ -410,18 +423,26 @@ __device__ __forceinline__ void dr_accumulate(uint32_t c, float D, float (&acc)[
         acc[j] = acc[j] + d;            // sum of Eq. 8, in worker order
     }
 }
-// v_cvt_off_f32_i4 of the low nibble of byte 1 of x (an SDWA byte select instead of a shift).
-__device__ __forceinline__ float cvt_off_i4_byte1(uint32_t x) {
+// v_cvt_off_f32_i4 of the low nibble of byte SEL of x (an SDWA byte select instead of a shift).
+template <int SEL>
+__device__ __forceinline__ float cvt_off_i4_byte(uint32_t x) {
+    static_assert(SEL >= 0 && SEL < 4, "byte select");
     float f;
-    asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1" : "=v"(f) : "v"(x));
+    if constexpr (SEL == 0) f = __builtin_amdgcn_cvt_off_f32_i4((int)x);
+    else if constexpr (SEL == 1)
+        asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1" : "=v"(f) : "v"(x));
+    else if constexpr (SEL == 2)
+        asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2" : "=v"(f) : "v"(x));
+    else
+        asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3" : "=v"(f) : "v"(x));
     return f;
 }
 __device__ __forceinline__ void dr_accumulate_nibbles_x16(uint32_t c, float D16, float (&acc)[4]) {
     const uint32_t t = c >> 4;
     const float f0 = __builtin_amdgcn_cvt_off_f32_i4((int)c);   // q0 / 16
     const float f1 = __builtin_amdgcn_cvt_off_f32_i4((int)t);   // q1 / 16
-    const float f2 = cvt_off_i4_byte1(c);                       // q2 / 16
-    const float f3 = cvt_off_i4_byte1(t);                       // q3 / 16
+    const float f2 = cvt_off_i4_byte<1>(c);                       // q2 / 16
+    const float f3 = cvt_off_i4_byte<1>(t);                       // q3 / 16
     acc[0] = acc[0] + f0 * D16;
     acc[1] = acc[1] + f1 * D16;
     acc[2] = acc[2] + f2 * D16;
@@ -440,7 +461,8 @@ constexpr uint32_t kBigStepBits = 0x7B800000u;  // 2^120 as a binary32 bit patte
 // are a wavefront-uniform base (SGPRs, advanced per worker on the scalar unit) plus a
 // 32-bit lane offset; with BLOCK >= 256 a slot lies in one block, so its step is a scalar
 // load shared by the wavefront.
-template <int BITS, int BLOCK, int SLOTS, int THREADS, int WU, bool NT, int XCDK, Epilogue EPI, typename S>
+template <int BITS, int BLOCK, int SLOTS, int THREADS, int WU, bool NT, int XCDK, Epilogue EPI, typename S,
+          bool LANE_STEPS = false>
 __global__ void __launch_bounds__(THREADS)
 dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __restrict__ scales,
           size_t scale_stride, int W, size_t n, float inv_w, EpilogueArgs epi) {
@@ -466,14 +488,30 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __rest
             for (int j = 0; j < 4; ++j) acc[s][j] = 0.0f;
         }
 
+        // LANE_STEPS (blocks of 128 elements and more): the steps of a whole chunk of workers
+        // come in with ONE vector load, lane (u, s, half) fetching the step of worker u, slot s
+        // (and half-slot, when a slot holds two blocks), and are handed to the wavefront with
+        // lane reads.  Through the scalar cache instead, the lines of steps were fetched from
+        // memory about twice (3.7 % more read traffic at 4 bits, B = 256).
+        constexpr int NBPS = BLOCK >= kSlot ? 1 : kSlot / BLOCK;   // blocks per slot
+        constexpr int PER_W = SLOTS * NBPS;                        // steps per worker in this tile
+        static_assert(!LANE_STEPS || (NBPS <= 2 && WU * PER_W <= kWave), "steps of a chunk fit one wavefront load");
+        const uint32_t ls_u = lane / PER_W, ls_r = lane % PER_W;
+        const size_t ls_off = (size_t)ls_u * scale_stride + ((ls_r / NBPS) * kSlot) / BLOCK + (NBPS == 2 ? ls_r % NBPS : 0);
         auto load_chunk = [&](int count, uint32_t (&c)[WU][SLOTS], float (&D)[WU][SLOTS]) {
+            float lane_step = 0.0f;
+            if constexpr (LANE_STEPS) {
+                if (lane < (uint32_t)(count * PER_W)) lane_step = step_from_storage(scales[sidx + ls_off]);
+            }
 #pragma unroll
             for (int u = 0; u < WU; ++u) {
                 if (u < count) {
 #pragma unroll
                     for (int s = 0; s < SLOTS; ++s) {
                         c[u][s] = load_quad_codes<BITS, NT>(cbase + (size_t)(s * SLOT_CODE_BYTES + code_off));
-                        if constexpr (UNIFORM_STEP) {
+                        if constexpr (LANE_STEPS) {
+                            // filled in below, once the chunk's loads are all issued
+                        } else if constexpr (UNIFORM_STEP) {
                             D[u][s] = load_uniform_step(scales, sidx + (s * kSlot) / BLOCK);
                         } else if constexpr (BLOCK * 2 == kSlot) {
                             // two blocks per slot: two scalar loads and a select by half-wavefront measured
@@ -488,6 +526,21 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __rest
                     cbase += code_stride;
                     sidx += scale_stride;
                 }
+            }
+            if constexpr (LANE_STEPS) {
+#pragma unroll
+                for (int u = 0; u < WU; ++u)
+                    if (u < count)
+#pragma unroll
+                        for (int s = 0; s < SLOTS; ++s) {
+                            if constexpr (NBPS == 1) {
+                                D[u][s] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lane_step), u * PER_W + s));
+                            } else {
+                                const float lo = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lane_step), (u * SLOTS + s) * 2));
+                                const float hi = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lane_step), (u * SLOTS + s) * 2 + 1));
+                                D[u][s] = lane < 32 ? lo : hi;
+                            }
+                        }
             }
         };
         auto accumulate_chunk = [&](int count, const uint32_t (&c)[WU][SLOTS], const float (&D)[WU][SLOTS]) {
@@ -565,6 +618,184 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __rest
                 if (i + j < n) epilogue_element<EPI>(epi, i + j, acc[j] * inv_w);
         }
     }
+}
+
+// Eight nibbles of one dword: acc_j = acc_j + (q_j / 16) * (16 D), j = 0..7.
+__device__ __forceinline__ void dr_accumulate_octet_x16(uint32_t c, float D16, float* acc) {
+    const uint32_t t = c >> 4;
+    acc[0] = acc[0] + cvt_off_i4_byte<0>(c) * D16;
+    acc[1] = acc[1] + cvt_off_i4_byte<0>(t) * D16;
+    acc[2] = acc[2] + cvt_off_i4_byte<1>(c) * D16;
+    acc[3] = acc[3] + cvt_off_i4_byte<1>(t) * D16;
+    acc[4] = acc[4] + cvt_off_i4_byte<2>(c) * D16;
+    acc[5] = acc[5] + cvt_off_i4_byte<2>(t) * D16;
+    acc[6] = acc[6] + cvt_off_i4_byte<3>(c) * D16;
+    acc[7] = acc[7] + cvt_off_i4_byte<3>(t) * D16;
+}
+// One dword of codes in the plain form (any step): 8 nibbles or 4 bytes.
+template <int BITS>
+__device__ __forceinline__ void dr_accumulate_dword(uint32_t c, float D, float* acc) {
+#pragma unroll
+    for (int j = 0; j < 32 / BITS; ++j) {
+        const int q = ((int)(c << (32 - BITS * (j + 1)))) >> (32 - BITS);
+        const float d = (float)q * D;
+        acc[j] = acc[j] + d;
+    }
+}
+
+// ---- Algorithm 1 step 3 / Eq. 8 with wide code loads ----
+// The same arithmetic as dr_kernel in another decomposition: a lane loads CB = 4, 8 or 16
+// bytes of codes per worker, i.e. EL = 8*CB/BITS consecutive elements, so a wavefront
+// instruction fetches 256 B .. 1 KB of one payload instead of 128 B (4-bit quads) and a
+// wavefront owns one unit of 64*EL elements.  A lane's EL sums are consecutive in memory;
+// before they are written they are transposed through a wavefront-private piece of LDS
+// into the quad layout, so that every store instruction (and every optimizer-state access
+// of the fused epilogues) covers 1 KB without gaps.  No barrier: a wavefront only reads
+// what it wrote itself, and its LDS instructions execute in order.
+//
+// Block steps: a lane's EL <= 32 elements lie inside one block.  A unit inside one block
+// takes a scalar load, two blocks per unit take two scalar loads and a select, more blocks
+// per unit a vector load in which the lanes of a block share the address.
+template <int CB> struct CodeWord;
+template <> struct CodeWord<4> { typedef uint32_t type; };
+template <> struct CodeWord<8> { typedef u32x2 type; };
+template <> struct CodeWord<16> { typedef u32x4 type; };
+template <int CB>
+__device__ __forceinline__ uint32_t code_dword(const typename CodeWord<CB>::type& v, int k) {
+    if constexpr (CB == 4) return v;
+    else return v[k];
+}
+
+// Index of 16-byte piece p of a wavefront's LDS region: the low three bits are mixed with
+// the next three, so that the eight lanes served together hit different banks both when
+// lanes write their own consecutive pieces and when they read the transposed ones.
+__device__ __forceinline__ uint32_t lds_piece(uint32_t p) { return p ^ ((p >> 3) & 7u); }
+
+template <int BITS, int BLOCK, int CB, int THREADS, int WU, bool NT, int XCDK, Epilogue EPI, typename S>
+__global__ void __launch_bounds__(THREADS)
+dr_wide_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __restrict__ scales,
+               size_t scale_stride, int W, size_t n, float inv_w, EpilogueArgs epi) {
+    constexpr int EL = CB * 8 / BITS;             // elements per lane
+    constexpr int NQ = EL / kQuad;                // quads (16-byte pieces of fp32) per lane
+    constexpr int DW = CB / 4;                    // code dwords per lane and worker
+    constexpr int PER_DW = 32 / BITS;             // elements per code dword
+    constexpr size_t UNIT = (size_t)kWave * EL;
+    constexpr bool UNIFORM_STEP = BLOCK >= (int)UNIT;
+    constexpr int NBLK = UNIFORM_STEP ? 1 : (int)UNIT / BLOCK;   // blocks per unit
+    static_assert(EL >= 8 && EL <= 32 && EL <= BLOCK, "a lane's elements lie inside one block");
+    typedef typename CodeWord<CB>::type code_t;
+    __shared__ f32x4 stage[THREADS / kWave][kWave * NQ];
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wv = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const size_t tile0 = wave_tile_index<THREADS, XCDK>() * UNIT;
+    if (tile0 >= n) return;
+
+    if (tile0 + UNIT <= n) {
+        const uint8_t* cbase = codes + tile0 * BITS / 8;   // uniform, advanced per worker
+        size_t sidx = tile0 / BLOCK;                        // uniform, advanced per worker
+        const uint32_t code_off = lane * CB;
+        const uint32_t step_off = UNIFORM_STEP ? 0u : (lane * EL) / (uint32_t)BLOCK;
+        float acc[EL];
+        EpilogueState<EPI> est[NQ];
+#pragma unroll
+        for (int k = 0; k < NQ; ++k)
+            epilogue_prefetch<EPI, NT>(epi, tile0 + (size_t)k * kSlot + (size_t)lane * kQuad, est[k]);
+#pragma unroll
+        for (int j = 0; j < EL; ++j) acc[j] = 0.0f;
+
+        auto chunk = [&](int count) {
+            code_t c[WU];
+            float D[WU];
+#pragma unroll
+            for (int u = 0; u < WU; ++u) {
+                if (u < count) {
+                    c[u] = vload<NT>(reinterpret_cast<const code_t*>(cbase + code_off));
+                    if constexpr (UNIFORM_STEP) {
+                        D[u] = load_uniform_step(scales, sidx);
+                    } else if constexpr (NBLK == 2) {
+                        const float lo = load_uniform_step(scales, sidx);
+                        const float hi = load_uniform_step(scales, sidx + 1);
+                        D[u] = step_off ? hi : lo;
+                    } else {
+                        D[u] = step_from_storage(scales[sidx + step_off]);
+                    }
+                    cbase += code_stride;
+                    sidx += scale_stride;
+                }
+            }
+            if constexpr (BITS == 4) {
+                uint32_t top = 0;
+#pragma unroll
+                for (int u = 0; u < WU; ++u)
+                    if (u < count) top = umax(top, __float_as_uint(D[u]) & 0x7FFFFFFFu);
+                if (__builtin_expect(__any(top >= kBigStepBits), 0)) {
+#pragma unroll
+                    for (int u = 0; u < WU; ++u)
+                        if (u < count)
+#pragma unroll
+                            for (int k = 0; k < DW; ++k) dr_accumulate_dword<4>(code_dword<CB>(c[u], k), D[u], acc + k * PER_DW);
+                } else {
+#pragma unroll
+                    for (int u = 0; u < WU; ++u)
+                        if (u < count) {
+                            const float D16 = D[u] * 16.0f;
+#pragma unroll
+                            for (int k = 0; k < DW; ++k) dr_accumulate_octet_x16(code_dword<CB>(c[u], k), D16, acc + k * PER_DW);
+                        }
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < WU; ++u)
+                    if (u < count)
+#pragma unroll
+                        for (int k = 0; k < DW; ++k) dr_accumulate_dword<8>(code_dword<CB>(c[u], k), D[u], acc + k * PER_DW);
+            }
+        };
+        int w = 0;
+        for (; w + WU <= W; w += WU) chunk(WU);
+        if (w < W) chunk(W - w);
+
+        // transpose: lane L holds elements [L*EL, L*EL + EL) of the unit; store k wants lane L
+        // to hold elements [k*256 + 4L, +4)
+        f32x4* mine = stage[wv];
+#pragma unroll
+        for (int k = 0; k < NQ; ++k)
+            mine[lds_piece(lane * NQ + k)] = f32x4{acc[4 * k] * inv_w, acc[4 * k + 1] * inv_w,
+                                                   acc[4 * k + 2] * inv_w, acc[4 * k + 3] * inv_w};
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int k = 0; k < NQ; ++k) {
+            const f32x4 v = mine[lds_piece((uint32_t)k * kWave + lane)];
+            const float g[4] = {v.x, v.y, v.z, v.w};
+            epilogue_finish<EPI, NT>(epi, tile0 + (size_t)k * kSlot + (size_t)lane * kQuad, g, est[k]);
+        }
+    } else {
+        // last, partial unit: element by element, never at or beyond n
+#pragma unroll 1
+        for (int j = 0; j < EL; ++j) {
+            const size_t i = tile0 + (size_t)lane * EL + j;
+            if (i >= n) break;
+            float acc = 0.0f;
+            for (int w = 0; w < W; ++w) {
+                const uint8_t* p = codes + (size_t)w * code_stride;
+                int q;
+                if constexpr (BITS == 4) q = (((int)(p[i >> 1] >> (4 * (i & 1))) & 15) ^ 8) - 8;
+                else q = (int)(int8_t)p[i];
+                const float D = step_from_storage(scales[(size_t)w * scale_stride + i / BLOCK]);
+                const float d = (float)q * D;
+                acc = acc + d;
+            }
+            epilogue_element<EPI>(epi, i, acc * inv_w);
+        }
+    }
+}
+
+// The step counter k of Eq. 7 in device memory: set it (add == 0) or add to it (add != 0).
+// One lane writes, with an ordinary vector store.
+__global__ void step_index_kernel(long long* step_index, long long value, int add) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *step_index = add ? *step_index + value : value;
 }
 
 // ---- helpers: zero fill of the state, plain streaming kernels (16 bytes per lane and slot) ----

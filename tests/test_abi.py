@@ -79,6 +79,22 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.loco_stream_read(null, 32, one, null) == 1
     assert lib.loco_stream_fill(null, 0, null) == 0
     assert lib.loco_stream_sum2(one, one, null, 32, null) == 1
+    # the integer sums of the fixed-scale reduce are exact only below 2^24: worker count bounded
+    assert lib.loco_dequant_reduce_fixed(one, 16, (1 << 21) + 1, 0, 4, 19, one, null) == 2
+    assert lib.loco_dequant_reduce_fixed(one, 16, (1 << 17) + 1, 0, 8, 19, one, null) == 2
+    assert lib.loco_dequant_reduce_fixed(null, 16, 1 << 21, 0, 4, 19, null, null) == 0
+    assert lib.loco_dequant_reduce_fixed(null, 16, 1 << 17, 0, 8, 19, null, null) == 0
+    # scheduled calls: NULL or misaligned step index, negative period; decomposition out of range
+    assert lib.loco_compensate_quantize_scheduled(one, 0, one, 8, 4, 256, 0.25, null, 3, one, one, null) == 1
+    assert lib.loco_compensate_quantize_scheduled(one, 0, one, 8, 4, 256, 0.25, ctypes.c_void_p(12), 3, one, one, null) == 3
+    assert lib.loco_compensate_quantize_scheduled(one, 0, one, 8, 4, 256, 0.25, one, -2, one, one, null) == 1
+    assert lib.loco_compensate_quantize_scheduled(null, 0, null, 0, 4, 256, 0.25, null, 3, null, null, null) == 0
+    assert lib.loco_step_index_advance(null, null) == 1 and lib.loco_step_index_set(ctypes.c_void_p(4), 0, null) == 3
+    assert lib.loco_dequant_reduce_decomposed(one, 16, one, 1, 1, 8, 4, 256, one, 6, null) == 2
+    assert lib.loco_dequant_reduce_decomposed(one, 16, one, 1, 1, 8, 4, 256, one, -1, null) == 2
+    assert lib.loco_dequant_reduce_decomposition(8, 4, 256) == 1 and lib.loco_dequant_reduce_decomposition(8, 5, 256) == -1
+    assert lib.loco_reset_due(0, 512) == 1 and lib.loco_reset_due(512, 512) == 1 and lib.loco_reset_due(5, 512) == 0
+    assert lib.loco_runtime_copy(null, one, 16, null) == 1 and lib.loco_runtime_copy(null, null, 0, null) == 0
 
 
 def test_missing_library_is_an_error(tmp_path):
