@@ -20,9 +20,9 @@ take only the shapes of such models and stand in for them:
   dense70b_shard      2.2e9 contiguous bf16 values ~ N(0, (1e-3)^2), each
                       multiplied by 100 with probability 1e-3
 
-Random numbers come from torch generators seeded with BASE_SEED + step (own
-gradient) or BASE_SEED + 1000*(worker+1) + step (a peer's gradient); per-tensor
-factors come from a CPU generator so they do not depend on the device.
+Random numbers come from a counter-based generator keyed on (BASE_SEED, step,
+worker, tensor, index within the tensor), written in integer operations and table
+look-ups so that the CPU and the GPU produce the same bytes (see below).
 """
 from __future__ import annotations
 
@@ -152,12 +152,122 @@ def small(name: str) -> Workload:
     raise KeyError(name)
 
 
+# ---------------------------------------------------------------------------------------
+# The random numbers: a counter-based generator, so that every element is a pure function of
+# (seed, step, worker, tensor, index within the tensor).  It is written once, in torch
+# integer operations and table look-ups plus float64 add/multiply (correctly rounded on every
+# device), and therefore gives the same bytes on the CPU and on the GPU, in any chunking.
+#
+#   bits     x = mix(key + index * GOLDEN), mix = the SplitMix64 finaliser, key = the mix of
+#            (seed, step, worker, tensor); two 32-bit draws per element (high and low half)
+#   normal   inverse-CDF sampling of |Z| from a table of 2^16 + 1 quantiles with linear
+#            interpolation on 15 more bits, the last cell (p > 1 - 2^-16) from a second table
+#            of 2^15 quantiles; the sign is one more bit
+#   t(3)     the same with Student's t quantiles (3 degrees of freedom)
+# The quantile tables are computed once per process on the host (scipy.special, float64) and
+# rounded to float32 precision, which makes them insensitive to last-bit differences between
+# builds of the special functions; the per-tensor factors 10^U use decimal arithmetic.
+# ---------------------------------------------------------------------------------------
+_GOLDEN = 0x9E3779B97F4A7C15
+_M1, _M2 = 0xBF58476D1CE4E5B9, 0x94D049BB133111EB
+_MASK64 = (1 << 64) - 1
+_CELLS, _FRAC_BITS = 1 << 16, 15
+
+
+def _mix_int(x: int) -> int:
+    """SplitMix64 finaliser on a Python integer (mod 2^64)."""
+    x &= _MASK64
+    x = ((x ^ (x >> 30)) * _M1) & _MASK64
+    x = ((x ^ (x >> 27)) * _M2) & _MASK64
+    return x ^ (x >> 31)
+
+
+def stream_key(seed: int, step: int, worker: Optional[int], tensor: int) -> int:
+    """One 64-bit key per (seed, step, worker, tensor); worker None is this worker's own gradient."""
+    k = _mix_int(seed)
+    for part in (step, 0 if worker is None else worker + 1, tensor):
+        k = _mix_int(k ^ _mix_int(part + 0x632BE59BD9B4E019))
+    return k
+
+
+def _signed(x: int) -> int:
+    x &= _MASK64
+    return x - (1 << 64) if x >> 63 else x
+
+
+def _lsr(x: torch.Tensor, k: int) -> torch.Tensor:
+    """Logical shift right of int64 bit patterns."""
+    return (x >> k) & ((1 << (64 - k)) - 1)
+
+
+def random_bits(key: int, first: int, count: int, device) -> torch.Tensor:
+    """int64 bit patterns x_i = mix(key + i * GOLDEN) for i in [first, first + count)."""
+    i = torch.arange(first, first + count, dtype=torch.int64, device=device)
+    x = i * _signed(_GOLDEN) + _signed(key)          # wraps mod 2^64
+    x = (x ^ _lsr(x, 30)) * _signed(_M1)
+    x = (x ^ _lsr(x, 27)) * _signed(_M2)
+    return x ^ _lsr(x, 31)
+
+
+_TABLES: dict = {}
+
+
+def _quantile_tables(kind: str, device) -> Tuple[torch.Tensor, torch.Tensor]:
+    """(body, tail): quantiles of |X| at p = i / 2^16, i = 0 .. 2^16 - 1 plus the left edge of the
+    last cell repeated, and at the mid-points of the 2^15 sub-cells of the last cell."""
+    dev = torch.device(device)
+    hit = _TABLES.get((kind, str(dev)))
+    if hit is not None:
+        return hit
+    host = _TABLES.get((kind, "host"))
+    if host is None:
+        import numpy as np
+        from scipy import special
+        ppf = special.ndtri if kind == "normal" else (lambda p: special.stdtrit(3.0, p))
+        p_body = np.arange(_CELLS, dtype=np.float64) / _CELLS                      # 0 .. 1 - 2^-16
+        p_tail = (_CELLS - 1 + (np.arange(1 << _FRAC_BITS, dtype=np.float64) + 0.5) / (1 << _FRAC_BITS)) / _CELLS
+        body = ppf(0.5 + p_body / 2)
+        body = np.concatenate([body, body[-1:]])                                     # entry 2^16 is never the
+        tail = ppf(0.5 + p_tail / 2)                                                 # right end of a used cell
+        host = tuple(torch.from_numpy(t.astype(np.float32).astype(np.float64)) for t in (body, tail))
+        _TABLES[(kind, "host")] = host
+    out = tuple(t.to(dev) for t in host)
+    _TABLES[(kind, str(dev))] = out
+    return out
+
+
+def _symmetric_from_bits(u32: torch.Tensor, kind: str) -> torch.Tensor:
+    """float64 samples of a symmetric distribution from 32-bit draws (int64 tensor, values < 2^32)."""
+    body, tail = _quantile_tables(kind, u32.device)
+    cell = (u32 >> 16) & (_CELLS - 1)
+    frac = (u32 >> 1) & ((1 << _FRAC_BITS) - 1)
+    lo = body[cell]
+    hi = body[cell + 1]
+    t = (frac.to(torch.float64) + 0.5) * (1.0 / (1 << _FRAC_BITS))                   # exact
+    mag = lo + (hi - lo) * t
+    mag = torch.where(cell == _CELLS - 1, tail[frac], mag)
+    return torch.where((u32 & 1) == 1, -mag, mag)
+
+
+def _hi32(x: torch.Tensor) -> torch.Tensor:
+    return _lsr(x, 32)
+
+
+def _lo32(x: torch.Tensor) -> torch.Tensor:
+    return x & 0xFFFFFFFF
+
+
 def _tensor_factors(w: Workload, lo: float, hi: float) -> List[float]:
     """One log-uniform factor 10^U per tensor; fixed for the workload (not per step)."""
-    g = torch.Generator(device="cpu")
-    g.manual_seed(BASE_SEED ^ 0x5CA1E)
-    u = torch.rand(len(w.segments), generator=g, dtype=torch.float64) * (hi - lo) + lo
-    return [10.0 ** float(x) for x in u]
+    import decimal
+    out = []
+    with decimal.localcontext() as ctx:
+        ctx.prec = 40
+        for t in range(len(w.segments)):
+            h = _mix_int(stream_key(BASE_SEED ^ 0x5CA1E, 0, None, t)) >> 11           # 53 uniform bits
+            u = decimal.Decimal(lo) + (decimal.Decimal(hi) - decimal.Decimal(lo)) * decimal.Decimal(h) / decimal.Decimal(1 << 53)
+            out.append(float(decimal.Decimal(10) ** u))
+    return out
 
 
 def _chunks(length: int, chunk: int):
@@ -168,45 +278,42 @@ def _chunks(length: int, chunk: int):
         pos += ln
 
 
+OUTLIER_THRESHOLD = 4294967          # floor(1e-3 * 2^32): an element is an outlier when its low draw is below
+
+
 def gradient(w: Workload, step: int = 0, worker: Optional[int] = None,
-             device: str | torch.device = "cpu", chunk: int = 1 << 26) -> torch.Tensor:
-    """The flat gradient of `w` for one step (own gradient, or peer `worker`'s)."""
-    seed = BASE_SEED + step + (0 if worker is None else 1000 * (worker + 1))
+             device: str | torch.device = "cpu", chunk: int = 1 << 24) -> torch.Tensor:
+    """The flat gradient of `w` for one step (own gradient, or peer `worker`'s).  The same bytes
+    on every device and for every chunk size."""
     dev = torch.device(device)
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(seed)
     out = torch.empty(w.n, dtype=w.grad_dtype, device=dev)
 
-    def randn(k):
-        return torch.randn(k, generator=gen, device=dev, dtype=torch.float32)
+    def store(start, values64):
+        out[start:start + values64.numel()] = values64.to(torch.float32).to(w.grad_dtype)
 
-    if w.recipe == "gauss":
-        for pos, ln in _chunks(w.n, chunk):
-            out[pos:pos + ln] = (randn(ln) * 1e-3).to(w.grad_dtype)
-    elif w.recipe == "student_t":
+    if w.recipe == "student_t":
         factors = _tensor_factors(w, -5.0, -2.0)
-        for (_, start, length), fac in zip(w.segments, factors):
-            for pos, ln in _chunks(length, chunk):
-                z = randn(ln)
-                chi = (randn(ln) ** 2 + randn(ln) ** 2 + randn(ln) ** 2) / 3.0
-                t = z / torch.sqrt(chi)
-                out[start + pos:start + pos + ln] = (t * fac).to(w.grad_dtype)
     elif w.recipe == "moe":
         factors = _tensor_factors(w, -6.0, -3.0)
-        for e, ((_, start, length), fac) in enumerate(zip(w.segments, factors)):
-            if e in ZERO_EXPERTS:
-                out[start:start + length] = 0
-                continue
-            for pos, ln in _chunks(length, chunk):
-                out[start + pos:start + pos + ln] = (randn(ln) * fac).to(w.grad_dtype)
-    elif w.recipe == "outlier":
-        for pos, ln in _chunks(w.n, chunk):
-            z = randn(ln) * 1e-3
-            hit = torch.rand(ln, generator=gen, device=dev) < 1e-3
-            z = torch.where(hit, z * 100.0, z)
-            out[pos:pos + ln] = z.to(w.grad_dtype)
     else:
-        raise ValueError(w.recipe)
+        factors = [1e-3] * len(w.segments)
+    for t, ((_, start, length), fac) in enumerate(zip(w.segments, factors)):
+        if w.recipe == "moe" and t in ZERO_EXPERTS:
+            out[start:start + length] = 0
+            continue
+        key = stream_key(BASE_SEED, step, worker, t)
+        for pos, ln in _chunks(length, chunk):
+            x = random_bits(key, pos, ln, dev)
+            if w.recipe in ("gauss", "moe"):
+                v = _symmetric_from_bits(_hi32(x), "normal") * fac
+            elif w.recipe == "student_t":
+                v = _symmetric_from_bits(_hi32(x), "student_t3") * fac
+            elif w.recipe == "outlier":
+                v = _symmetric_from_bits(_hi32(x), "normal") * fac
+                v = torch.where(_lo32(x) < OUTLIER_THRESHOLD, v * 100.0, v)
+            else:
+                raise ValueError(w.recipe)
+            store(start + pos, v)
     return out
 
 
