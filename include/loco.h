@@ -113,6 +113,10 @@ loco_status_t loco_compensate_quantize(const void *grad, loco_dtype_t grad_dtype
  *   num_workers         W >= 1 (N of Eq. 8)
  *   bits, block_size    as for loco_compensate_quantize
  *   grad_out            [n] fp32 device, overwritten, 16-byte aligned
+ * Performance note: a wavefront reads the same position of all W payloads at once.  When the
+ * strides are multiples of a large power of two (a shard of exactly 2^k elements laid out
+ * back to back), those W reads meet in one memory channel and the call can lose up to a
+ * quarter of its rate for W >= 32; padding each payload by a few hundred bytes avoids it.
  */
 loco_status_t loco_dequant_reduce(const uint8_t *codes, size_t code_stride_bytes,
                                   const float *scales, size_t scale_stride_elems,
@@ -333,6 +337,8 @@ int loco_dequant_reduce_decomposition(int num_workers, int bits, int block_size)
  *                     keeps the loads alive without a store stream)
  *   loco_stream_fill  dst[i] = 0
  *   loco_stream_sum2  dst[i] = src_a[i] + src_b[i] on 32-bit words (wrapping)
+ *   loco_stream_update3  a[i] += 1, b[i] += a[i], c[i] += b[i] in place on 32-bit words: the
+ *                     traffic of an optimizer step with two moment arrays and nothing else
  * loco_runtime_copy is the HIP runtime's own device-to-device copy (hipMemcpyDtoDAsync) on
  * the same stream, as an independent figure beside loco_stream_copy; any size and alignment.
  */
@@ -340,6 +346,7 @@ loco_status_t loco_stream_copy(void *dst, const void *src, size_t bytes, void *s
 loco_status_t loco_stream_read(const void *src, size_t bytes, void *sink16, void *stream);
 loco_status_t loco_stream_fill(void *dst, size_t bytes, void *stream);
 loco_status_t loco_stream_sum2(void *dst, const void *src_a, const void *src_b, size_t bytes, void *stream);
+loco_status_t loco_stream_update3(void *a, void *b, void *c, size_t bytes, void *stream);
 loco_status_t loco_runtime_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 /*

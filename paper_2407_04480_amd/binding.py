@@ -56,6 +56,7 @@ EXPORTS = (
     "loco_dequant_reduce_decomposed",
     "loco_dequant_reduce_decomposition",
     "loco_runtime_copy",
+    "loco_stream_update3",
 )
 
 _lib = None
@@ -135,6 +136,7 @@ def load_library(path: Optional[str] = None):
     lib.loco_dequant_reduce_decomposed.restype = i
     lib.loco_dequant_reduce_decomposition.argtypes, lib.loco_dequant_reduce_decomposition.restype = [i, i, i], i
     lib.loco_runtime_copy.argtypes, lib.loco_runtime_copy.restype = [vp, vp, sz, vp], i
+    lib.loco_stream_update3.argtypes, lib.loco_stream_update3.restype = [vp, vp, vp, sz, vp], i
     for _n in ("loco_dequant_reduce_sgd", "loco_dequant_reduce_adam", "loco_dequant_reduce_fixed_sgd",
                "loco_dequant_reduce_fixed_adam"):
         getattr(lib, _n).restype = i
@@ -603,3 +605,13 @@ def loco_runtime_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None
         raise ValueError("dst too small")
     st = lib.loco_runtime_copy(_dev_ptr(dst, "dst"), _dev_ptr(src, "src"), nbytes, _stream_handle(stream))
     _check("loco_runtime_copy", st)
+
+
+def loco_stream_update3(a: torch.Tensor, b: torch.Tensor, c: torch.Tensor, stream=None) -> None:
+    """In-place update of three equally sized arrays: the traffic of an optimizer step alone (measurement aid)."""
+    lib = load_library()
+    nbytes = a.numel() * a.element_size()
+    if b.numel() * b.element_size() != nbytes or c.numel() * c.element_size() != nbytes:
+        raise ValueError("sizes differ")
+    st = lib.loco_stream_update3(_dev_ptr(a, "a"), _dev_ptr(b, "b"), _dev_ptr(c, "c"), nbytes, _stream_handle(stream))
+    _check("loco_stream_update3", st)

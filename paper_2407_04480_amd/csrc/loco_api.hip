@@ -35,12 +35,15 @@ constexpr bool kNonTemporal = true;
 // of fetching it into all eight.
 constexpr int kCqXcdRun = 0;
 constexpr int kDrXcdRun = 32;
+constexpr int kDrNaturalOrderWorkers = 16;              // 4-bit plain reduce: from this many payloads and
+constexpr size_t kDrNaturalOrderElements = (size_t)1 << 30;   // elements on, no runs of tiles per XCD
 // Plain streaming kernels, each in the shape that measured fastest for its mix: a pure write
 // stream likes 4 KB per workgroup, a copy one wavefront per KB, a pure read 4 KB per wavefront.
 struct FillShape { static constexpr int kSlots = 1, kThreads = 256; };
 struct CopyShape { static constexpr int kSlots = 1, kThreads = 64; };
 struct ReadShape { static constexpr int kSlots = 4, kThreads = 64; };
 struct Sum2Shape { static constexpr int kSlots = 1, kThreads = 64; };
+struct Update3Shape { static constexpr int kSlots = 4, kThreads = 64; };
 static_assert(CqShape<4>::kSlots % 2 == 0 && CqShape<8>::kSlots % 2 == 0,
               "block size 512 spans two slots of one wavefront");
 
@@ -166,34 +169,35 @@ using DrShapeFor = std::conditional_t<dr_updates_in_place(EPI), DrShape<8>, DrSh
 // kQuadLaneSteps the same with the block steps of a chunk of workers fetched by one vector
 // load (blocks of 128 elements and more); kWide4/8/16 is dr_wide_kernel with that many code
 // bytes per lane and worker.  Measured on MI355X (2^26 .. 2.2e9 elements):
-//   - at the usual worker counts (W <= 16) the quad layout is the fastest at every block size;
-//   - with many workers the code loads of the quad layout (2 bytes per lane at 4 bits) become
-//     the limit: W >= 32 with blocks of 32..128 elements gains 6-10 points of HBM peak from
-//     wide loads, W >= 96 with larger blocks 4 points;
+//   - up to 16 payloads of 4-bit codes with blocks of 256 elements and more, and for 8-bit codes
+//     up to 64 payloads, the quad layout is the fastest;
+//   - with more payloads its code loads (2 bytes per lane at 4 bits) become the limit: 4-bit codes
+//     with blocks of 32..128 elements gain 6-10 points of HBM peak from wide loads from W = 16 on,
+//     with larger blocks 1-5 points from W = 64 on, 8-bit codes 2 points at W = 128;
 //   - lane-loaded steps remove the doubled fetch of step lines that the scalar cache causes
 //     (read traffic 1.037x -> 1.001x of the algorithmic bytes at 4 bits, B = 256) but cost
-//     1-6 % of speed at 4 bits; at 8 bits with B >= 256 they are 1.6 points faster.
+//     1-6 % of speed at 4 bits; at 8 bits with B >= 256 they are 1-3 points faster.
 enum DrDecomposition { kDrAuto = 0, kDrQuad = 1, kDrQuadLaneSteps = 2, kDrWide4 = 3, kDrWide8 = 4, kDrWide16 = 5 };
 template <int CB> struct DrWideShape { static constexpr int kThreads = CB == 16 ? 128 : 256, kInFlight = 4; };
 
 int dr_auto_decomposition(int bits, int block, int W, Epilogue kind, bool scales_bf16) {
     if (kind != Epilogue::kStore || scales_bf16) return kDrQuad;
+    if (W >= 96) return kDrWide16;                       // every bit width and block size
     if (bits == 4) {
-        if (block <= 128 && W >= 64) return kDrWide16;
-        if (block <= 128 && W >= 32) return kDrWide8;
-        if (block >= 256 && W >= 96) return kDrWide16;
+        if (block <= 128 && W >= 16) return W >= 64 ? kDrWide16 : kDrWide8;
+        if (block >= 256 && W >= 64) return kDrWide16;
         return kDrQuad;
     }
     return block >= 256 && !dr_few_workers(bits, W) ? kDrQuadLaneSteps : kDrQuad;
 }
 
-template <int BITS, int BLOCK, Epilogue EPI, typename Shape, typename S, bool LANE_STEPS>
+template <int BITS, int BLOCK, Epilogue EPI, typename Shape, typename S, bool LANE_STEPS, int XCD_RUN = kDrXcdRun>
 loco_status_t launch_dr_quad(hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
     unsigned grid;
     if (loco_status_t st = grid_for(a.n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid,
-                                    kDrXcdRun ? 8 * kDrXcdRun : 1))
+                                    XCD_RUN ? 8 * XCD_RUN : 1))
         return st;
-    return launch(dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun, EPI, S,
+    return launch(dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, XCD_RUN, EPI, S,
                             LANE_STEPS>,
                   grid, Shape::kThreads, s, a.codes, a.code_stride, static_cast<const S*>(a.scales), a.scale_stride, a.W,
                   a.n, 1.0f / (float)a.W, epi);
@@ -237,6 +241,17 @@ loco_status_t launch_dr(int how, hipStream_t s, const DrArgs& a, const EpilogueA
     if (how != kDrQuad) return LOCO_ERR_UNSUPPORTED;
     if constexpr (!dr_updates_in_place(EPI)) {
         if (dr_few_workers(BITS, a.W)) return launch_dr_quad<BITS, BLOCK, EPI, DrFewWorkersShape, float, false>(s, a, epi);
+    }
+    if constexpr (EPI == Epilogue::kStore && BITS == 4) {
+        // Large shards with 16 payloads and more: the hardware's own round robin of workgroups over
+        // the XCDs measured 2-3 points of HBM peak faster than runs of tiles per XCD (2.2e9 elements,
+        // W = 16: 80 % against 77.6 %), although every L2 then fetches the lines of block steps for
+        // itself (read traffic 1.24x instead of 1.04x of the algorithmic bytes).  Not when the payload
+        // strides are multiples of a large power of two: the W loads of a wavefront then meet in one
+        // memory channel, which the round robin suffers from far more (down to 40-60 % of the rate).
+        const bool aliased = a.code_stride % 4096 == 0 || (a.scale_stride * sizeof(float)) % 4096 == 0;
+        if (a.W >= kDrNaturalOrderWorkers && a.n >= kDrNaturalOrderElements && !aliased)
+            return launch_dr_quad<BITS, BLOCK, EPI, DrShape<BITS>, float, false, 0>(s, a, epi);
     }
     return launch_dr_quad<BITS, BLOCK, EPI, DrShapeFor<BITS, EPI>, float, false>(s, a, epi);
 }
@@ -368,14 +383,22 @@ loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const
     return LOCO_ERR_UNSUPPORTED;
 }
 
+// Runs of 32 tiles per XCD measured about one point of HBM peak faster for the fp32 output and the
+// fused optimizers of the fixed-scale reduce, and slower for the bf16 output.
+template <Epilogue EPI> constexpr int fixed_dr_xcd_run() { return EPI == Epilogue::kStoreBf16 ? 0 : 32; }
+
 template <Epilogue EPI>
-loco_status_t launch_fixed_dr(int bits, unsigned grid, hipStream_t s, const uint8_t* codes, size_t cs, int W,
+loco_status_t launch_fixed_dr(int bits, hipStream_t s, const uint8_t* codes, size_t cs, int W,
                               size_t n, float inv_s, float inv_w, const EpilogueArgs& epi) {
     using Shape = FixedDrShapeFor<EPI>;
+    constexpr int kRun = fixed_dr_xcd_run<EPI>();
+    unsigned grid;
+    if (loco_status_t st = grid_for(n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid, kRun ? 8 * kRun : 1))
+        return st;
     if (bits == 4)
-        return launch(fixed_dr_kernel<4, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI>, grid,
+        return launch(fixed_dr_kernel<4, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI, kRun>, grid,
                       Shape::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
-    return launch(fixed_dr_kernel<8, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI>, grid,
+    return launch(fixed_dr_kernel<8, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI, kRun>, grid,
                   Shape::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
 }
 
@@ -401,18 +424,13 @@ loco_status_t reduce_fixed(const uint8_t* codes, size_t code_stride_bytes, int n
     if (!aligned(codes, 16)) return LOCO_ERR_ALIGNMENT;
     if (loco_status_t st = check_device_range(codes, (W - 1) * code_stride_bytes + cb)) return st;
     if (loco_status_t st = check_epilogue(kind, epi, n)) return st;
-    unsigned grid;
-    const size_t per_group = kind == Epilogue::kAdam
-        ? (size_t)kSlot * FixedDrWideShape::kSlots * (FixedDrWideShape::kThreads / kWave)
-        : (size_t)kSlot * FixedDrShape::kSlots * (FixedDrShape::kThreads / kWave);
-    if (loco_status_t st = grid_for(n, per_group, &grid)) return st;
     const float inv_s = std::ldexp(1.0f, -log2_s), inv_w = 1.0f / (float)num_workers;
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (kind) {
-        case Epilogue::kStore: return launch_fixed_dr<Epilogue::kStore>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi);
-        case Epilogue::kStoreBf16: return launch_fixed_dr<Epilogue::kStoreBf16>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi);
-        case Epilogue::kSgd: return launch_fixed_dr<Epilogue::kSgd>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi);
-        case Epilogue::kAdam: return launch_fixed_dr<Epilogue::kAdam>(bits, grid, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi);
+        case Epilogue::kStore: return launch_fixed_dr<Epilogue::kStore>(bits, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi);
+        case Epilogue::kStoreBf16: return launch_fixed_dr<Epilogue::kStoreBf16>(bits, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi);
+        case Epilogue::kSgd: return launch_fixed_dr<Epilogue::kSgd>(bits, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi);
+        case Epilogue::kAdam: return launch_fixed_dr<Epilogue::kAdam>(bits, s, codes, code_stride_bytes, num_workers, n, inv_s, inv_w, epi);
     }
     return LOCO_ERR_UNSUPPORTED;
 }
@@ -692,6 +710,21 @@ loco_status_t loco_stream_sum2(void* dst, const void* src_a, const void* src_b, 
     if (loco_status_t st = check_device_range(src_a, bytes)) return st;
     if (loco_status_t st = check_device_range(src_b, bytes)) return st;
     return launch_stream<StreamMode::kSum2, Sum2Shape>(dst, src_a, src_b, bytes, stream);
+}
+
+loco_status_t loco_stream_update3(void* a, void* b, void* c, size_t bytes, void* stream) {
+    if (bytes == 0) return LOCO_OK;
+    if (!a || !b || !c) return LOCO_ERR_INVALID_ARG;
+    if (bytes % 16 != 0 || !aligned(a, 16) || !aligned(b, 16) || !aligned(c, 16)) return LOCO_ERR_ALIGNMENT;
+    if (loco_status_t st = check_device_range(a, bytes)) return st;
+    if (loco_status_t st = check_device_range(b, bytes)) return st;
+    if (loco_status_t st = check_device_range(c, bytes)) return st;
+    const size_t n16 = bytes / 16;
+    unsigned grid;
+    if (loco_status_t st = grid_for(n16, (size_t)Update3Shape::kThreads * Update3Shape::kSlots, &grid)) return st;
+    return launch(update3_kernel<Update3Shape::kSlots, Update3Shape::kThreads, kNonTemporal>, grid, Update3Shape::kThreads,
+                  static_cast<hipStream_t>(stream), static_cast<u32x4*>(a), static_cast<u32x4*>(b),
+                  static_cast<u32x4*>(c), n16);
 }
 
 loco_status_t loco_stream_fill(void* dst, size_t bytes, void* stream) {

@@ -247,7 +247,7 @@ fixed_f32_cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size
 // the byte sums are widened every 16 workers); 8-bit codes are biased to 0..255 and summed
 // in 16-bit halves (up to 256 workers per widening).  A lane owns 4 consecutive elements
 // per slot, as in dr_kernel, so the fp32 output is written 16 B per lane, gap-free.
-template <int BITS, int SLOTS, int THREADS, int WU, bool NT, Epilogue EPI>
+template <int BITS, int SLOTS, int THREADS, int WU, bool NT, Epilogue EPI, int XCDK = 0>
 __global__ void __launch_bounds__(THREADS)
 fixed_dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, int W, size_t n, float inv_s,
                 float inv_w, EpilogueArgs epi) {
@@ -255,7 +255,7 @@ fixed_dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, int W, si
     constexpr uint32_t SLOT_CODE_BYTES = kSlot * BITS / 8;
     constexpr int FLUSH = BITS == 4 ? 16 : 256;   // workers per widening of the packed sums
     const uint32_t lane = threadIdx.x & (kWave - 1);
-    const size_t tile0 = wave_tile_index<THREADS, 0>() * TILE;
+    const size_t tile0 = wave_tile_index<THREADS, XCDK>() * TILE;
     if (tile0 >= n) return;
 
     if (tile0 + TILE <= n) {

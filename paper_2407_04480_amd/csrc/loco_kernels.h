@@ -849,4 +849,28 @@ stream_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, const u32x
     }
 }
 
+// In-place update of three arrays (a += 1; b += a; c += b on 32-bit words): the traffic of an
+// optimizer with two moment arrays and nothing else, three read and three write streams.
+template <int SLOTS, int THREADS, bool NT>
+__global__ void __launch_bounds__(THREADS)
+update3_kernel(u32x4* __restrict__ a, u32x4* __restrict__ b, u32x4* __restrict__ c, size_t n16) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const size_t wave = (size_t)blockIdx.x * (THREADS / kWave) + (threadIdx.x >> 6);
+    const size_t tile0 = wave * ((size_t)kWave * SLOTS);
+    u32x4 x[SLOTS], y[SLOTS], z[SLOTS];
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s) {
+        const size_t i = tile0 + (size_t)s * kWave + lane;
+        if (i < n16) { x[s] = vload<NT>(a + i); y[s] = vload<NT>(b + i); z[s] = vload<NT>(c + i); }
+    }
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s) {
+        const size_t i = tile0 + (size_t)s * kWave + lane;
+        if (i < n16) {
+            x[s] += 1u; y[s] += x[s]; z[s] += y[s];
+            vstore<NT>(a + i, x[s]); vstore<NT>(b + i, y[s]); vstore<NT>(c + i, z[s]);
+        }
+    }
+}
+
 }  // namespace loco

@@ -92,7 +92,7 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.loco_step_index_advance(null, null) == 1 and lib.loco_step_index_set(ctypes.c_void_p(4), 0, null) == 3
     assert lib.loco_dequant_reduce_decomposed(one, 16, one, 1, 1, 8, 4, 256, one, 6, null) == 2
     assert lib.loco_dequant_reduce_decomposed(one, 16, one, 1, 1, 8, 4, 256, one, -1, null) == 2
-    assert lib.loco_dequant_reduce_decomposition(8, 4, 256) == 1 and lib.loco_dequant_reduce_decomposition(8, 5, 256) == -1
+    assert lib.loco_dequant_reduce_decomposition(8, 4, 256) == 1 and lib.loco_dequant_reduce_decomposition(128, 8, 64) == 5 and lib.loco_dequant_reduce_decomposition(8, 5, 256) == -1
     assert lib.loco_reset_due(0, 512) == 1 and lib.loco_reset_due(512, 512) == 1 and lib.loco_reset_due(5, 512) == 0
     assert lib.loco_runtime_copy(null, one, 16, null) == 1 and lib.loco_runtime_copy(null, null, 0, null) == 0
 

@@ -22,8 +22,9 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 FULL = ["llama7b_shard_4bit_b256", "llama7b_shard_8bit_b64", "mixtral_moe_shard_4bit_b128",
         "dense70b_shard_4bit_b256"]
-STEPS = {"llama7b_shard_4bit_b256": 4, "llama7b_shard_8bit_b64": 3, "mixtral_moe_shard_4bit_b128": 10,
-         "dense70b_shard_4bit_b256": 4}
+# every step of every workload: 20 for the dense shards, 10 for the MoE shard (error accumulation)
+STEPS = {"llama7b_shard_4bit_b256": 20, "llama7b_shard_8bit_b64": 20, "mixtral_moe_shard_4bit_b128": 10,
+         "dense70b_shard_4bit_b256": 20}
 
 
 def sample_blocks(w: workloads.Workload, count=3000, seed=11):
@@ -81,11 +82,20 @@ def test_full_size_against_sampled_oracle(name):
     grads = [workloads.gradient(w, s, device=DEV) for s in range(2)]   # ring of two, as in bench.py
     e_ref = np.zeros(ns, np.float32)
     qmax = (1 << (bits - 1)) - 1
+    # Lemma 1 telescoped over the steps, on the GPU's own outputs, accumulated in float64 on the device
+    decoded = torch.empty(n, dtype=torch.float32, device=DEV)
+    sum_d = torch.zeros(ns, dtype=torch.float64, device=DEV)
+    sum_g = torch.zeros(ns, dtype=torch.float64, device=DEV)
+    step_max = torch.zeros(blocks.size, dtype=torch.float32, device=DEV)
 
     for step in range(STEPS[name]):
         g = grads[step & 1]
         g_s = host_grad(g[eidx])
         loco_compensate_quantize(g, err, bits, B, w.beta, False, own_codes, own_scales)
+        loco_dequant_reduce(own_codes, 0, own_scales, 0, 1, n, bits, B, decoded)      # d_k, what a receiver decodes
+        sum_d += decoded[eidx].double()
+        sum_g += g[eidx].double()
+        step_max = torch.maximum(step_max, own_scales[bidx])
         c_ref, s_ref = oracle.compensate_quantize(g_s, e_ref, bits, B, w.beta)
         torch.cuda.synchronize()
         c_gpu = own_codes[cidx].cpu().numpy()
@@ -96,6 +106,18 @@ def test_full_size_against_sampled_oracle(name):
         top = float(np.abs(e_ref).max())
         assert float(np.abs(e_gpu.astype(np.float64) - e_ref).max()) <= 1e-6 * top
         assert np.count_nonzero(e_gpu != e_ref) == 0, f"step {step}: state not identical"
+
+    # ---- Lemma 1 with an uncompressed state, telescoped: sum_k d_k = sum_k g_k - e~_K / beta ----
+    # Per step the binary32 roundings of h = g + e~ and of the fmaf of Eq. 5 enter the identity with at
+    # most 2^-24 (|h| + |e~'| / beta) <= 2^-24 D (qmax + 1 / (2 beta)); the bound below doubles that.
+    K = STEPS[name]
+    residual = (sum_d - (sum_g - err[eidx].double() / w.beta)).abs().view(blocks.size, B).amax(dim=1)
+    bound = K * 2.0 ** -24 * 2.0 * (qmax + 0.5 / w.beta) * step_max.double()
+    worst = float((residual / bound.clamp_min(1e-300)).max())
+    assert bool((residual <= bound).all()), f"Lemma 1 after {K} steps: residual up to {worst:.3f} of the bound"
+    assert bool((residual[step_max == 0] == 0).all())
+    print(f"[{name}] Lemma 1 telescoped over {K} steps: largest residual {worst:.3f} of the rounding bound", flush=True)
+    del decoded, sum_d, sum_g
 
     # ---- whole-array properties of the last payload (device-side reductions) ----
     scales_all = own_scales

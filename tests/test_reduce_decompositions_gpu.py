@@ -59,9 +59,9 @@ def test_every_decomposition_matches_the_oracle(decomposition, bits, B):
             f"decomposition {decomposition} bits={bits} B={B} W={W} n={n}: {np.count_nonzero(got != want)} differ"
 
 
-@pytest.mark.parametrize("bits,B,W", [(4, 32, 31), (4, 32, 32), (4, 64, 33), (4, 64, 63), (4, 64, 64), (4, 128, 70),
-                                      (4, 256, 95), (4, 256, 96), (4, 256, 130), (4, 512, 128), (8, 64, 40),
-                                      (8, 256, 1), (8, 256, 2), (8, 512, 9)])
+@pytest.mark.parametrize("bits,B,W", [(4, 32, 15), (4, 32, 16), (4, 64, 33), (4, 64, 63), (4, 64, 64), (4, 128, 70),
+                                      (4, 256, 63), (4, 256, 64), (4, 256, 130), (4, 512, 128), (8, 64, 40),
+                                      (8, 64, 95), (8, 64, 96), (8, 256, 1), (8, 256, 2), (8, 512, 9), (8, 512, 100)])
 def test_the_librarys_own_choice_matches_the_oracle(bits, B, W):
     """loco_dequant_reduce itself on both sides of every switch point of its dispatch."""
     rs = np.random.default_rng(7 * W + B + bits)
@@ -79,8 +79,13 @@ def test_the_librarys_own_choice_matches_the_oracle(bits, B, W):
 def test_many_workers_take_the_wide_loads():
     assert loco_dequant_reduce_decomposition(8, 4, 256) == QUAD
     assert loco_dequant_reduce_decomposition(16, 4, 256) == QUAD
+    assert loco_dequant_reduce_decomposition(64, 4, 256) == WIDE16
     assert loco_dequant_reduce_decomposition(128, 4, 256) == WIDE16
-    assert loco_dequant_reduce_decomposition(32, 4, 64) == WIDE8
+    assert loco_dequant_reduce_decomposition(8, 4, 64) == QUAD
+    assert loco_dequant_reduce_decomposition(16, 4, 64) == WIDE8
     assert loco_dequant_reduce_decomposition(64, 4, 64) == WIDE16
     assert loco_dequant_reduce_decomposition(8, 8, 64) == QUAD
+    assert loco_dequant_reduce_decomposition(64, 8, 64) == QUAD
+    assert loco_dequant_reduce_decomposition(128, 8, 64) == WIDE16
+    assert loco_dequant_reduce_decomposition(8, 8, 256) == QUAD_LANE_STEPS
     assert loco_dequant_reduce_decomposition(8, 3, 64) == -1 and loco_dequant_reduce_decomposition(0, 4, 64) == -1
