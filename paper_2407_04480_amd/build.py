@@ -89,5 +89,23 @@ def build(out: str = LIB, tuning: dict | None = None, verbose: bool = False) -> 
     return out
 
 
+PROBE = os.path.join(HERE, "loco_traffic_probe")
+
+
+def build_probe(out: str = PROBE) -> str:
+    """The plain-C driver of the library for counter collection (csrc/loco_traffic_probe.c): gcc, C99,
+    linked against libloco.so and the HIP runtime."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-I", os.path.join(ROOT, "include"), "-I", os.path.join(rocm, "include"),
+           "-o", out, os.path.join(CSRC, "loco_traffic_probe.c"), "-L", HERE, "-lloco", "-L", os.path.join(rocm, "lib"),
+           "-lamdhip64", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stdout + res.stderr)
+        raise RuntimeError("gcc failed on the traffic probe (exit %d)" % res.returncode)
+    return out
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_probe())

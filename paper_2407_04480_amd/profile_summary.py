@@ -2,11 +2,13 @@
 
 Two steps, so that the raw CSVs (large) never have to leave the GPU machine:
 
-  condense DIR    DIR holds the output of the three profiler runs of one bench.py command
-                  line (see COMMANDS below): DIR/stats, DIR/fetch, DIR/write and the bench
-                  line of the stats run in DIR/bench.json.  Writes DIR/condensed.json: per
-                  kernel the call count and durations of the stats run and the mean
-                  FETCH_SIZE / WRITE_SIZE per dispatch of the counter runs.
+  condense DIR    DIR holds the output of the three profiler runs of one workload (see COMMANDS
+                  below): DIR/stats (bench.py under --kernel-trace --stats, its JSON line in
+                  DIR/bench.json, its arguments in DIR/args.txt) and DIR/fetch, DIR/write (the
+                  plain-C driver loco_traffic_probe under --pmc, its arguments in
+                  DIR/probe_args.txt).  Writes DIR/condensed.json: per kernel the call count
+                  and durations of the stats run and the mean FETCH_SIZE / WRITE_SIZE per
+                  dispatch of the counter runs.
   write FILES...  Each FILE is a condensed.json.  Writes profiles/<entry point>_<workload>.md
                   for the two kernels of the step and updates profiles/traffic.json, the
                   table bench.py reads its `traffic` figures from.
@@ -14,6 +16,11 @@ Two steps, so that the raw CSVs (large) never have to leave the GPU machine:
 
 The counters are scaled by what they read for the library's plain copy kernel in the same
 run (2 GiB read, 2 GiB written): bytes = KiB reported * 1024 * (2 GiB / copy's reading).
+They are collected from loco_traffic_probe, a C99 process that makes the same library calls at
+the same shape as bench.py: counter collection serialises every dispatch of the process, and
+the Python process adds some 10^5 small dispatches of the input generator to the few hundred
+of the library.  Kernel names, and therefore launch shapes, are checked to agree between the
+two programs.
 """
 from __future__ import annotations
 
@@ -31,8 +38,8 @@ COPY_KERNEL = "stream_kernel<(loco::StreamMode)0"
 
 COMMANDS = """\
     rocprofv3 --kernel-trace --stats -d $O/stats -o st --output-format csv -- python3 bench.py {args} --configs none --steps 10 --warmup 2 --cpu-sample 0
-    rocprofv3 --kernel-trace --pmc FETCH_SIZE -d $O/fetch -o pf --output-format csv -- python3 bench.py {args} --configs none --steps 3 --warmup 1 --cpu-sample 0
-    rocprofv3 --kernel-trace --pmc WRITE_SIZE -d $O/write -o pw --output-format csv -- python3 bench.py {args} --configs none --steps 3 --warmup 1 --cpu-sample 0"""
+    rocprofv3 --kernel-trace --pmc FETCH_SIZE -d $O/fetch -o pf --output-format csv -- paper_2407_04480_amd/loco_traffic_probe {probe_args}
+    rocprofv3 --kernel-trace --pmc WRITE_SIZE -d $O/write -o pw --output-format csv -- paper_2407_04480_amd/loco_traffic_probe {probe_args}"""
 
 
 def find_one(directory, pattern):
@@ -75,9 +82,11 @@ def condense(directory: str) -> str:
         bench = json.loads([line for line in fh if line.startswith("{")][-1])
     with open(os.path.join(directory, "args.txt")) as fh:
         args = fh.read().strip()
+    with open(os.path.join(directory, "probe_args.txt")) as fh:
+        probe_args = fh.read().strip()
     out = os.path.join(directory, "condensed.json")
     with open(out, "w") as fh:
-        json.dump({"bench_args": args, "stats": stats, "counters_KiB_per_dispatch": means, "bench": bench}, fh, indent=1)
+        json.dump({"bench_args": args, "probe_args": probe_args, "stats": stats, "counters_KiB_per_dispatch": means, "bench": bench}, fh, indent=1)
     return out
 
 
@@ -98,14 +107,19 @@ def write_profiles(files) -> None:
             traffic = json.load(fh)
     except (OSError, ValueError):
         traffic = {}
+    loaded = []
     for path in files:
         with open(path) as fh:
-            data = json.load(fh)
+            loaded.append((path, json.load(fh)))
+    # a kernel that several runs share (the plain compressor under a fused reduce, say) is written
+    # by each of them: the run with the plainest command line goes last and is the one that stays
+    loaded.sort(key=lambda item: -len(item[1]["bench_args"]))
+    for path, data in loaded:
         bench, stats, counters = data["bench"], data["stats"], data["counters_KiB_per_dispatch"]
         workload, n = bench["config"]["workload"], bench["config"]["n"]
         copy = [k for k in counters if COPY_KERNEL in k]
         if not copy:
-            raise ValueError(f"{path}: the copy kernel is not in the counter runs (bench.py ran with --no-copy-ceiling?)")
+            raise ValueError(f"{path}: the copy kernel is not in the counter runs")
         fscale = COPY_BYTES / 1024 / counters[copy[0]]["FETCH_SIZE"]
         wscale = COPY_BYTES / 1024 / counters[copy[0]]["WRITE_SIZE"]
         for live in bench["kernels"]:
@@ -128,8 +142,10 @@ Kernel: `{k}`, n = {n} elements per launch.
 
 Commands (run from the repository root on the GPU box after `cd /tmp && export TMPDIR=/tmp`; `$O` is an output folder):
 
-{COMMANDS.format(args=data['bench_args'])}
+{COMMANDS.format(args=data['bench_args'], probe_args=data['probe_args'])}
 
+`loco_traffic_probe` (paper_2407_04480_amd/csrc/loco_traffic_probe.c, built by `__graft_entry__.build()`) is a C99 process that
+makes the same library calls at the same shape; its arguments are N BITS BLOCK WORKERS GRAD FORM OPTIMIZER OUT SCALES CLIP STEPS.
 The summary below was made from those CSVs with `python3 -m paper_2407_04480_amd.profile_summary`.
 
 ## Duration (`--kernel-trace --stats`, kernel_stats.csv)
