@@ -445,6 +445,9 @@ def config_entry(result):
     keep = ("workload", "form", "n", "grad_dtype", "bits", "block_size", "log2_s", "se_mult", "state", "num_workers",
             "steps", "warmup", "ms_per_step", "value", "unit", "elements_per_s", "reduce_decomposition")
     entry = {k: result[k] for k in keep if k in result}
+    if sum(k["algorithmic_bytes_per_launch"] for k in result["kernels"]) < 256e6:
+        entry["note"] = ("the whole step moves less than the 256 MB memory-side cache and each kernel runs a few "
+                         "microseconds: bound by launches, not by HBM; a parity workload, not a bandwidth figure")
     entry["kernels"] = [{k: kern[k] for k in ("kernel", "avg_ms", "min_ms", "achieved", "frac", "traffic",
                                               "traffic_source", "algorithmic_bytes_per_launch")}
                         for kern in result["kernels"]]
@@ -507,6 +510,15 @@ def sweep(args):
         table.append({"grad": str(g.dtype).replace("torch.", ""), "bits": 4, "form": "fixed",
                       **rate(g.element_size() + 2 + 0.5, n, ms)})
     out["compensate_quantize_7b_shard"] = table
+    # 4-bit codes: direct 2-byte stores from every lane against 16-byte stores staged through LDS
+    staged = []
+    for g in (g16,):
+        for B in (256, 128):
+            for name, fn in (("direct", api.loco_compensate_quantize), ("staged", api.loco_compensate_quantize_staged_codes)):
+                ms = median_ms(lambda: fn(g, err, 4, B, 0.25, False, codes, scales, stream))
+                staged.append({"grad": "bfloat16", "bits": 4, "block_size": B, "code_stores": name,
+                               **rate(g.element_size() + 8 + 0.5 + 4 / B, n, ms)})
+    out["compensate_quantize_code_store_shapes"] = staged
     del g16, g32, err, err8, codes, scales
     release()
 

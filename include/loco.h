@@ -306,6 +306,17 @@ loco_status_t loco_dequant_reduce_bf16_scales(const uint8_t *codes, size_t code_
                                               float *grad_out, void *stream);
 
 /*
+ * Measurement aid: loco_compensate_quantize (bits = 4 only) with the codes gathered in LDS and
+ * written as 16-byte stores from a few lanes instead of 2-byte stores from every lane; same
+ * arithmetic, same bytes.  It exists so that the comparison of the two store shapes can be
+ * repeated (the direct stores are 1-2 % faster and are what loco_compensate_quantize uses).
+ */
+loco_status_t loco_compensate_quantize_staged_codes(const void *grad, loco_dtype_t grad_dtype,
+                                                    float *err_state, size_t n, int bits, int block_size,
+                                                    float beta, int reset, uint8_t *codes_out,
+                                                    float *scales_out, void *stream);
+
+/*
  * Measurement and tuning aid: loco_dequant_reduce with the work decomposition chosen by the
  * caller instead of by the library (same arithmetic, same result bit for bit):
  *   0  what loco_dequant_reduce picks (see loco_dequant_reduce_decomposition)

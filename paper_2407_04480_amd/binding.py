@@ -57,6 +57,7 @@ EXPORTS = (
     "loco_dequant_reduce_decomposition",
     "loco_runtime_copy",
     "loco_stream_update3",
+    "loco_compensate_quantize_staged_codes",
 )
 
 _lib = None
@@ -136,6 +137,8 @@ def load_library(path: Optional[str] = None):
     lib.loco_dequant_reduce_decomposed.restype = i
     lib.loco_dequant_reduce_decomposition.argtypes, lib.loco_dequant_reduce_decomposition.restype = [i, i, i], i
     lib.loco_runtime_copy.argtypes, lib.loco_runtime_copy.restype = [vp, vp, sz, vp], i
+    lib.loco_compensate_quantize_staged_codes.argtypes = [vp, i, vp, sz, i, i, f, i, vp, vp, vp]
+    lib.loco_compensate_quantize_staged_codes.restype = i
     lib.loco_stream_update3.argtypes, lib.loco_stream_update3.restype = [vp, vp, vp, sz, vp], i
     for _n in ("loco_dequant_reduce_sgd", "loco_dequant_reduce_adam", "loco_dequant_reduce_fixed_sgd",
                "loco_dequant_reduce_fixed_adam"):
@@ -615,3 +618,19 @@ def loco_stream_update3(a: torch.Tensor, b: torch.Tensor, c: torch.Tensor, strea
         raise ValueError("sizes differ")
     st = lib.loco_stream_update3(_dev_ptr(a, "a"), _dev_ptr(b, "b"), _dev_ptr(c, "c"), nbytes, _stream_handle(stream))
     _check("loco_stream_update3", st)
+
+
+def loco_compensate_quantize_staged_codes(grad, err_state, bits, block_size, beta, reset, codes_out, scales_out,
+                                          stream=None) -> None:
+    """loco_compensate_quantize (4-bit) with the codes staged through LDS into 16-byte stores (measurement aid)."""
+    lib = load_library()
+    n = grad.numel()
+    if err_state.numel() != n:
+        raise ValueError("err_state must have as many elements as grad")
+    if codes_out.numel() < (n * 4 + 7) // 8 or (block_size >= 1 and scales_out.numel() < (n + block_size - 1) // block_size):
+        raise ValueError("codes_out or scales_out too small")
+    st = lib.loco_compensate_quantize_staged_codes(
+        _dev_ptr(grad, "grad"), _grad_dtype_code(grad), _dev_ptr(err_state, "err_state", torch.float32), n, int(bits),
+        int(block_size), float(beta), 1 if reset else 0, _dev_ptr(codes_out, "codes_out", torch.uint8),
+        _dev_ptr(scales_out, "scales_out", torch.float32), _stream_handle(stream))
+    _check("loco_compensate_quantize_staged_codes", st)

@@ -118,12 +118,19 @@ struct CqArgs {
     uint8_t* codes;
     void* scales;      // float[nb], or uint16_t[nb] holding bf16 steps
     bool scales_bf16;
+    bool stage_codes;  // measurement variant: 4-bit codes leave through LDS as 16-byte stores
 };
 
 template <typename G, int BITS, int BLOCK>
 loco_status_t launch_cq(unsigned grid, hipStream_t s, const CqArgs& a) {
     const float one_minus_beta = 1.0f - a.beta;
     using Shape = CqShape<BITS>;
+    if constexpr (BITS == 4) {
+        if (a.stage_codes)
+            return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, float, true>,
+                          grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
+                          a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
+    }
     if (a.scales_bf16)   // offered without clipping only
         return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, uint16_t>,
                       grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
@@ -446,7 +453,7 @@ loco_status_t check_step_index(const int64_t* step_index_dev, int64_t reset_peri
 loco_status_t compress_block(const void* grad, loco_dtype_t grad_dtype, float clip_abs, float* err_state,
                              size_t n, int bits, int block_size, float beta, int reset,
                              const int64_t* step_index_dev, int64_t reset_period, uint8_t* codes_out,
-                             void* scales_out, bool scales_bf16, void* stream) {
+                             void* scales_out, bool scales_bf16, void* stream, bool stage_codes = false) {
     const size_t step_bytes = scales_bf16 ? sizeof(uint16_t) : sizeof(float);
     if (bits != 4 && bits != 8) return LOCO_ERR_UNSUPPORTED;
     if (!block_size_ok(block_size)) return LOCO_ERR_UNSUPPORTED;
@@ -469,7 +476,7 @@ loco_status_t compress_block(const void* grad, loco_dtype_t grad_dtype, float cl
     if (loco_status_t st = grid_for(n, per_group, &grid, kCqXcdRun ? 8 * kCqXcdRun : 1)) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const CqArgs a{grad, err_state, n, beta, reset, reinterpret_cast<const long long*>(step_index_dev),
-                   (long long)reset_period, clip_abs, codes_out, scales_out, scales_bf16};
+                   (long long)reset_period, clip_abs, codes_out, scales_out, scales_bf16, stage_codes};
     if (grad_dtype == LOCO_BF16)
         return bits == 4 ? dispatch_cq_block<bf16_t, 4>(block_size, grid, s, a) : dispatch_cq_block<bf16_t, 8>(block_size, grid, s, a);
     return bits == 4 ? dispatch_cq_block<float, 4>(block_size, grid, s, a) : dispatch_cq_block<float, 8>(block_size, grid, s, a);
@@ -601,6 +608,14 @@ loco_status_t loco_compensate_quantize(const void* grad, loco_dtype_t grad_dtype
                                        uint8_t* codes_out, float* scales_out, void* stream) {
     return compress_block(grad, grad_dtype, INFINITY, err_state, n, bits, block_size, beta, reset, nullptr, 0,
                           codes_out, scales_out, false, stream);
+}
+
+loco_status_t loco_compensate_quantize_staged_codes(const void* grad, loco_dtype_t grad_dtype, float* err_state,
+                                                    size_t n, int bits, int block_size, float beta, int reset,
+                                                    uint8_t* codes_out, float* scales_out, void* stream) {
+    if (bits != 4) return LOCO_ERR_UNSUPPORTED;
+    return compress_block(grad, grad_dtype, INFINITY, err_state, n, bits, block_size, beta, reset, nullptr, 0,
+                          codes_out, scales_out, false, stream, true);
 }
 
 loco_status_t loco_compensate_quantize_scheduled(const void* grad, loco_dtype_t grad_dtype, float* err_state,

@@ -219,7 +219,12 @@ __device__ __forceinline__ void cq_tile(const float (&h)[SLOTS][4], float (&e)[S
 // own contiguous tile.  step_index == nullptr: `reset` is the caller's flag for this step.  grid = ceil(n / (SLOTS*256*THREADS/64)), rounded up to a multiple of 8*XCDK.  A wavefront whose tile
 // lies inside [0, n) takes the vector path; the last one may take the guarded path, which
 // touches memory element by element and never at or beyond n.
-template <typename G, int BITS, int BLOCK, int SLOTS, int THREADS, bool NT, int XCDK, bool CLIP, typename S>
+// STAGE_CODES (a measurement variant, 4-bit codes): the tile's nibbles are gathered in LDS and
+// leave as 16-byte stores from a few lanes instead of 2-byte stores from all 64.  Either way a
+// wavefront hands the memory pipeline the same 128 contiguous bytes per slot; measured, the
+// staged form is 1-2 % slower (an LDS round trip in front of the store), so it is not the default.
+template <typename G, int BITS, int BLOCK, int SLOTS, int THREADS, bool NT, int XCDK, bool CLIP, typename S,
+          bool STAGE_CODES = false>
 __global__ void __launch_bounds__(THREADS)
 cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, float beta,
           float one_minus_beta, int reset, const long long* __restrict__ step_index, long long reset_period,
@@ -249,12 +254,27 @@ cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, floa
 #pragma unroll
             for (int j = 0; j < 4; ++j) h[s][j] = clip_grad<CLIP>(h[s][j], clip) + e[s][j];  // Eq. 2
         cq_tile<BITS, BLOCK, SLOTS, S16>(h, e, beta, one_minus_beta, rst, lane, pk, step);
+        if constexpr (STAGE_CODES && BITS == 4) {
+            // SLOTS * 128 bytes of codes per wavefront: lane L puts its 2 bytes of slot s at
+            // s*128 + 2L, lanes 0 .. SLOTS*8-1 then each take 16 bytes out and store them
+            __shared__ uint16_t staged[THREADS / kWave][SLOTS * kWave];
+            const uint32_t wv = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+#pragma unroll
+            for (int s = 0; s < SLOTS; ++s) staged[wv][s * kWave + lane] = (uint16_t)pk[s];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (lane < SLOTS * 8) {
+                const u32x4 v = reinterpret_cast<const u32x4*>(staged[wv])[lane];
+                vstore<NT>(reinterpret_cast<u32x4*>(codes + (tile0 >> 1)) + lane, v);
+            }
+        }
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
             vstore<NT>(reinterpret_cast<f32x4*>(err + i), f32x4{e[s][0], e[s][1], e[s][2], e[s][3]});
             if constexpr (BITS == 4) {
-                vstore<NT>(reinterpret_cast<uint16_t*>(codes + (i >> 1)), (uint16_t)pk[s]);
+                if constexpr (!STAGE_CODES) vstore<NT>(reinterpret_cast<uint16_t*>(codes + (i >> 1)), (uint16_t)pk[s]);
             } else {
                 vstore<NT>(reinterpret_cast<uint32_t*>(codes + i), pk[s]);
             }

@@ -200,6 +200,12 @@ def write_sweeps(path: str) -> None:
                  [("gradient", lambda r: r["grad"]), ("form", lambda r: r.get("form", "block")),
                   ("bits", lambda r: r["bits"]), ("block", lambda r: r.get("block_size", "-")),
                   ("ms", lambda r: r["ms"]), ("GB/s", lambda r: r["GBps"]), pct]),
+           "\n## Compensate-quantize, 4-bit: how the codes leave the wavefront\n",
+           "`direct`: 2-byte stores from all 64 lanes (the library's choice); `staged`: gathered in LDS, 16-byte stores "
+           "from 16 lanes (`loco_compensate_quantize_staged_codes`).\n",
+           table(sw["compensate_quantize_code_store_shapes"],
+                 [("block", lambda r: r["block_size"]), ("code stores", lambda r: r["code_stores"]),
+                  ("ms", lambda r: r["ms"]), ("GB/s", lambda r: r["GBps"]), pct]),
            "\n## Dequant-reduce: every work decomposition at the benchmark sizes\n",
            "`choice` marks what `loco_dequant_reduce` picks by itself.\n",
            table(sw["dequant_reduce_decompositions_benchmark_sizes"],

@@ -328,3 +328,23 @@ def test_resume_from_saved_state():
         assert torch.equal(straight[k][0], resumed[k][0]), f"step {k}: codes differ after the resume"
         assert torch.equal(straight[k][1].view(torch.int32), resumed[k][1].view(torch.int32)), f"step {k}: steps"
     assert torch.equal(e_straight.view(torch.int32), e_resumed.view(torch.int32))
+
+
+@pytest.mark.parametrize("B", [32, 64, 128, 256, 512])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_cq_staged_code_stores_give_the_same_bytes(B, dtype):
+    """The measurement variant that stages 4-bit codes through LDS: same codes, steps and state as the oracle."""
+    from paper_2407_04480_amd import loco_compensate_quantize_staged_codes
+    rng = torch.Generator(device="cpu").manual_seed(4000 + B)
+    for n in (1, 511, 512, 513, 4096, 6 * 2048 + 1031, 100_003):
+        e_t = torch.zeros(n, dtype=torch.float32, device=DEV)
+        e_host = np.zeros(n, np.float32)
+        for step in range(2):
+            g = (torch.randn(n, generator=rng) * 1e-3).to(dtype)
+            codes = torch.full((loco_code_bytes(n, 4),), 0xAA, dtype=torch.uint8, device=DEV)
+            scales = torch.full((loco_num_blocks(n, B),), -1.0, dtype=torch.float32, device=DEV)
+            loco_compensate_quantize_staged_codes(g.to(DEV), e_t, 4, B, 0.25, False, codes, scales)
+            c_ref, s_ref = oracle.compensate_quantize(workloads.as_numpy_grad(g), e_host, 4, B, 0.25)
+            torch.cuda.synchronize()
+            assert np.array_equal(codes.cpu().numpy(), c_ref), f"n={n} B={B} step={step}: codes"
+            assert bits_equal_f32(scales.cpu().numpy(), s_ref) == 0 and np.array_equal(e_t.cpu().numpy(), e_host)
