@@ -571,6 +571,29 @@ def sweep(args):
         release()
     out["dequant_reduce_fixed_many_workers"] = rows
 
+    # ---- shard size: where a call stops being bound by the launch ----
+    rows = []
+    for log2n in range(20, 29):
+        nn = 1 << log2n
+        w_ = workloads.Workload(f"size_2p{log2n}", "gauss", nn, torch.bfloat16, 4, 256, num_workers=8,
+                                segments=(("all", 0, nn),))
+        gk = workloads.gradient(w_, 0, device=dev)
+        ek = torch.zeros(nn, dtype=torch.float32, device=dev)
+        cbk, nbk = api.loco_code_bytes(nn, 4), api.loco_num_blocks(nn, 256)
+        csk = cbk + 256                       # payloads padded: strides of 2^k bytes share a memory channel
+        rck = torch.zeros(8 * csk, dtype=torch.uint8, device=dev)
+        rsk = torch.rand(8 * (nbk + 8), dtype=torch.float32, device=dev) * 1e-3
+        ok = torch.empty(nn, dtype=torch.float32, device=dev)
+        ms_cq = median_ms(lambda: api.loco_compensate_quantize(gk, ek, 4, 256, 0.25, False, rck[:cbk], rsk[:nbk], stream))
+        ms_dr = median_ms(lambda: api.loco_dequant_reduce(rck, csk, rsk, nbk + 8, 8, nn, 4, 256, ok, stream))
+        rows.append({"n": nn, "compensate_quantize": rate(10.515625, nn, ms_cq), "dequant_reduce": rate(8.125, nn, ms_dr)})
+        del gk, ek, rck, rsk, ok
+        release()
+    out["shard_size_4bit_b256_w8"] = rows
+    small, _cpu = measure(workloads.by_name("gauss_1m"), Variant(), 200, 20, load_traffic(), graph=True)
+    out["gauss_1m_step_us"] = {"eager_from_python": round(small["ms_per_step"] * 1e3, 2),
+                               "hip_graph_replay": round(small["graph_replay"]["ms_per_step"] * 1e3, 2)}
+
     # ---- host time per call (a launch-bound size), with and without the pointer checks ----
     ns = 1 << 12
     g = torch.zeros(ns, dtype=torch.bfloat16, device=dev)

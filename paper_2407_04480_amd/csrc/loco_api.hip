@@ -188,14 +188,14 @@ enum DrDecomposition { kDrAuto = 0, kDrQuad = 1, kDrQuadLaneSteps = 2, kDrWide4 
 template <int CB> struct DrWideShape { static constexpr int kThreads = CB == 16 ? 128 : 256, kInFlight = 4; };
 
 int dr_auto_decomposition(int bits, int block, int W, Epilogue kind, bool scales_bf16) {
-    if (kind != Epilogue::kStore || scales_bf16) return kDrQuad;
-    if (W >= 96) return kDrWide16;                       // every bit width and block size
+    if (scales_bf16) return kDrQuad;
+    if (W >= 96) return kDrWide16;                       // every bit width, block size and epilogue
     if (bits == 4) {
         if (block <= 128 && W >= 16) return W >= 64 ? kDrWide16 : kDrWide8;
         if (block >= 256 && W >= 64) return kDrWide16;
         return kDrQuad;
     }
-    return block >= 256 && !dr_few_workers(bits, W) ? kDrQuadLaneSteps : kDrQuad;
+    return kind == Epilogue::kStore && block >= 256 && !dr_few_workers(bits, W) ? kDrQuadLaneSteps : kDrQuad;
 }
 
 template <int BITS, int BLOCK, Epilogue EPI, typename Shape, typename S, bool LANE_STEPS, int XCD_RUN = kDrXcdRun>
@@ -210,15 +210,14 @@ loco_status_t launch_dr_quad(hipStream_t s, const DrArgs& a, const EpilogueArgs&
                   a.n, 1.0f / (float)a.W, epi);
 }
 
-template <int BITS, int BLOCK, int CB>
+template <int BITS, int BLOCK, int CB, Epilogue EPI = Epilogue::kStore>
 loco_status_t launch_dr_wide(hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
     using Shape = DrWideShape<CB>;
     constexpr size_t kUnitElems = (size_t)kWave * (CB * 8 / BITS);
     unsigned grid;
     if (loco_status_t st = grid_for(a.n, kUnitElems * (Shape::kThreads / kWave), &grid, kDrXcdRun ? 8 * kDrXcdRun : 1))
         return st;
-    return launch(dr_wide_kernel<BITS, BLOCK, CB, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun,
-                                 Epilogue::kStore, float>,
+    return launch(dr_wide_kernel<BITS, BLOCK, CB, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun, EPI, float>,
                   grid, Shape::kThreads, s, a.codes, a.code_stride, static_cast<const float*>(a.scales), a.scale_stride,
                   a.W, a.n, 1.0f / (float)a.W, epi);
 }
@@ -244,6 +243,10 @@ loco_status_t launch_dr(int how, hipStream_t s, const DrArgs& a, const EpilogueA
             if (dr_few_workers(BITS, a.W)) return launch_dr_quad<BITS, BLOCK, EPI, DrFewWorkersShape, uint16_t, false>(s, a, epi);
             return launch_dr_quad<BITS, BLOCK, EPI, DrShape<BITS>, uint16_t, false>(s, a, epi);
         }
+    }
+    if constexpr (EPI != Epilogue::kStore) {   // many payloads: the wide loads, whatever follows the sum
+        if (how == kDrWide8) return launch_dr_wide<BITS, BLOCK, 8, EPI>(s, a, epi);
+        if (how == kDrWide16) return launch_dr_wide<BITS, BLOCK, 16, EPI>(s, a, epi);
     }
     if (how != kDrQuad) return LOCO_ERR_UNSUPPORTED;
     if constexpr (!dr_updates_in_place(EPI)) {

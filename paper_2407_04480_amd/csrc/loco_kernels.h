@@ -716,10 +716,6 @@ dr_wide_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* _
         const uint32_t code_off = lane * CB;
         const uint32_t step_off = UNIFORM_STEP ? 0u : (lane * EL) / (uint32_t)BLOCK;
         float acc[EL];
-        EpilogueState<EPI> est[NQ];
-#pragma unroll
-        for (int k = 0; k < NQ; ++k)
-            epilogue_prefetch<EPI, NT>(epi, tile0 + (size_t)k * kSlot + (size_t)lane * kQuad, est[k]);
 #pragma unroll
         for (int j = 0; j < EL; ++j) acc[j] = 0.0f;
 
@@ -775,6 +771,12 @@ dr_wide_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* _
         for (; w + WU <= W; w += WU) chunk(WU);
         if (w < W) chunk(W - w);
 
+        // the optimizer state of the fused epilogues is fetched only now (its latency hides behind the
+        // transposition): held across the decode loop it would cost up to 96 registers per lane
+        EpilogueState<EPI> est[NQ];
+#pragma unroll
+        for (int k = 0; k < NQ; ++k)
+            epilogue_prefetch<EPI, NT>(epi, tile0 + (size_t)k * kSlot + (size_t)lane * kQuad, est[k]);
         // transpose: lane L holds elements [L*EL, L*EL + EL) of the unit; store k wants lane L
         // to hold elements [k*256 + 4L, +4)
         f32x4* mine = stage[wv];

@@ -228,6 +228,16 @@ def write_sweeps(path: str) -> None:
            "\n## Fixed-scale reduce with many workers (52 643 840 elements, 4-bit)\n",
            table(sw["dequant_reduce_fixed_many_workers"],
                  [("W", lambda r: r["num_workers"]), ("ms", lambda r: r["ms"]), ("GB/s", lambda r: r["GBps"]), pct]),
+           "\n## Shard size (bf16 gradient, 4-bit, B = 256, W = 8; payloads padded by 256 bytes)\n",
+           table(sw["shard_size_4bit_b256_w8"],
+                 [("n", lambda r: r["n"]), ("CQ ms", lambda r: r["compensate_quantize"]["ms"]),
+                  ("CQ % of 8 TB/s", lambda r: r["compensate_quantize"]["pct_peak"]),
+                  ("DR ms", lambda r: r["dequant_reduce"]["ms"]), ("DR % of 8 TB/s", lambda r: r["dequant_reduce"]["pct_peak"])]),
+           "\nA kernel takes about 6.5 us however small the shard; from 2^25 elements (0.35 GB per call) on, a call runs "
+           "within a few points of the full rate.\n",
+           "\n## The 2^20-element workload, one step (two kernels), microseconds\n",
+           table([sw["gauss_1m_step_us"]], [("eager, from Python", lambda r: r["eager_from_python"]),
+                                            ("replayed from a captured HIP graph (two steps per replay)", lambda r: r["hip_graph_replay"])]),
            "\n## Host time per call through the Python binding (4096 elements, 5000 calls)\n",
            table([sw["host_us_per_call_through_the_binding"]],
                  [("pointer checks on, us", lambda r: r["pointer_checks_on"]),

@@ -15,7 +15,9 @@ def bits_of(t):
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-@pytest.mark.parametrize("bits,B,W", [(4, 256, 8), (8, 64, 3), (4, 32, 1), (4, 512, 16)])
+# the last four worker counts take the wide code loads (8 or 16 bytes per lane) in front of the rounding
+@pytest.mark.parametrize("bits,B,W", [(4, 256, 8), (8, 64, 3), (4, 32, 1), (4, 512, 16), (4, 64, 20), (4, 128, 70),
+                                      (4, 256, 100), (8, 64, 97)])
 @pytest.mark.parametrize("n", [6 * 2048 + 777, 9, 2049])
 def test_block_reduce_bf16(bits, B, W, n):
     rs = np.random.default_rng(bits + B + W + n)

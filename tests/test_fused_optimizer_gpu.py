@@ -35,7 +35,9 @@ def same(name, got_t, want):
     assert np.array_equal(got, want), f"{name}: {np.count_nonzero(got != want)} of {want.size} differ"
 
 
-@pytest.mark.parametrize("bits,B,W", [(4, 256, 8), (8, 64, 3), (4, 32, 1), (4, 512, 16)])
+# the last four worker counts take the wide code loads (8 or 16 bytes per lane) in front of the epilogue
+@pytest.mark.parametrize("bits,B,W", [(4, 256, 8), (8, 64, 3), (4, 32, 1), (4, 512, 16), (4, 64, 20), (4, 128, 70),
+                                      (4, 256, 100), (8, 64, 97)])
 @pytest.mark.parametrize("n", [6 * 2048 + 777, 9, 2048])
 def test_block_reduce_with_sgd_and_adam(bits, B, W, n):
     rs = np.random.default_rng(bits * B + W + n)
