@@ -18,9 +18,12 @@ using namespace loco;
 // Launch shapes chosen by measurement on MI355X (sweeps at the 7B-shard size): slots of
 // 256 elements per wavefront, threads per workgroup, payloads in flight per lane in the
 // reduce kernel, the non-temporal hint on the streaming accesses, XCD-aware tile order.
-template <int BITS> struct CqShape;
-template <> struct CqShape<4> { static constexpr int kSlots = 2, kThreads = 128; };
-template <> struct CqShape<8> { static constexpr int kSlots = 2, kThreads = 64; };
+// Compensate-quantize: two slots per wavefront; one-wavefront workgroups for 8-bit codes and for
+// 4-bit codes with blocks up to 128 elements (about one point of HBM peak faster there), two
+// wavefronts for 4-bit codes with larger blocks (1.5 points faster there).
+template <int BITS, int BLOCK = 256> struct CqShape {
+    static constexpr int kSlots = 2, kThreads = (BITS == 8 || BLOCK <= 128) ? 64 : 128;
+};
 template <int BITS> struct DrShape;
 template <> struct DrShape<4> { static constexpr int kSlots = 2, kThreads = 128, kInFlight = 4; };
 template <> struct DrShape<8> { static constexpr int kSlots = 1, kThreads = 256, kInFlight = 4; };
@@ -44,7 +47,7 @@ struct CopyShape { static constexpr int kSlots = 1, kThreads = 64; };
 struct ReadShape { static constexpr int kSlots = 4, kThreads = 64; };
 struct Sum2Shape { static constexpr int kSlots = 1, kThreads = 64; };
 struct Update3Shape { static constexpr int kSlots = 4, kThreads = 64; };
-static_assert(CqShape<4>::kSlots % 2 == 0 && CqShape<8>::kSlots % 2 == 0,
+static_assert(CqShape<4, 512>::kSlots % 2 == 0 && CqShape<8, 512>::kSlots % 2 == 0,
               "block size 512 spans two slots of one wavefront");
 
 std::atomic<int> g_pointer_checks{1};
@@ -122,9 +125,13 @@ struct CqArgs {
 };
 
 template <typename G, int BITS, int BLOCK>
-loco_status_t launch_cq(unsigned grid, hipStream_t s, const CqArgs& a) {
+loco_status_t launch_cq(hipStream_t s, const CqArgs& a) {
     const float one_minus_beta = 1.0f - a.beta;
-    using Shape = CqShape<BITS>;
+    using Shape = CqShape<BITS, BLOCK>;
+    unsigned grid;
+    if (loco_status_t st = grid_for(a.n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid,
+                                    kCqXcdRun ? 8 * kCqXcdRun : 1))
+        return st;
     if constexpr (BITS == 4) {
         if (a.stage_codes)
             return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, float, true>,
@@ -145,13 +152,13 @@ loco_status_t launch_cq(unsigned grid, hipStream_t s, const CqArgs& a) {
 }
 
 template <typename G, int BITS>
-loco_status_t dispatch_cq_block(int block, unsigned grid, hipStream_t s, const CqArgs& a) {
+loco_status_t dispatch_cq_block(int block, hipStream_t s, const CqArgs& a) {
     switch (block) {
-        case 32: return launch_cq<G, BITS, 32>(grid, s, a);
-        case 64: return launch_cq<G, BITS, 64>(grid, s, a);
-        case 128: return launch_cq<G, BITS, 128>(grid, s, a);
-        case 256: return launch_cq<G, BITS, 256>(grid, s, a);
-        case 512: return launch_cq<G, BITS, 512>(grid, s, a);
+        case 32: return launch_cq<G, BITS, 32>(s, a);
+        case 64: return launch_cq<G, BITS, 64>(s, a);
+        case 128: return launch_cq<G, BITS, 128>(s, a);
+        case 256: return launch_cq<G, BITS, 256>(s, a);
+        case 512: return launch_cq<G, BITS, 512>(s, a);
         default: return LOCO_ERR_UNSUPPORTED;
     }
 }
@@ -473,16 +480,12 @@ loco_status_t compress_block(const void* grad, loco_dtype_t grad_dtype, float cl
     if (loco_status_t st = check_device_range(codes_out, loco_code_bytes(n, bits))) return st;
     if (loco_status_t st = check_device_range(scales_out, loco_num_blocks(n, block_size) * step_bytes))
         return st;
-    unsigned grid;
-    const size_t per_group = bits == 4 ? (size_t)kSlot * CqShape<4>::kSlots * (CqShape<4>::kThreads / kWave)
-                                       : (size_t)kSlot * CqShape<8>::kSlots * (CqShape<8>::kThreads / kWave);
-    if (loco_status_t st = grid_for(n, per_group, &grid, kCqXcdRun ? 8 * kCqXcdRun : 1)) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const CqArgs a{grad, err_state, n, beta, reset, reinterpret_cast<const long long*>(step_index_dev),
                    (long long)reset_period, clip_abs, codes_out, scales_out, scales_bf16, stage_codes};
     if (grad_dtype == LOCO_BF16)
-        return bits == 4 ? dispatch_cq_block<bf16_t, 4>(block_size, grid, s, a) : dispatch_cq_block<bf16_t, 8>(block_size, grid, s, a);
-    return bits == 4 ? dispatch_cq_block<float, 4>(block_size, grid, s, a) : dispatch_cq_block<float, 8>(block_size, grid, s, a);
+        return bits == 4 ? dispatch_cq_block<bf16_t, 4>(block_size, s, a) : dispatch_cq_block<bf16_t, 8>(block_size, s, a);
+    return bits == 4 ? dispatch_cq_block<float, 4>(block_size, s, a) : dispatch_cq_block<float, 8>(block_size, s, a);
 }
 
 loco_status_t compress_fixed(const void* grad, loco_dtype_t grad_dtype, float clip_abs, int8_t* err_state8, size_t n,
