@@ -46,8 +46,10 @@ extern "C" {
 
 typedef enum {
     LOCO_OK = 0,
-    LOCO_ERR_INVALID_ARG = 1, /* NULL pointer, beta outside [0,1] or NaN, W < 1, stride too small */
-    LOCO_ERR_UNSUPPORTED = 2, /* bits, block_size, dtype, worker count or decomposition outside the supported sets */
+    LOCO_ERR_INVALID_ARG = 1, /* NULL pointer, beta outside [0,1] or NaN, W < 1, stride too small, or so
+                                 large that W payloads would not fit the address space */
+    LOCO_ERR_UNSUPPORTED = 2, /* bits, block_size, dtype, worker count or decomposition outside the supported
+                                 sets; more than 2^48 elements, or more workgroups than one launch holds */
     LOCO_ERR_ALIGNMENT = 3,   /* a pointer or stride breaks the alignment rule of the call */
     LOCO_ERR_LAUNCH = 4,      /* the HIP runtime refused the launch */
     LOCO_ERR_BAD_POINTER = 5  /* a buffer is not device memory, or too small for the call */

@@ -7,6 +7,7 @@
 
 #include <atomic>
 #include <cmath>
+#include <cstdint>
 #include <tuple>
 #include <type_traits>
 #include <utility>
@@ -54,6 +55,9 @@ std::atomic<int> g_pointer_checks{1};
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// No device holds this many elements; refusing more keeps every byte count below in range.
+constexpr size_t kMaxElements = (size_t)1 << 48;
+
 bool block_size_ok(int b) { return b == 32 || b == 64 || b == 128 || b == 256 || b == 512; }
 
 // Is [p, p+bytes) inside one device allocation known to the runtime?
@@ -80,6 +84,14 @@ loco_status_t check_device_range(const void* p, size_t bytes) {
     const uintptr_t lo = reinterpret_cast<uintptr_t>(base), q = reinterpret_cast<uintptr_t>(p);
     if (q < lo || bytes > size || q - lo > size - bytes) return LOCO_ERR_BAD_POINTER;
     return LOCO_OK;
+}
+
+// Bytes from the start of payload 0 to the end of payload W-1: (W - 1) * stride + last, or false
+// when that does not fit a size_t (a stride or worker count that cannot describe real memory).
+bool payload_span(size_t W, size_t stride, size_t last, size_t unit, size_t* bytes) {
+    if (W > 1 && stride > (SIZE_MAX / unit - last) / (W - 1)) return false;
+    *bytes = ((W - 1) * stride + last) * unit;
+    return true;
 }
 
 // Workgroups needed for `units` at `per_group` each, rounded up to a multiple of `round`
@@ -372,6 +384,7 @@ loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const
     if (decomposition < kDrAuto || decomposition > kDrWide16) return LOCO_ERR_UNSUPPORTED;
     if (num_workers < 1) return LOCO_ERR_INVALID_ARG;
     if (n == 0) return LOCO_OK;
+    if (n > kMaxElements) return LOCO_ERR_UNSUPPORTED;
     if (!codes || !scales) return LOCO_ERR_INVALID_ARG;
     const size_t cb = loco_code_bytes(n, bits), nb = loco_num_blocks(n, block_size);
     const size_t W = (size_t)num_workers;
@@ -383,9 +396,12 @@ loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const
         if (code_stride_bytes % 16 != 0) return LOCO_ERR_ALIGNMENT;
     }
     if (!aligned(codes, 16) || !aligned(scales, 4)) return LOCO_ERR_ALIGNMENT;
-    if (loco_status_t st = check_device_range(codes, (W - 1) * code_stride_bytes + cb)) return st;
-    if (loco_status_t st = check_device_range(scales, ((W - 1) * scale_stride_elems + nb) * step_bytes))
-        return st;
+    size_t code_span, step_span;
+    if (!payload_span(W, code_stride_bytes, cb, 1, &code_span) ||
+        !payload_span(W, scale_stride_elems, nb, step_bytes, &step_span))
+        return LOCO_ERR_INVALID_ARG;
+    if (loco_status_t st = check_device_range(codes, code_span)) return st;
+    if (loco_status_t st = check_device_range(scales, step_span)) return st;
     if (loco_status_t st = check_epilogue(kind, epi, n)) return st;
     const int how = decomposition == kDrAuto ? dr_auto_decomposition(bits, block_size, num_workers, kind, scales_bf16)
                                              : decomposition;
@@ -429,6 +445,7 @@ loco_status_t reduce_fixed(const uint8_t* codes, size_t code_stride_bytes, int n
     if (num_workers < 1) return LOCO_ERR_INVALID_ARG;
     if (num_workers > (bits == 4 ? kFixedMaxWorkers4 : kFixedMaxWorkers8)) return LOCO_ERR_UNSUPPORTED;
     if (n == 0) return LOCO_OK;
+    if (n > kMaxElements) return LOCO_ERR_UNSUPPORTED;
     if (!codes) return LOCO_ERR_INVALID_ARG;
     const size_t cb = loco_code_bytes(n, bits);
     const size_t W = (size_t)num_workers;
@@ -439,7 +456,9 @@ loco_status_t reduce_fixed(const uint8_t* codes, size_t code_stride_bytes, int n
         if (code_stride_bytes % 16 != 0) return LOCO_ERR_ALIGNMENT;
     }
     if (!aligned(codes, 16)) return LOCO_ERR_ALIGNMENT;
-    if (loco_status_t st = check_device_range(codes, (W - 1) * code_stride_bytes + cb)) return st;
+    size_t code_span;
+    if (!payload_span(W, code_stride_bytes, cb, 1, &code_span)) return LOCO_ERR_INVALID_ARG;
+    if (loco_status_t st = check_device_range(codes, code_span)) return st;
     if (loco_status_t st = check_epilogue(kind, epi, n)) return st;
     const float inv_s = std::ldexp(1.0f, -log2_s), inv_w = 1.0f / (float)num_workers;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -471,6 +490,7 @@ loco_status_t compress_block(const void* grad, loco_dtype_t grad_dtype, float cl
     if (!(beta >= 0.0f && beta <= 1.0f)) return LOCO_ERR_INVALID_ARG;  // also rejects NaN
     if (!(clip_abs > 0.0f)) return LOCO_ERR_INVALID_ARG;               // NaN, zero, negative
     if (n == 0) return LOCO_OK;
+    if (n > kMaxElements) return LOCO_ERR_UNSUPPORTED;
     if (!grad || !err_state || !codes_out || !scales_out) return LOCO_ERR_INVALID_ARG;
     if (!aligned(grad, 16) || !aligned(err_state, 16) || !aligned(codes_out, 16) || !aligned(scales_out, step_bytes))
         return LOCO_ERR_ALIGNMENT;
@@ -496,6 +516,7 @@ loco_status_t compress_fixed(const void* grad, loco_dtype_t grad_dtype, float cl
     if (grad_dtype != LOCO_F32 && grad_dtype != LOCO_BF16) return LOCO_ERR_UNSUPPORTED;
     if (!(beta >= 0.0f && beta <= 1.0f)) return LOCO_ERR_INVALID_ARG;
     if (n == 0) return LOCO_OK;
+    if (n > kMaxElements) return LOCO_ERR_UNSUPPORTED;
     if (!grad || !err_state8 || !codes_out) return LOCO_ERR_INVALID_ARG;
     if (!aligned(grad, 16) || !aligned(err_state8, 16) || !aligned(codes_out, 16)) return LOCO_ERR_ALIGNMENT;
     const size_t gsz = grad_dtype == LOCO_BF16 ? 2 : 4;
@@ -527,6 +548,7 @@ loco_status_t compress_fixed_f32state(const void* grad, loco_dtype_t grad_dtype,
     if (grad_dtype != LOCO_F32 && grad_dtype != LOCO_BF16) return LOCO_ERR_UNSUPPORTED;
     if (!(beta >= 0.0f && beta <= 1.0f)) return LOCO_ERR_INVALID_ARG;
     if (n == 0) return LOCO_OK;
+    if (n > kMaxElements) return LOCO_ERR_UNSUPPORTED;
     if (!grad || !err_state || !codes_out) return LOCO_ERR_INVALID_ARG;
     if (!aligned(grad, 16) || !aligned(err_state, 16) || !aligned(codes_out, 16)) return LOCO_ERR_ALIGNMENT;
     const size_t gsz = grad_dtype == LOCO_BF16 ? 2 : 4;
@@ -593,6 +615,7 @@ int loco_set_pointer_checks(int enabled) { return g_pointer_checks.exchange(enab
 
 loco_status_t loco_error_state_init(float* err_state, size_t n, void* stream) {
     if (n == 0) return LOCO_OK;
+    if (n > kMaxElements) return LOCO_ERR_UNSUPPORTED;
     if (!err_state) return LOCO_ERR_INVALID_ARG;
     if (!aligned(err_state, 16)) return LOCO_ERR_ALIGNMENT;
     if (loco_status_t st = check_device_range(err_state, n * sizeof(float))) return st;
@@ -791,6 +814,7 @@ loco_status_t loco_step_index_advance(int64_t* step_index_dev, void* stream) {
 
 loco_status_t loco_error_state8_init(int8_t* err_state8, size_t n, void* stream) {
     if (n == 0) return LOCO_OK;
+    if (n > kMaxElements) return LOCO_ERR_UNSUPPORTED;
     if (!err_state8) return LOCO_ERR_INVALID_ARG;
     if (!aligned(err_state8, 16)) return LOCO_ERR_ALIGNMENT;
     if (loco_status_t st = check_device_range(err_state8, n)) return st;

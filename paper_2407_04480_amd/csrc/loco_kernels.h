@@ -8,9 +8,9 @@
 // Work decomposition shared by both: a lane owns 4 consecutive elements (a "quad"), so
 // one wavefront instruction moves 256 consecutive elements (a "slot": 1 KB of fp32 state,
 // 512 B of bf16 gradient) with every lane's 16 bytes adjacent to its neighbour's.  A
-// wavefront owns SLOTS consecutive slots and is scheduled on its own (one-wave
-// workgroups): measured on MI355X this shape, with the non-temporal hint on every
-// streaming access, carries the most bytes per second.  A quantisation block of 32..512
+// wavefront owns SLOTS consecutive slots, a tile of its own whatever the workgroup size
+// (one to four wavefronts per workgroup, chosen per kernel by measurement on MI355X, as is
+// the non-temporal hint on every streaming access).  A quantisation block of 32..512
 // elements lies inside one wavefront's tile, so its max-abs is an all-reduce over 8..64
 // lanes (and at most two slots) with DPP moves and lane reads; no LDS, no barrier.
 //
@@ -137,9 +137,7 @@ template <> struct Grad<bf16_t> {
     }
 };
 
-// ---- Algorithm 1 steps 1-2 on a wavefront's tile held in registers ----
-// h: compensated gradient (Eq. 2), e: old state; on return e holds the new state, packed
-// the codes of each quad (16 or 32 bits) and step the quad's block step D.
+// ---- block steps ----
 // A block step as it is stored: binary32, or bf16 bits (uint16_t).  A bf16 step is rounded
 // (nearest, ties to even, in integer arithmetic so that subnormal steps round like any
 // other) before anything uses it, so compressor, own decompressor and the receivers all
@@ -165,6 +163,9 @@ __device__ __forceinline__ float load_uniform_step(const uint16_t* base, size_t 
     return __uint_as_float((k & 1) ? (word & 0xFFFF0000u) : (word << 16));
 }
 
+// ---- Algorithm 1 steps 1-2 on a wavefront's tile held in registers ----
+// h: compensated gradient (Eq. 2), e: old state; on return e holds the new state, packed
+// the codes of each quad (16 or 32 bits) and step the quad's block step D.
 template <int BITS, int BLOCK, int SLOTS, bool S16>
 __device__ __forceinline__ void cq_tile(const float (&h)[SLOTS][4], float (&e)[SLOTS][4], float beta,
                                         float one_minus_beta, bool reset, int lane,
@@ -216,9 +217,10 @@ __device__ __forceinline__ void cq_tile(const float (&h)[SLOTS][4], float (&e)[S
 }
 
 // One wavefront per SLOTS*256 elements; THREADS/64 wavefronts per workgroup, each with its
-// own contiguous tile.  step_index == nullptr: `reset` is the caller's flag for this step.  grid = ceil(n / (SLOTS*256*THREADS/64)), rounded up to a multiple of 8*XCDK.  A wavefront whose tile
-// lies inside [0, n) takes the vector path; the last one may take the guarded path, which
-// touches memory element by element and never at or beyond n.
+// own contiguous tile.  step_index == nullptr: `reset` is the caller's flag for this step.
+// grid = ceil(n / (SLOTS*256*THREADS/64)), rounded up to a multiple of 8*XCDK.  A wavefront
+// whose tile lies inside [0, n) takes the vector path; the last one may take the guarded
+// path, which touches memory element by element and never at or beyond n.
 // STAGE_CODES (a measurement variant, 4-bit codes): the tile's nibbles are gathered in LDS and
 // leave as 16-byte stores from a few lanes instead of 2-byte stores from all 64.  Either way a
 // wavefront hands the memory pipeline the same 128 contiguous bytes per slot; measured, the
