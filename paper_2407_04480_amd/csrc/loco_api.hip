@@ -19,11 +19,11 @@ using namespace loco;
 // Launch shapes chosen by measurement on MI355X (sweeps at the 7B-shard size): slots of
 // 256 elements per wavefront, threads per workgroup, payloads in flight per lane in the
 // reduce kernel, the non-temporal hint on the streaming accesses, XCD-aware tile order.
-// Compensate-quantize: two slots per wavefront; one-wavefront workgroups for 8-bit codes and for
-// 4-bit codes with blocks up to 128 elements (about one point of HBM peak faster there), two
-// wavefronts for 4-bit codes with larger blocks (1.5 points faster there).
+// Compensate-quantize: two slots per wavefront, at most 4 wavefronts resident per SIMD (see
+// kCqWavesPerSimd); with that, one-wavefront workgroups for 8-bit codes and two wavefronts for
+// 4-bit codes measured best (up to 2 points over the other choice, and over 4 slots or 256 threads).
 template <int BITS, int BLOCK = 256> struct CqShape {
-    static constexpr int kSlots = 2, kThreads = (BITS == 8 || BLOCK <= 128) ? 64 : 128;
+    static constexpr int kSlots = 2, kThreads = BITS == 8 ? 64 : 128;
 };
 template <int BITS> struct DrShape;
 template <> struct DrShape<4> { static constexpr int kSlots = 2, kThreads = 128, kInFlight = 4; };

@@ -216,6 +216,12 @@ __device__ __forceinline__ void cq_tile(const float (&h)[SLOTS][4], float (&e)[S
     }
 }
 
+// Resident wavefronts per SIMD for the compressor.  Its registers would allow 8; with 4 (16 per
+// CU, each with two slots of every stream in flight) the kernel measured 1-3 points of HBM peak
+// faster on every gradient type, bit width and block size, with 3 it starts to lose.  Fewer
+// wavefronts touch fewer DRAM pages at a time for the five streams the kernel reads and writes.
+constexpr int kCqWavesPerSimd = 4;
+
 // One wavefront per SLOTS*256 elements; THREADS/64 wavefronts per workgroup, each with its
 // own contiguous tile.  step_index == nullptr: `reset` is the caller's flag for this step.
 // grid = ceil(n / (SLOTS*256*THREADS/64)), rounded up to a multiple of 8*XCDK.  A wavefront
@@ -227,7 +233,7 @@ __device__ __forceinline__ void cq_tile(const float (&h)[SLOTS][4], float (&e)[S
 // staged form is 1-2 % slower (an LDS round trip in front of the store), so it is not the default.
 template <typename G, int BITS, int BLOCK, int SLOTS, int THREADS, bool NT, int XCDK, bool CLIP, typename S,
           bool STAGE_CODES = false>
-__global__ void __launch_bounds__(THREADS)
+__global__ void __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, kCqWavesPerSimd)))
 cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, float beta,
           float one_minus_beta, int reset, const long long* __restrict__ step_index, long long reset_period,
           float clip, uint8_t* __restrict__ codes, S* __restrict__ scales) {
@@ -565,49 +571,80 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __rest
                         }
             }
         };
+        // 4-bit codes take the 16*D shortcut of dr_accumulate without asking whether it holds:
+        // `top` gathers the largest step seen, as a bit pattern (a negative step compares as larger
+        // than any positive one), and if that turns out to be 2^120 or more the tile is summed
+        // again from the start with the plain arithmetic.  Steps that large do not come out of the
+        // compressor for finite gradients of ordinary size, and a loop without a second path
+        // keeps the sums in the same registers from one iteration to the next.
+        uint32_t top = 0;
         auto accumulate_chunk = [&](int count, const uint32_t (&c)[WU][SLOTS], const float (&D)[WU][SLOTS]) {
-            if constexpr (BITS == 4) {
-                uint32_t top = 0;  // largest |D| of the chunk, as a bit pattern
 #pragma unroll
-                for (int u = 0; u < WU; ++u)
-                    if (u < count)
+            for (int u = 0; u < WU; ++u)
+                if (u < count)
 #pragma unroll
-                        for (int s = 0; s < SLOTS; ++s) top = umax(top, __float_as_uint(D[u][s]) & 0x7FFFFFFFu);
-                if (__builtin_expect(__any(top >= kBigStepBits), 0)) {
-#pragma unroll
-                    for (int u = 0; u < WU; ++u)
-                        if (u < count)
-#pragma unroll
-                            for (int s = 0; s < SLOTS; ++s) dr_accumulate<4>(c[u][s], D[u][s], acc[s]);
-                } else {
-#pragma unroll
-                    for (int u = 0; u < WU; ++u)
-                        if (u < count)
-#pragma unroll
-                            for (int s = 0; s < SLOTS; ++s)
-                                dr_accumulate_nibbles_x16(c[u][s], D[u][s] * 16.0f, acc[s]);
-                }
-            } else {
-#pragma unroll
-                for (int u = 0; u < WU; ++u)
-                    if (u < count)
-#pragma unroll
-                        for (int s = 0; s < SLOTS; ++s) dr_accumulate<8>(c[u][s], D[u][s], acc[s]);
-            }
+                    for (int s = 0; s < SLOTS; ++s) {
+                        if constexpr (BITS == 4) {
+                            top = umax(top, __float_as_uint(D[u][s]));
+                            dr_accumulate_nibbles_x16(c[u][s], D[u][s] * 16.0f, acc[s]);
+                        } else {
+                            dr_accumulate<8>(c[u][s], D[u][s], acc[s]);
+                        }
+                    }
         };
 
-        int w = 0;
-        for (; w + WU <= W; w += WU) {
-            uint32_t c[WU][SLOTS];
-            float D[WU][SLOTS];
-            load_chunk(WU, c, D);
-            accumulate_chunk(WU, c, D);
+        const int chunks = W / WU, rest = W % WU;
+        // From three chunks on, 4-bit codes run with two register sets: the loads of one chunk are
+        // in flight while the other is summed (2-4 points of HBM peak at W = 16..48).  With two
+        // chunks that would put all 2*WU payloads in flight at once, which measured slower; 8-bit
+        // codes gain nothing from it.
+        if (BITS == 4 && chunks >= 3) {
+            uint32_t ca[WU][SLOTS], cb2[WU][SLOTS];
+            float Da[WU][SLOTS], Db[WU][SLOTS];
+            load_chunk(WU, ca, Da);
+            int i = 1;
+            for (; i + 1 < chunks; i += 2) {
+                load_chunk(WU, cb2, Db);
+                accumulate_chunk(WU, ca, Da);
+                load_chunk(WU, ca, Da);
+                accumulate_chunk(WU, cb2, Db);
+            }
+            if (i < chunks) {
+                load_chunk(WU, cb2, Db);
+                accumulate_chunk(WU, ca, Da);
+                accumulate_chunk(WU, cb2, Db);
+            } else {
+                accumulate_chunk(WU, ca, Da);
+            }
+        } else {
+            for (int i = 0; i < chunks; ++i) {
+                uint32_t c[WU][SLOTS];
+                float D[WU][SLOTS];
+                load_chunk(WU, c, D);
+                accumulate_chunk(WU, c, D);
+            }
         }
-        if (w < W) {
+        if (rest) {
             uint32_t c[WU][SLOTS];
             float D[WU][SLOTS];
-            load_chunk(W - w, c, D);
-            accumulate_chunk(W - w, c, D);
+            load_chunk(rest, c, D);
+            accumulate_chunk(rest, c, D);
+        }
+        if constexpr (BITS == 4) {
+            if (__builtin_expect(__any(top >= kBigStepBits), 0)) {
+                const uint8_t* p = codes + tile0 * BITS / 8 + code_off;
+                const S* ps = scales + tile0 / BLOCK + (lane * kQuad) / (uint32_t)BLOCK;
+#pragma unroll
+                for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[s][j] = 0.0f;
+#pragma unroll 1
+                for (int w = 0; w < W; ++w, p += code_stride, ps += scale_stride)
+#pragma unroll
+                    for (int s = 0; s < SLOTS; ++s)
+                        dr_accumulate<4>(load_quad_codes<BITS, NT>(p + s * SLOT_CODE_BYTES),
+                                         step_from_storage(ps[(s * kSlot) / BLOCK]), acc[s]);
+            }
         }
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
@@ -721,9 +758,15 @@ dr_wide_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* _
 #pragma unroll
         for (int j = 0; j < EL; ++j) acc[j] = 0.0f;
 
-        auto chunk = [&](int count) {
-            code_t c[WU];
-            float D[WU];
+        // One chunk of `count` workers: all loads first, then the sums.  4-bit codes take the 16*D
+        // shortcut (see dr_accumulate) without asking whether it holds: `top` gathers the largest
+        // step seen, as a bit pattern (a negative step compares as larger than any positive one),
+        // and if that turns out to be 2^120 or more the unit is summed again from the start with
+        // the plain arithmetic.  Steps that large do not come out of the compressor for finite
+        // gradients of ordinary size, and a loop without a second path keeps the EL sums in the
+        // same registers from one iteration to the next.
+        uint32_t top = 0;
+        auto load_chunk = [&](int count, code_t (&c)[WU], float (&D)[WU]) {
 #pragma unroll
             for (int u = 0; u < WU; ++u) {
                 if (u < count) {
@@ -741,37 +784,64 @@ dr_wide_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* _
                     sidx += scale_stride;
                 }
             }
-            if constexpr (BITS == 4) {
-                uint32_t top = 0;
+        };
+        auto accumulate_chunk = [&](int count, const code_t (&c)[WU], const float (&D)[WU]) {
 #pragma unroll
-                for (int u = 0; u < WU; ++u)
-                    if (u < count) top = umax(top, __float_as_uint(D[u]) & 0x7FFFFFFFu);
-                if (__builtin_expect(__any(top >= kBigStepBits), 0)) {
+            for (int u = 0; u < WU; ++u)
+                if (u < count) {
+                    if constexpr (BITS == 4) {
+                        top = umax(top, __float_as_uint(D[u]));
+                        const float D16 = D[u] * 16.0f;
 #pragma unroll
-                    for (int u = 0; u < WU; ++u)
-                        if (u < count)
-#pragma unroll
-                            for (int k = 0; k < DW; ++k) dr_accumulate_dword<4>(code_dword<CB>(c[u], k), D[u], acc + k * PER_DW);
-                } else {
-#pragma unroll
-                    for (int u = 0; u < WU; ++u)
-                        if (u < count) {
-                            const float D16 = D[u] * 16.0f;
-#pragma unroll
-                            for (int k = 0; k < DW; ++k) dr_accumulate_octet_x16(code_dword<CB>(c[u], k), D16, acc + k * PER_DW);
-                        }
-                }
-            } else {
-#pragma unroll
-                for (int u = 0; u < WU; ++u)
-                    if (u < count)
+                        for (int k = 0; k < DW; ++k) dr_accumulate_octet_x16(code_dword<CB>(c[u], k), D16, acc + k * PER_DW);
+                    } else {
 #pragma unroll
                         for (int k = 0; k < DW; ++k) dr_accumulate_dword<8>(code_dword<CB>(c[u], k), D[u], acc + k * PER_DW);
-            }
+                    }
+                }
         };
-        int w = 0;
-        for (; w + WU <= W; w += WU) chunk(WU);
-        if (w < W) chunk(W - w);
+        const int chunks = W / WU, rest = W % WU;
+        // two register sets: the loads of one chunk are in flight while the other is summed
+        code_t ca[WU], cb2[WU];
+        float Da[WU], Db[WU];
+        if (chunks > 0) {
+            load_chunk(WU, ca, Da);
+            int i = 1;
+            for (; i + 1 < chunks; i += 2) {
+                load_chunk(WU, cb2, Db);
+                accumulate_chunk(WU, ca, Da);
+                load_chunk(WU, ca, Da);
+                accumulate_chunk(WU, cb2, Db);
+            }
+            if (i < chunks) {
+                load_chunk(WU, cb2, Db);
+                accumulate_chunk(WU, ca, Da);
+                accumulate_chunk(WU, cb2, Db);
+            } else {
+                accumulate_chunk(WU, ca, Da);
+            }
+        }
+        if (rest) {
+            code_t c[WU];
+            float D[WU];
+            load_chunk(rest, c, D);
+            accumulate_chunk(rest, c, D);
+        }
+        if constexpr (BITS == 4) {
+            if (__builtin_expect(__any(top >= kBigStepBits), 0)) {
+                const uint8_t* p = codes + tile0 * BITS / 8 + code_off;
+                const S* ps = scales + tile0 / BLOCK + (lane * EL) / (uint32_t)BLOCK;
+#pragma unroll
+                for (int j = 0; j < EL; ++j) acc[j] = 0.0f;
+#pragma unroll 1
+                for (int w = 0; w < W; ++w, p += code_stride, ps += scale_stride) {
+                    const code_t c = vload<NT>(reinterpret_cast<const code_t*>(p));
+                    const float D = step_from_storage(*ps);
+#pragma unroll
+                    for (int k = 0; k < DW; ++k) dr_accumulate_dword<4>(code_dword<CB>(c, k), D, acc + k * PER_DW);
+                }
+            }
+        }
 
         // the optimizer state of the fused epilogues is fetched only now (its latency hides behind the
         // transposition): held across the decode loop it would cost up to 96 registers per lane

@@ -41,9 +41,13 @@ def random_payloads(rs, W, n, bits, B, code_pad=0, scale_pad=0, huge=False):
 @pytest.mark.parametrize("B", [32, 64, 128, 256, 512])
 def test_every_decomposition_matches_the_oracle(decomposition, bits, B):
     rs = np.random.default_rng(1000 * decomposition + 10 * B + bits)
-    cases = [(1, 1), (2, 7), (3, 4097), (5, 2048 * 9), (4, 100_003), (9, 33 * 1024 + 517)]
+    cases = [(1, 1), (2, 7), (3, 4097), (5, 2048 * 9), (4, 100_003), (9, 33 * 1024 + 517), (13, 2048 * 21 + 3),
+             (27, 2048 * 5 + 77)]
     for W, n in cases:
-        codes, scales, cs, ss = random_payloads(rs, W, n, bits, B, code_pad=W % 3, scale_pad=W % 2, huge=(W == 5 and bits == 4))
+        # W = 5, 13, 27: a few steps of 2^120, for which 4-bit tiles are summed again without the shortcut
+        # (one chunk and a rest; three chunks and a rest, which is the pipelined loop; six and a rest)
+        codes, scales, cs, ss = random_payloads(rs, W, n, bits, B, code_pad=W % 3, scale_pad=W % 2,
+                                                huge=(W in (5, 13, 27) and bits == 4))
         out = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
         args = (torch.from_numpy(codes).to(DEV), cs, torch.from_numpy(scales).to(DEV), ss, W, n, bits, B, out)
         if not exists(decomposition, bits, B):
