@@ -41,8 +41,9 @@ constexpr int kCqXcdRun = 0;
 constexpr int kDrXcdRun = 32;
 constexpr int kDrNaturalOrderWorkers = 16;              // 4-bit plain reduce: from this many payloads and
 constexpr size_t kDrNaturalOrderElements = (size_t)1 << 30;   // elements on, no runs of tiles per XCD
-// Plain streaming kernels, each in the shape that measured fastest for its mix: a pure write
-// stream likes 4 KB per workgroup, a copy one wavefront per KB, a pure read 4 KB per wavefront.
+// Plain streaming kernels, each in the shape that measured fastest for its mix (together with
+// the resident wavefronts per SIMD set on the kernels): a pure write stream likes 4 KB per
+// workgroup, a copy one wavefront per KB, a pure read 4 KB per wavefront.
 struct FillShape { static constexpr int kSlots = 1, kThreads = 256; };
 struct CopyShape { static constexpr int kSlots = 1, kThreads = 64; };
 struct ReadShape { static constexpr int kSlots = 4, kThreads = 64; };

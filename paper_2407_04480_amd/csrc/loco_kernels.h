@@ -354,6 +354,14 @@ struct EpilogueArgs {
 
 template <Epilogue E> struct EpilogueState { f32x4 theta, m, v; };
 
+// Resident wavefronts per SIMD for dr_kernel by what follows the sum.  With Adam the kernel
+// updates three fp32 arrays in place on top of the payloads, a traffic mix like the
+// compressor's, and like it runs 3 points of HBM peak faster with 4 than with the 8 its
+// registers allow; the plain outputs and SGD are fastest with all 8.
+constexpr int dr_waves_per_simd(Epilogue e) { return e == Epilogue::kAdam ? 4 : 8; }
+// (Where it is 8 the kernel also asks the compiler for it: a register allocation of 65 instead
+// of 64 would silently take the eighth wavefront away.)
+
 // fp32 -> bf16, nearest with ties to even (the hardware conversion of gfx950); NaN stays NaN.
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
     const __bf16 b = (__bf16)x;
@@ -492,6 +500,7 @@ constexpr uint32_t kBigStepBits = 0x7B800000u;  // 2^120 as a binary32 bit patte
 template <int BITS, int BLOCK, int SLOTS, int THREADS, int WU, bool NT, int XCDK, Epilogue EPI, typename S,
           bool LANE_STEPS = false>
 __global__ void __launch_bounds__(THREADS)
+    __attribute__((amdgpu_waves_per_eu(dr_waves_per_simd(EPI) == 8 ? 8 : 1, dr_waves_per_simd(EPI))))
 dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __restrict__ scales,
           size_t scale_stride, int W, size_t n, float inv_w, EpilogueArgs epi) {
     constexpr size_t TILE = (size_t)kSlot * SLOTS;
@@ -597,8 +606,10 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __rest
         // From three chunks on, 4-bit codes run with two register sets: the loads of one chunk are
         // in flight while the other is summed (2-4 points of HBM peak at W = 16..48).  With two
         // chunks that would put all 2*WU payloads in flight at once, which measured slower; 8-bit
-        // codes gain nothing from it.
-        if (BITS == 4 && chunks >= 3) {
+        // codes gain nothing from it, and the variants with lane-loaded or bf16 steps would not
+        // fit the 64 registers that eight resident wavefronts per SIMD leave each.
+        constexpr bool TWO_SETS = BITS == 4 && !LANE_STEPS && sizeof(S) == 4;
+        if (TWO_SETS && chunks >= 3) {
             uint32_t ca[WU][SLOTS], cb2[WU][SLOTS];
             float Da[WU][SLOTS], Db[WU][SLOTS];
             load_chunk(WU, ca, Da);
@@ -893,8 +904,9 @@ __global__ void step_index_kernel(long long* step_index, long long value, int ad
 }
 
 // ---- helpers: zero fill of the state, plain streaming kernels (16 bytes per lane and slot) ----
+constexpr int kFillWavesPerSimd = 3;   // see stream_waves_per_simd
 template <int SLOTS, int THREADS, bool NT>
-__global__ void __launch_bounds__(THREADS)
+__global__ void __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, kFillWavesPerSimd)))
 fill_zero_kernel(float* __restrict__ dst, size_t n) {
     const int lane = threadIdx.x & (kWave - 1);
     const size_t wave = (size_t)blockIdx.x * (THREADS / kWave) + (threadIdx.x >> 6);
@@ -915,8 +927,14 @@ fill_zero_kernel(float* __restrict__ dst, size_t n) {
 // a lane's 16 bytes xor to `never`, so that the loads cannot be dropped; kFill writes zeros;
 // kSum2 dst = src + src2 word by word (two read streams, one write stream).
 enum class StreamMode { kCopy, kRead, kFill, kSum2 };
+// Resident wavefronts per SIMD at which each stream measured fastest in its launch shape: a pure
+// write stream wants few (90 % of HBM peak with 2-3 against 82 % with 8), a pure read stream 6
+// (94 % against 89 %), two reads and a write 5, the copy all 8.
+constexpr int stream_waves_per_simd(StreamMode m) {
+    return m == StreamMode::kFill ? kFillWavesPerSimd : m == StreamMode::kRead ? 6 : m == StreamMode::kSum2 ? 5 : 8;
+}
 template <StreamMode MODE, int SLOTS, int THREADS, bool NT>
-__global__ void __launch_bounds__(THREADS)
+__global__ void __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, stream_waves_per_simd(MODE))))
 stream_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, const u32x4* __restrict__ src2,
               size_t n16, uint32_t never) {
     const int lane = threadIdx.x & (kWave - 1);
