@@ -359,8 +359,6 @@ template <Epilogue E> struct EpilogueState { f32x4 theta, m, v; };
 // compressor's, and like it runs 3 points of HBM peak faster with 4 than with the 8 its
 // registers allow; the plain outputs and SGD are fastest with all 8.
 constexpr int dr_waves_per_simd(Epilogue e) { return e == Epilogue::kAdam ? 4 : 8; }
-// (Where it is 8 the kernel also asks the compiler for it: a register allocation of 65 instead
-// of 64 would silently take the eighth wavefront away.)
 
 // fp32 -> bf16, nearest with ties to even (the hardware conversion of gfx950); NaN stays NaN.
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
@@ -499,8 +497,7 @@ constexpr uint32_t kBigStepBits = 0x7B800000u;  // 2^120 as a binary32 bit patte
 // load shared by the wavefront.
 template <int BITS, int BLOCK, int SLOTS, int THREADS, int WU, bool NT, int XCDK, Epilogue EPI, typename S,
           bool LANE_STEPS = false>
-__global__ void __launch_bounds__(THREADS)
-    __attribute__((amdgpu_waves_per_eu(dr_waves_per_simd(EPI) == 8 ? 8 : 1, dr_waves_per_simd(EPI))))
+__global__ void __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, dr_waves_per_simd(EPI))))
 dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __restrict__ scales,
           size_t scale_stride, int W, size_t n, float inv_w, EpilogueArgs epi) {
     constexpr size_t TILE = (size_t)kSlot * SLOTS;
