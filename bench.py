@@ -519,6 +519,15 @@ def sweep(args):
                 staged.append({"grad": "bfloat16", "bits": 4, "block_size": B, "code_stores": name,
                                **rate(g.element_size() + 8 + 0.5 + 4 / B, n, ms)})
     out["compensate_quantize_code_store_shapes"] = staged
+    # resident wavefronts per SIMD: the library's 4 against 6 and the 8 the registers allow
+    resident = []
+    for bits, B in ((4, 256), (8, 64), (4, 128), (4, 32)):
+        for waves in (4, 6, 8):
+            ms = median_ms(lambda: api.loco_compensate_quantize_resident(g16, err, bits, B, 0.25, False, codes, scales,
+                                                                         waves, stream))
+            resident.append({"grad": "bfloat16", "bits": bits, "block_size": B, "waves_per_simd": waves,
+                             **rate(g16.element_size() + 8 + bits / 8 + 4 / B, n, ms)})
+    out["compensate_quantize_resident_wavefronts"] = resident
     del g16, g32, err, err8, codes, scales
     release()
 

@@ -319,6 +319,17 @@ loco_status_t loco_compensate_quantize_staged_codes(const void *grad, loco_dtype
                                                     float *scales_out, void *stream);
 
 /*
+ * Measurement aid: loco_compensate_quantize with the number of wavefronts resident per SIMD
+ * chosen by the caller: 4 (what loco_compensate_quantize itself runs with), 6 or 8 (all that the
+ * kernel's registers allow); anything else is LOCO_ERR_UNSUPPORTED.  Same arithmetic, same bytes.
+ * It exists so that the comparison behind the library's choice can be repeated (4 is 1-3 % faster).
+ */
+loco_status_t loco_compensate_quantize_resident(const void *grad, loco_dtype_t grad_dtype,
+                                                float *err_state, size_t n, int bits, int block_size,
+                                                float beta, int reset, uint8_t *codes_out,
+                                                float *scales_out, int waves_per_simd, void *stream);
+
+/*
  * Measurement and tuning aid: loco_dequant_reduce with the work decomposition chosen by the
  * caller instead of by the library (same arithmetic, same result bit for bit):
  *   0  what loco_dequant_reduce picks (see loco_dequant_reduce_decomposition)

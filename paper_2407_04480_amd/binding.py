@@ -58,6 +58,7 @@ EXPORTS = (
     "loco_runtime_copy",
     "loco_stream_update3",
     "loco_compensate_quantize_staged_codes",
+    "loco_compensate_quantize_resident",
 )
 
 _lib = None
@@ -139,6 +140,8 @@ def load_library(path: Optional[str] = None):
     lib.loco_runtime_copy.argtypes, lib.loco_runtime_copy.restype = [vp, vp, sz, vp], i
     lib.loco_compensate_quantize_staged_codes.argtypes = [vp, i, vp, sz, i, i, f, i, vp, vp, vp]
     lib.loco_compensate_quantize_staged_codes.restype = i
+    lib.loco_compensate_quantize_resident.argtypes = [vp, i, vp, sz, i, i, f, i, vp, vp, i, vp]
+    lib.loco_compensate_quantize_resident.restype = i
     lib.loco_stream_update3.argtypes, lib.loco_stream_update3.restype = [vp, vp, vp, sz, vp], i
     for _n in ("loco_dequant_reduce_sgd", "loco_dequant_reduce_adam", "loco_dequant_reduce_fixed_sgd",
                "loco_dequant_reduce_fixed_adam"):
@@ -634,3 +637,20 @@ def loco_compensate_quantize_staged_codes(grad, err_state, bits, block_size, bet
         int(block_size), float(beta), 1 if reset else 0, _dev_ptr(codes_out, "codes_out", torch.uint8),
         _dev_ptr(scales_out, "scales_out", torch.float32), _stream_handle(stream))
     _check("loco_compensate_quantize_staged_codes", st)
+
+
+def loco_compensate_quantize_resident(grad, err_state, bits, block_size, beta, reset, codes_out, scales_out,
+                                      waves_per_simd, stream=None) -> None:
+    """loco_compensate_quantize with 4, 6 or 8 wavefronts resident per SIMD (measurement aid)."""
+    lib = load_library()
+    n = grad.numel()
+    if err_state.numel() != n:
+        raise ValueError("err_state must have as many elements as grad")
+    if bits in (4, 8) and block_size >= 1 and (codes_out.numel() < (n * bits + 7) // 8
+                                               or scales_out.numel() < (n + block_size - 1) // block_size):
+        raise ValueError("codes_out or scales_out too small")
+    st = lib.loco_compensate_quantize_resident(
+        _dev_ptr(grad, "grad"), _grad_dtype_code(grad), _dev_ptr(err_state, "err_state", torch.float32), n, int(bits),
+        int(block_size), float(beta), 1 if reset else 0, _dev_ptr(codes_out, "codes_out", torch.uint8),
+        _dev_ptr(scales_out, "scales_out", torch.float32), int(waves_per_simd), _stream_handle(stream))
+    _check("loco_compensate_quantize_resident", st)

@@ -135,6 +135,7 @@ struct CqArgs {
     void* scales;      // float[nb], or uint16_t[nb] holding bf16 steps
     bool scales_bf16;
     bool stage_codes;  // measurement variant: 4-bit codes leave through LDS as 16-byte stores
+    int waves;         // measurement variant: resident wavefronts per SIMD (0: the library's own)
 };
 
 template <typename G, int BITS, int BLOCK>
@@ -150,6 +151,15 @@ loco_status_t launch_cq(hipStream_t s, const CqArgs& a) {
             return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, float, true>,
                           grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
                           a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
+    }
+    if (a.waves == 6 || a.waves == 8) {
+        if (a.waves == 6)
+            return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, float, false, 6>,
+                          grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
+                          a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
+        return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, float, false, 8>,
+                      grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
+                      a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
     }
     if (a.scales_bf16)   // offered without clipping only
         return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, uint16_t>,
@@ -483,7 +493,8 @@ loco_status_t check_step_index(const int64_t* step_index_dev, int64_t reset_peri
 loco_status_t compress_block(const void* grad, loco_dtype_t grad_dtype, float clip_abs, float* err_state,
                              size_t n, int bits, int block_size, float beta, int reset,
                              const int64_t* step_index_dev, int64_t reset_period, uint8_t* codes_out,
-                             void* scales_out, bool scales_bf16, void* stream, bool stage_codes = false) {
+                             void* scales_out, bool scales_bf16, void* stream, bool stage_codes = false,
+                             int waves = 0) {
     const size_t step_bytes = scales_bf16 ? sizeof(uint16_t) : sizeof(float);
     if (bits != 4 && bits != 8) return LOCO_ERR_UNSUPPORTED;
     if (!block_size_ok(block_size)) return LOCO_ERR_UNSUPPORTED;
@@ -503,7 +514,7 @@ loco_status_t compress_block(const void* grad, loco_dtype_t grad_dtype, float cl
         return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const CqArgs a{grad, err_state, n, beta, reset, reinterpret_cast<const long long*>(step_index_dev),
-                   (long long)reset_period, clip_abs, codes_out, scales_out, scales_bf16, stage_codes};
+                   (long long)reset_period, clip_abs, codes_out, scales_out, scales_bf16, stage_codes, waves};
     if (grad_dtype == LOCO_BF16)
         return bits == 4 ? dispatch_cq_block<bf16_t, 4>(block_size, s, a) : dispatch_cq_block<bf16_t, 8>(block_size, s, a);
     return bits == 4 ? dispatch_cq_block<float, 4>(block_size, s, a) : dispatch_cq_block<float, 8>(block_size, s, a);
@@ -646,6 +657,16 @@ loco_status_t loco_compensate_quantize_staged_codes(const void* grad, loco_dtype
     if (bits != 4) return LOCO_ERR_UNSUPPORTED;
     return compress_block(grad, grad_dtype, INFINITY, err_state, n, bits, block_size, beta, reset, nullptr, 0,
                           codes_out, scales_out, false, stream, true);
+}
+
+loco_status_t loco_compensate_quantize_resident(const void* grad, loco_dtype_t grad_dtype, float* err_state,
+                                                size_t n, int bits, int block_size, float beta, int reset,
+                                                uint8_t* codes_out, float* scales_out, int waves_per_simd,
+                                                void* stream) {
+    if (waves_per_simd != kCqWavesPerSimd && waves_per_simd != 6 && waves_per_simd != 8) return LOCO_ERR_UNSUPPORTED;
+    return compress_block(grad, grad_dtype, INFINITY, err_state, n, bits, block_size, beta, reset, nullptr, 0,
+                          codes_out, scales_out, false, stream, false,
+                          waves_per_simd == kCqWavesPerSimd ? 0 : waves_per_simd);
 }
 
 loco_status_t loco_compensate_quantize_scheduled(const void* grad, loco_dtype_t grad_dtype, float* err_state,

@@ -221,6 +221,7 @@ __device__ __forceinline__ void cq_tile(const float (&h)[SLOTS][4], float (&e)[S
 // faster on every gradient type, bit width and block size, with 3 it starts to lose.  Fewer
 // wavefronts touch fewer DRAM pages at a time for the five streams the kernel reads and writes.
 constexpr int kCqWavesPerSimd = 4;
+// (WAVES on the kernel: other values exist only behind the measurement call that repeats the comparison.)
 
 // One wavefront per SLOTS*256 elements; THREADS/64 wavefronts per workgroup, each with its
 // own contiguous tile.  step_index == nullptr: `reset` is the caller's flag for this step.
@@ -232,8 +233,8 @@ constexpr int kCqWavesPerSimd = 4;
 // wavefront hands the memory pipeline the same 128 contiguous bytes per slot; measured, the
 // staged form is 1-2 % slower (an LDS round trip in front of the store), so it is not the default.
 template <typename G, int BITS, int BLOCK, int SLOTS, int THREADS, bool NT, int XCDK, bool CLIP, typename S,
-          bool STAGE_CODES = false>
-__global__ void __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, kCqWavesPerSimd)))
+          bool STAGE_CODES = false, int WAVES = kCqWavesPerSimd>
+__global__ void __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, WAVES)))
 cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, float beta,
           float one_minus_beta, int reset, const long long* __restrict__ step_index, long long reset_period,
           float clip, uint8_t* __restrict__ codes, S* __restrict__ scales) {

@@ -206,6 +206,13 @@ def write_sweeps(path: str) -> None:
            table(sw["compensate_quantize_code_store_shapes"],
                  [("block", lambda r: r["block_size"]), ("code stores", lambda r: r["code_stores"]),
                   ("ms", lambda r: r["ms"]), ("GB/s", lambda r: r["GBps"]), pct]),
+           "\n## Compensate-quantize: wavefronts resident per SIMD (bf16 gradient, 7B-shard size)\n",
+           "4 is what `loco_compensate_quantize` runs with; 6 and 8 (all that the kernel's registers allow) through "
+           "`loco_compensate_quantize_resident`.\n",
+           table(sw.get("compensate_quantize_resident_wavefronts", []),
+                 [("bits", lambda r: r["bits"]), ("block", lambda r: r["block_size"]),
+                  ("wavefronts per SIMD", lambda r: r["waves_per_simd"]),
+                  ("ms", lambda r: r["ms"]), ("GB/s", lambda r: r["GBps"]), pct]),
            "\n## Dequant-reduce: every work decomposition at the benchmark sizes\n",
            "`choice` marks what `loco_dequant_reduce` picks by itself.\n",
            table(sw["dequant_reduce_decompositions_benchmark_sizes"],

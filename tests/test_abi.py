@@ -95,6 +95,9 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.loco_dequant_reduce_decomposition(8, 4, 256) == 1 and lib.loco_dequant_reduce_decomposition(128, 8, 64) == 5 and lib.loco_dequant_reduce_decomposition(8, 5, 256) == -1
     assert lib.loco_reset_due(0, 512) == 1 and lib.loco_reset_due(512, 512) == 1 and lib.loco_reset_due(5, 512) == 0
     assert lib.loco_runtime_copy(null, one, 16, null) == 1 and lib.loco_runtime_copy(null, null, 0, null) == 0
+    # the residency variant exists for 4, 6 and 8 wavefronts per SIMD only
+    assert lib.loco_compensate_quantize_resident(one, 0, one, 8, 4, 256, 0.25, 0, one, one, 5, null) == 2
+    assert lib.loco_compensate_quantize_resident(null, 0, null, 0, 4, 256, 0.25, 0, null, null, 8, null) == 0
     # sizes no device can hold, and strides whose W payloads would wrap the address space
     assert lib.loco_compensate_quantize(one, 0, one, (1 << 48) + 1, 4, 256, 0.25, 0, one, one, null) == 2
     assert lib.loco_dequant_reduce(one, 1 << 50, one, 1 << 50, 2, (1 << 48) + 1, 4, 256, one, null) == 2

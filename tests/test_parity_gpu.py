@@ -330,6 +330,33 @@ def test_resume_from_saved_state():
     assert torch.equal(e_straight.view(torch.int32), e_resumed.view(torch.int32))
 
 
+@pytest.mark.parametrize("bits,B", [(4, 32), (4, 256), (8, 64), (8, 512)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_cq_with_other_residency_gives_the_same_bytes(bits, B, dtype):
+    """The measurement variant with 6 or 8 resident wavefronts per SIMD: same codes, steps and state as the
+    oracle; values the library does not build are refused."""
+    from paper_2407_04480_amd import loco_compensate_quantize_resident
+    rng = torch.Generator(device="cpu").manual_seed(4100 + B + bits)
+    for waves in (4, 6, 8):
+        for n in (1, 513, 6 * 2048 + 1031, 100_003):
+            e_t = torch.zeros(n, dtype=torch.float32, device=DEV)
+            e_host = np.zeros(n, np.float32)
+            for step in range(2):
+                g = (torch.randn(n, generator=rng) * 1e-3).to(dtype)
+                codes = torch.full((loco_code_bytes(n, bits),), 0xAA, dtype=torch.uint8, device=DEV)
+                scales = torch.full((loco_num_blocks(n, B),), -1.0, dtype=torch.float32, device=DEV)
+                loco_compensate_quantize_resident(g.to(DEV), e_t, bits, B, 0.25, False, codes, scales, waves)
+                c_ref, s_ref = oracle.compensate_quantize(workloads.as_numpy_grad(g), e_host, bits, B, 0.25)
+                torch.cuda.synchronize()
+                assert np.array_equal(codes.cpu().numpy(), c_ref), f"waves={waves} n={n} step={step}: codes"
+                assert bits_equal_f32(scales.cpu().numpy(), s_ref) == 0 and np.array_equal(e_t.cpu().numpy(), e_host)
+    g = torch.zeros(512, device=DEV)
+    with pytest.raises(LocoError) as ei:
+        loco_compensate_quantize_resident(g, torch.zeros_like(g), 4, 256, 0.25, False,
+                                          torch.zeros(256, dtype=torch.uint8, device=DEV), torch.zeros(2, device=DEV), 5)
+    assert ei.value.status == 2
+
+
 @pytest.mark.parametrize("B", [32, 64, 128, 256, 512])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_cq_staged_code_stores_give_the_same_bytes(B, dtype):
