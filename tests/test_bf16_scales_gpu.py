@@ -83,6 +83,8 @@ def test_dequant_reduce_bf16_scales(bits, B, W, n):
     top = 0xFA if W == 1 else 0xF0
     steps = ((rs.integers(1, top, W * sstride).astype(np.uint16) << 7) | rs.integers(0, 128, W * sstride).astype(np.uint16))
     steps[rs.random(W * sstride) < 0.1] = 0
+    if 1 < W <= 9:      # a few steps of 2^120: 4-bit tiles that meet one are summed again without the 16*D shortcut
+        steps[rs.random(W * sstride) < 0.02] = 0x7B80
     out = torch.full((n,), 7.0, dtype=torch.float32, device=DEV)
     st = torch.from_numpy(steps.view(np.int16)).view(torch.bfloat16).to(DEV)
     loco_dequant_reduce_bf16_scales(torch.from_numpy(codes).to(DEV), cstride, st, sstride, W, n, bits, B, out)
