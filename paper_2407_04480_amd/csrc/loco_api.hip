@@ -442,6 +442,12 @@ loco_status_t launch_fixed_dr(int bits, hipStream_t s, const uint8_t* codes, siz
     if (bits == 4)
         return launch(fixed_dr_kernel<4, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI, kRun>, grid,
                       Shape::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
+    if constexpr (EPI == Epilogue::kStore) {
+        if (W >= kFixedDr8ManyWorkers)
+            return launch(fixed_dr_kernel<8, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI, kRun,
+                                          kFixedDr8ManyWorkersWaves>,
+                          grid, Shape::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
+    }
     return launch(fixed_dr_kernel<8, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI, kRun>, grid,
                   Shape::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
 }

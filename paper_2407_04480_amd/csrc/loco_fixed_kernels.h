@@ -255,9 +255,13 @@ fixed_f32_cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size
 // Resident wavefronts per SIMD: with a fused optimizer (arrays updated in place) 4 measured
 // 3-6 points of HBM peak faster than the 8 the registers allow, the plain outputs like all 8.
 constexpr int fixed_dr_waves_per_simd(Epilogue e) { return (e == Epilogue::kSgd || e == Epilogue::kAdam) ? 4 : 8; }
+// The fp32 output of 8-bit payloads, from 4 of them on, also likes 4 (80 % against 76.5 % at W = 8, +1 to
+// +3 points at W = 4..32), while with one or two payloads it wants all 8; the host picks by W.
+constexpr int kFixedDr8ManyWorkersWaves = 4, kFixedDr8ManyWorkers = 4;
 
-template <int BITS, int SLOTS, int THREADS, int WU, bool NT, Epilogue EPI, int XCDK = 0>
-__global__ void __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, fixed_dr_waves_per_simd(EPI))))
+template <int BITS, int SLOTS, int THREADS, int WU, bool NT, Epilogue EPI, int XCDK = 0,
+          int WAVES = fixed_dr_waves_per_simd(EPI)>
+__global__ void __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, WAVES)))
 fixed_dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, int W, size_t n, float inv_s,
                 float inv_w, EpilogueArgs epi) {
     constexpr size_t TILE = (size_t)kSlot * SLOTS;

@@ -85,7 +85,7 @@ def test_fixed_cq_scales_beta_reset_and_saturation(log2_s):
 
 
 @pytest.mark.parametrize("bits", [4, 8])
-@pytest.mark.parametrize("W", [1, 2, 3, 8, 15, 16, 17, 33, 257, 300])
+@pytest.mark.parametrize("W", [1, 2, 3, 4, 8, 15, 16, 17, 33, 257, 300])
 def test_fixed_dequant_reduce(bits, W):
     """Random codes (every value, including the most negative), padded strides, ragged n.
     W above 16 (4-bit) and above 256 (8-bit) crosses the widening of the packed sums."""
