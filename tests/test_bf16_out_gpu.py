@@ -15,7 +15,8 @@ def bits_of(t):
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-# the last four worker counts take the wide code loads (8 or 16 bytes per lane) in front of the rounding
+# 4-bit codes take the wide code loads (16 bytes per lane) in front of the rounding at every worker count,
+# 8-bit codes the quad layout up to W = 95
 @pytest.mark.parametrize("bits,B,W", [(4, 256, 8), (8, 64, 3), (4, 32, 1), (4, 512, 16), (4, 64, 20), (4, 128, 70),
                                       (4, 256, 100), (8, 64, 97)])
 @pytest.mark.parametrize("n", [6 * 2048 + 777, 9, 2049])
