@@ -442,13 +442,14 @@ __device__ __forceinline__ void epilogue_element(const EpilogueArgs& a, size_t i
 // One worker's contribution to one quad: acc_j = acc_j + (float) q_j * D, j = 0..3, where c
 // holds the quad's codes in its low 16 (4-bit) or 32 (8-bit) bits.
 //
-// This kernel is as close to the VALU limit as to the HBM limit (W decodes per output
-// element), so the decode is kept to three instructions per element and worker:
+// W decodes per output element make the arithmetic a visible share of this kernel's time (at
+// W = 8 the vector ALUs are busy two thirds of it), so the decode is kept to three instructions
+// per element and worker:
 //   8-bit  v_cvt_f32_i32 with a sign-extending byte select, v_mul, v_add;
 //   4-bit  v_cvt_off_f32_i4, which maps a two's complement nibble q straight to the float
 //          q/16, then v_mul by 16*D, v_add.  (q/16) * (16 D) is q * D with the same single
-//          rounding as long as 16 D does not overflow, so the caller takes this path only
-//          when D < 2^120 and the plain one otherwise.
+//          rounding as long as 16 D does not overflow; the kernels take this path first and
+//          sum a tile again with the plain one if a step of 2^120 or more was met.
 template <int BITS>
 __device__ __forceinline__ void dr_accumulate(uint32_t c, float D, float (&acc)[4]) {
 #pragma unroll
