@@ -29,9 +29,14 @@ template <int BITS> struct DrShape;
 template <> struct DrShape<4> { static constexpr int kSlots = 2, kThreads = 128, kInFlight = 4; };
 template <> struct DrShape<8> { static constexpr int kSlots = 1, kThreads = 256, kInFlight = 4; };
 // With few workers the reduce is mostly a write stream, which measured 3-9 % faster with
-// 2 KB of output per wavefront and 8 KB per workgroup.
+// 2 KB of output per wavefront and 8 KB per workgroup; with two or three payloads of 4-bit codes
+// 4 KB per wavefront (B = 256, W = 2: 80 % of HBM peak against 73 %; W = 3: 79 against 77; B = 64 the
+// same either way); a single payload of 8-bit codes with 6 resident wavefronts per SIMD instead of 8
+// (82.6 % against 79.2 %).
 struct DrFewWorkersShape { static constexpr int kSlots = 2, kThreads = 256, kInFlight = 4; };
+struct DrTwoOrThreeWorkersShape { static constexpr int kSlots = 4, kThreads = 256, kInFlight = 4; };
 constexpr bool dr_few_workers(int bits, int W) { return bits == 4 ? W <= 4 : W == 1; }
+constexpr int kDrOnePayload8BitWaves = 6;
 constexpr bool kNonTemporal = true;
 // Consecutive workgroups' tiles per XCD (see wave_tile_index).  Measured: compensate-
 // quantize is fastest with the hardware's own round robin (0); dequant-reduce loses
@@ -237,8 +242,10 @@ loco_status_t launch_dr_quad(hipStream_t s, const DrArgs& a, const EpilogueArgs&
     if (loco_status_t st = grid_for(a.n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid,
                                     XCD_RUN ? 8 * XCD_RUN : 1))
         return st;
+    constexpr int kWaves = (BITS == 8 && std::is_same_v<Shape, DrFewWorkersShape> && !dr_updates_in_place(EPI))
+                               ? kDrOnePayload8BitWaves : dr_waves_per_simd(EPI);
     return launch(dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, XCD_RUN, EPI, S,
-                            LANE_STEPS>,
+                            LANE_STEPS, kWaves>,
                   grid, Shape::kThreads, s, a.codes, a.code_stride, static_cast<const S*>(a.scales), a.scale_stride, a.W,
                   a.n, 1.0f / (float)a.W, epi);
 }
@@ -283,6 +290,9 @@ loco_status_t launch_dr(int how, hipStream_t s, const DrArgs& a, const EpilogueA
     }
     if (how != kDrQuad) return LOCO_ERR_UNSUPPORTED;
     if constexpr (!dr_updates_in_place(EPI)) {
+        if constexpr (BITS == 4 && BLOCK <= 256) {   // (blocks of 512 elements lose 7 points with it)
+            if (a.W == 2 || a.W == 3) return launch_dr_quad<BITS, BLOCK, EPI, DrTwoOrThreeWorkersShape, float, false>(s, a, epi);
+        }
         if (dr_few_workers(BITS, a.W)) return launch_dr_quad<BITS, BLOCK, EPI, DrFewWorkersShape, float, false>(s, a, epi);
     }
     if constexpr (EPI == Epilogue::kStore && BITS == 4) {
@@ -442,6 +452,26 @@ loco_status_t launch_fixed_dr(int bits, hipStream_t s, const uint8_t* codes, siz
     unsigned grid;
     if (loco_status_t st = grid_for(n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid, kRun ? 8 * kRun : 1))
         return st;
+    if constexpr (EPI == Epilogue::kStore) {
+        // few payloads, as for the block form: 4 KB of output per wavefront for two or three payloads of
+        // 4-bit codes (78 % of HBM peak against 69 %), 6 resident wavefronts for one payload of 8-bit codes
+        // (82 % against 71 %)
+        using Few = DrTwoOrThreeWorkersShape;
+        if (bits == 4 && (W == 2 || W == 3)) {
+            if (loco_status_t st = grid_for(n, (size_t)kSlot * Few::kSlots * (Few::kThreads / kWave), &grid, kRun ? 8 * kRun : 1))
+                return st;
+            return launch(fixed_dr_kernel<4, Few::kSlots, Few::kThreads, Few::kInFlight, kNonTemporal, EPI, kRun>, grid,
+                          Few::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
+        }
+        using One = DrFewWorkersShape;
+        if (bits == 8 && W == 1) {
+            if (loco_status_t st = grid_for(n, (size_t)kSlot * One::kSlots * (One::kThreads / kWave), &grid, kRun ? 8 * kRun : 1))
+                return st;
+            return launch(fixed_dr_kernel<8, One::kSlots, One::kThreads, One::kInFlight, kNonTemporal, EPI, kRun,
+                                          kDrOnePayload8BitWaves>,
+                          grid, One::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
+        }
+    }
     if (bits == 4)
         return launch(fixed_dr_kernel<4, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI, kRun>, grid,
                       Shape::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);

@@ -498,8 +498,8 @@ constexpr uint32_t kBigStepBits = 0x7B800000u;  // 2^120 as a binary32 bit patte
 // 32-bit lane offset; with BLOCK >= 256 a slot lies in one block, so its step is a scalar
 // load shared by the wavefront.
 template <int BITS, int BLOCK, int SLOTS, int THREADS, int WU, bool NT, int XCDK, Epilogue EPI, typename S,
-          bool LANE_STEPS = false>
-__global__ void __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, dr_waves_per_simd(EPI))))
+          bool LANE_STEPS = false, int WAVES = dr_waves_per_simd(EPI)>
+__global__ void __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, WAVES)))
 dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __restrict__ scales,
           size_t scale_stride, int W, size_t n, float inv_w, EpilogueArgs epi) {
     constexpr size_t TILE = (size_t)kSlot * SLOTS;
