@@ -31,12 +31,12 @@ template <> struct DrShape<8> { static constexpr int kSlots = 1, kThreads = 256,
 // With few workers the reduce is mostly a write stream, which measured 3-9 % faster with
 // 2 KB of output per wavefront and 8 KB per workgroup; with two or three payloads of 4-bit codes
 // 4 KB per wavefront (B = 256, W = 2: 80 % of HBM peak against 73 %; W = 3: 79 against 77; B = 64 the
-// same either way); a single payload of 8-bit codes with 6 resident wavefronts per SIMD instead of 8
-// (82.6 % against 79.2 %).
+// same either way); up to three payloads of 8-bit codes with 6 resident wavefronts per SIMD instead of
+// 8 (W = 1: 82.6 % against 79.2 %; W = 2, 3: 80-83 % against 75-79 % in the many-payload shape).
 struct DrFewWorkersShape { static constexpr int kSlots = 2, kThreads = 256, kInFlight = 4; };
 struct DrTwoOrThreeWorkersShape { static constexpr int kSlots = 4, kThreads = 256, kInFlight = 4; };
-constexpr bool dr_few_workers(int bits, int W) { return bits == 4 ? W <= 4 : W == 1; }
-constexpr int kDrOnePayload8BitWaves = 6;
+constexpr bool dr_few_workers(int bits, int W) { return bits == 4 ? W <= 4 : W <= 3; }
+constexpr int kDrFewPayloads8BitWaves = 6;
 constexpr bool kNonTemporal = true;
 // Consecutive workgroups' tiles per XCD (see wave_tile_index).  Measured: compensate-
 // quantize is fastest with the hardware's own round robin (0); dequant-reduce loses
@@ -243,7 +243,7 @@ loco_status_t launch_dr_quad(hipStream_t s, const DrArgs& a, const EpilogueArgs&
                                     XCD_RUN ? 8 * XCD_RUN : 1))
         return st;
     constexpr int kWaves = (BITS == 8 && std::is_same_v<Shape, DrFewWorkersShape> && !dr_updates_in_place(EPI))
-                               ? kDrOnePayload8BitWaves : dr_waves_per_simd(EPI);
+                               ? kDrFewPayloads8BitWaves : dr_waves_per_simd(EPI);
     return launch(dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, XCD_RUN, EPI, S,
                             LANE_STEPS, kWaves>,
                   grid, Shape::kThreads, s, a.codes, a.code_stride, static_cast<const S*>(a.scales), a.scale_stride, a.W,
@@ -468,7 +468,7 @@ loco_status_t launch_fixed_dr(int bits, hipStream_t s, const uint8_t* codes, siz
             if (loco_status_t st = grid_for(n, (size_t)kSlot * One::kSlots * (One::kThreads / kWave), &grid, kRun ? 8 * kRun : 1))
                 return st;
             return launch(fixed_dr_kernel<8, One::kSlots, One::kThreads, One::kInFlight, kNonTemporal, EPI, kRun,
-                                          kDrOnePayload8BitWaves>,
+                                          kDrFewPayloads8BitWaves>,
                           grid, One::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
         }
     }
