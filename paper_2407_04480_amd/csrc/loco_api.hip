@@ -214,7 +214,8 @@ using DrShapeFor = std::conditional_t<dr_updates_in_place(EPI), DrShape<8>, DrSh
 //   - up to 16 payloads of 4-bit codes with blocks of 256 elements and more, and for 8-bit codes
 //     up to 64 payloads, the quad layout is the fastest;
 //   - with more payloads its code loads (2 bytes per lane at 4 bits) become the limit: 4-bit codes
-//     with blocks of 32..128 elements gain 6-10 points of HBM peak from wide loads from W = 16 on,
+//     with blocks of 32..128 elements gain 6-10 points of HBM peak from wide loads from W = 16 on
+//     (blocks of 32 and 64 elements already 1-4 points from 4-byte loads at W = 8..15),
 //     with larger blocks 1-5 points from W = 64 on, 8-bit codes 2 points at W = 128;
 //   - lane-loaded steps remove the doubled fetch of step lines that the scalar cache causes
 //     (read traffic 1.037x -> 1.001x of the algorithmic bytes at 4 bits, B = 256) but cost
@@ -230,6 +231,7 @@ int dr_auto_decomposition(int bits, int block, int W, Epilogue kind, bool scales
     if (W >= 96) return kDrWide16;                       // every bit width, block size and epilogue
     if (bits == 4) {
         if (block <= 128 && W >= 16) return W >= 64 ? kDrWide16 : kDrWide8;
+        if (block <= 64 && W >= 8 && kind == Epilogue::kStore) return kDrWide4;   // 1-4 points over the quad layout
         if (block >= 256 && W >= 64) return kDrWide16;
         return kDrQuad;
     }

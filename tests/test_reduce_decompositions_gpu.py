@@ -63,7 +63,7 @@ def test_every_decomposition_matches_the_oracle(decomposition, bits, B):
             f"decomposition {decomposition} bits={bits} B={B} W={W} n={n}: {np.count_nonzero(got != want)} differ"
 
 
-@pytest.mark.parametrize("bits,B,W", [(4, 32, 15), (4, 32, 16), (4, 64, 33), (4, 64, 63), (4, 64, 64), (4, 128, 70),
+@pytest.mark.parametrize("bits,B,W", [(4, 32, 7), (4, 64, 8), (4, 32, 15), (4, 32, 16), (4, 64, 33), (4, 64, 63), (4, 64, 64), (4, 128, 70),
                                       (4, 256, 63), (4, 256, 64), (4, 256, 130), (4, 512, 128), (8, 64, 40),
                                       (8, 64, 95), (8, 64, 96), (8, 256, 1), (8, 256, 2), (8, 512, 9), (8, 512, 100)])
 def test_the_librarys_own_choice_matches_the_oracle(bits, B, W):
@@ -85,7 +85,9 @@ def test_many_workers_take_the_wide_loads():
     assert loco_dequant_reduce_decomposition(16, 4, 256) == QUAD
     assert loco_dequant_reduce_decomposition(64, 4, 256) == WIDE16
     assert loco_dequant_reduce_decomposition(128, 4, 256) == WIDE16
-    assert loco_dequant_reduce_decomposition(8, 4, 64) == QUAD
+    assert loco_dequant_reduce_decomposition(7, 4, 64) == QUAD
+    assert loco_dequant_reduce_decomposition(8, 4, 64) == WIDE4
+    assert loco_dequant_reduce_decomposition(8, 4, 128) == QUAD
     assert loco_dequant_reduce_decomposition(16, 4, 64) == WIDE8
     assert loco_dequant_reduce_decomposition(64, 4, 64) == WIDE16
     assert loco_dequant_reduce_decomposition(8, 8, 64) == QUAD
