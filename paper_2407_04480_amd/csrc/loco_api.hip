@@ -44,8 +44,8 @@ constexpr bool kNonTemporal = true;
 // of fetching it into all eight.
 constexpr int kCqXcdRun = 0;
 constexpr int kDrXcdRun = 32;
-constexpr int kDrNaturalOrderWorkers = 16;              // 4-bit plain reduce: from this many payloads and
-constexpr size_t kDrNaturalOrderElements = (size_t)1 << 30;   // elements on, no runs of tiles per XCD
+constexpr int kDrNaturalOrderWorkers = 16;              // 4-bit plain reduce: from this many payloads and this
+constexpr size_t kDrNaturalOrderWork = (size_t)1 << 34;  // many elements x payloads on, no runs of tiles per XCD
 // Plain streaming kernels, each in the shape that measured fastest for its mix (together with
 // the resident wavefronts per SIMD set on the kernels): a pure write stream likes 4 KB per
 // workgroup, a copy one wavefront per KB, a pure read 4 KB per wavefront.
@@ -298,14 +298,15 @@ loco_status_t launch_dr(int how, hipStream_t s, const DrArgs& a, const EpilogueA
         if (dr_few_workers(BITS, a.W)) return launch_dr_quad<BITS, BLOCK, EPI, DrFewWorkersShape, float, false>(s, a, epi);
     }
     if constexpr (EPI == Epilogue::kStore && BITS == 4) {
-        // Large shards with 16 payloads and more: the hardware's own round robin of workgroups over
-        // the XCDs measured 2-3 points of HBM peak faster than runs of tiles per XCD (2.2e9 elements,
-        // W = 16: 80 % against 77.6 %), although every L2 then fetches the lines of block steps for
-        // itself (read traffic 1.24x instead of 1.04x of the algorithmic bytes).  Not when the payload
+        // 16 payloads and more that together hold 2^34 codes or more: the hardware's own round robin
+        // of workgroups over the XCDs measured 2-6 points of HBM peak faster than runs of tiles per XCD
+        // (2.2e9 elements, W = 16: 82.5 % against 76 %; 8.4e8 elements, W = 32: 76.5 against 74.0; below
+        // that amount the runs are 1-3 points faster), although every L2 then fetches the lines of block
+        // steps for itself (read traffic 1.24x instead of 1.04x of the algorithmic bytes).  Not when the payload
         // strides are multiples of a large power of two: the W loads of a wavefront then meet in one
         // memory channel, which the round robin suffers from far more (down to 40-60 % of the rate).
         const bool aliased = a.code_stride % 4096 == 0 || (a.scale_stride * sizeof(float)) % 4096 == 0;
-        if (a.W >= kDrNaturalOrderWorkers && a.n >= kDrNaturalOrderElements && !aliased)
+        if (a.W >= kDrNaturalOrderWorkers && (size_t)a.W * a.n >= kDrNaturalOrderWork && !aliased)
             return launch_dr_quad<BITS, BLOCK, EPI, DrShape<BITS>, float, false, 0>(s, a, epi);
     }
     return launch_dr_quad<BITS, BLOCK, EPI, DrShapeFor<BITS, EPI>, float, false>(s, a, epi);
