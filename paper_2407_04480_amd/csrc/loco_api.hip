@@ -44,8 +44,18 @@ constexpr bool kNonTemporal = true;
 // of fetching it into all eight.
 constexpr int kCqXcdRun = 0;
 constexpr int kDrXcdRun = 32;
-constexpr int kDrNaturalOrderWorkers = 16;              // 4-bit plain reduce: from this many payloads and this
-constexpr size_t kDrNaturalOrderWork = (size_t)1 << 34;  // many elements x payloads on, no runs of tiles per XCD
+// The hardware's own round robin of workgroups over the XCDs instead of runs of tiles per XCD: when the
+// payloads together hold 2^33 bytes of codes or more (and there are at least 8 of them) it measured 2-6
+// points of HBM peak faster for the quad layout, the 8-byte code loads and the fixed-scale reduce (4-bit,
+// 2.2e9 elements, W = 16: 82.5 % against 76 %; 8.4e8 elements, W = 32: 76.5 against 74.0; 8-bit, W = 32:
+// 74.2 against 72.5; fixed-scale, 2.2e9 elements, W = 16: 77.7 against 75.1), although every L2 then
+// fetches the lines of block steps for itself (read traffic 1.24x instead of 1.04x of the algorithmic
+// bytes at 4 bits, B = 256).  Below that amount the runs are 1-3 points faster; the 16-byte code loads are
+// the same either way.  Not when the payload strides are multiples of a large power of two: the W loads of
+// a wavefront then meet in one memory channel, which the round robin suffers from far more (down to
+// 40-60 % of the rate).
+constexpr int kDrNaturalOrderWorkers = 8;
+constexpr size_t kDrNaturalOrderBytes = (size_t)1 << 33;
 // Plain streaming kernels, each in the shape that measured fastest for its mix (together with
 // the resident wavefronts per SIMD set on the kernels): a pure write stream likes 4 KB per
 // workgroup, a copy one wavefront per KB, a pure read 4 KB per wavefront.
@@ -201,6 +211,11 @@ struct DrArgs {
     size_t n;
 };
 
+bool dr_natural_order(int W, size_t n, int bits, size_t code_stride, size_t step_stride_bytes) {
+    const bool aliased = code_stride % 4096 == 0 || (step_stride_bytes != 0 && step_stride_bytes % 4096 == 0);
+    return W >= kDrNaturalOrderWorkers && (size_t)W * loco_code_bytes(n, bits) >= kDrNaturalOrderBytes && !aliased;
+}
+
 // With fp32 arrays updated in place behind the decode (theta; m and v for Adam) one slot per
 // wavefront and 256 threads measured best, whatever the worker count.
 constexpr bool dr_updates_in_place(Epilogue e) { return e == Epilogue::kSgd || e == Epilogue::kAdam; }
@@ -252,25 +267,27 @@ loco_status_t launch_dr_quad(hipStream_t s, const DrArgs& a, const EpilogueArgs&
                   a.n, 1.0f / (float)a.W, epi);
 }
 
-template <int BITS, int BLOCK, int CB, Epilogue EPI = Epilogue::kStore>
+template <int BITS, int BLOCK, int CB, Epilogue EPI = Epilogue::kStore, int XCD_RUN = kDrXcdRun>
 loco_status_t launch_dr_wide(hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
     using Shape = DrWideShape<CB>;
     constexpr size_t kUnitElems = (size_t)kWave * (CB * 8 / BITS);
     unsigned grid;
-    if (loco_status_t st = grid_for(a.n, kUnitElems * (Shape::kThreads / kWave), &grid, kDrXcdRun ? 8 * kDrXcdRun : 1))
+    if (loco_status_t st = grid_for(a.n, kUnitElems * (Shape::kThreads / kWave), &grid, XCD_RUN ? 8 * XCD_RUN : 1))
         return st;
-    return launch(dr_wide_kernel<BITS, BLOCK, CB, Shape::kThreads, Shape::kInFlight, kNonTemporal, kDrXcdRun, EPI, float>,
+    return launch(dr_wide_kernel<BITS, BLOCK, CB, Shape::kThreads, Shape::kInFlight, kNonTemporal, XCD_RUN, EPI, float>,
                   grid, Shape::kThreads, s, a.codes, a.code_stride, static_cast<const float*>(a.scales), a.scale_stride,
                   a.W, a.n, 1.0f / (float)a.W, epi);
 }
 
 template <int BITS, int BLOCK, Epilogue EPI>
 loco_status_t launch_dr(int how, hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
+    const bool natural = dr_natural_order(a.W, a.n, BITS, a.code_stride, a.scale_stride * sizeof(float));
     if constexpr (EPI == Epilogue::kStore) {   // the other decompositions: plain fp32 output, fp32 steps
         if (how != kDrQuad && a.scales_bf16) return LOCO_ERR_UNSUPPORTED;
         if (how == kDrQuadLaneSteps) {
             if constexpr (BLOCK >= 128) {
                 if (dr_few_workers(BITS, a.W)) return launch_dr_quad<BITS, BLOCK, EPI, DrFewWorkersShape, float, true>(s, a, epi);
+                if (natural) return launch_dr_quad<BITS, BLOCK, EPI, DrShape<BITS>, float, true, 0>(s, a, epi);
                 return launch_dr_quad<BITS, BLOCK, EPI, DrShape<BITS>, float, true>(s, a, epi);
             }
             return LOCO_ERR_UNSUPPORTED;
@@ -279,7 +296,10 @@ loco_status_t launch_dr(int how, hipStream_t s, const DrArgs& a, const EpilogueA
             if constexpr (BITS == 4) return launch_dr_wide<BITS, BLOCK, 4>(s, a, epi);
             return LOCO_ERR_UNSUPPORTED;
         }
-        if (how == kDrWide8) return launch_dr_wide<BITS, BLOCK, 8>(s, a, epi);
+        if (how == kDrWide8) {
+            if (natural) return launch_dr_wide<BITS, BLOCK, 8, EPI, 0>(s, a, epi);
+            return launch_dr_wide<BITS, BLOCK, 8>(s, a, epi);
+        }
         if (how == kDrWide16) return launch_dr_wide<BITS, BLOCK, 16>(s, a, epi);
         if (a.scales_bf16) {
             if (dr_few_workers(BITS, a.W)) return launch_dr_quad<BITS, BLOCK, EPI, DrFewWorkersShape, uint16_t, false>(s, a, epi);
@@ -297,17 +317,8 @@ loco_status_t launch_dr(int how, hipStream_t s, const DrArgs& a, const EpilogueA
         }
         if (dr_few_workers(BITS, a.W)) return launch_dr_quad<BITS, BLOCK, EPI, DrFewWorkersShape, float, false>(s, a, epi);
     }
-    if constexpr (EPI == Epilogue::kStore && BITS == 4) {
-        // 16 payloads and more that together hold 2^34 codes or more: the hardware's own round robin
-        // of workgroups over the XCDs measured 2-6 points of HBM peak faster than runs of tiles per XCD
-        // (2.2e9 elements, W = 16: 82.5 % against 76 %; 8.4e8 elements, W = 32: 76.5 against 74.0; below
-        // that amount the runs are 1-3 points faster), although every L2 then fetches the lines of block
-        // steps for itself (read traffic 1.24x instead of 1.04x of the algorithmic bytes).  Not when the payload
-        // strides are multiples of a large power of two: the W loads of a wavefront then meet in one
-        // memory channel, which the round robin suffers from far more (down to 40-60 % of the rate).
-        const bool aliased = a.code_stride % 4096 == 0 || (a.scale_stride * sizeof(float)) % 4096 == 0;
-        if (a.W >= kDrNaturalOrderWorkers && (size_t)a.W * a.n >= kDrNaturalOrderWork && !aliased)
-            return launch_dr_quad<BITS, BLOCK, EPI, DrShape<BITS>, float, false, 0>(s, a, epi);
+    if constexpr (EPI == Epilogue::kStore) {
+        if (natural) return launch_dr_quad<BITS, BLOCK, EPI, DrShape<BITS>, float, false, 0>(s, a, epi);
     }
     return launch_dr_quad<BITS, BLOCK, EPI, DrShapeFor<BITS, EPI>, float, false>(s, a, epi);
 }
@@ -473,6 +484,11 @@ loco_status_t launch_fixed_dr(int bits, hipStream_t s, const uint8_t* codes, siz
             return launch(fixed_dr_kernel<8, One::kSlots, One::kThreads, One::kInFlight, kNonTemporal, EPI, kRun,
                                           kDrFewPayloads8BitWaves>,
                           grid, One::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
+        }
+        if (bits == 4 && dr_natural_order(W, n, 4, cs, 0)) {   // see kDrNaturalOrderBytes
+            if (loco_status_t st = grid_for(n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid)) return st;
+            return launch(fixed_dr_kernel<4, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI, 0>, grid,
+                          Shape::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
         }
     }
     if (bits == 4)
