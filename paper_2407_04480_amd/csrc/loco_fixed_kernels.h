@@ -268,7 +268,7 @@ fixed_dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, int W, si
     constexpr uint32_t SLOT_CODE_BYTES = kSlot * BITS / 8;
     constexpr int FLUSH = BITS == 4 ? 16 : 256;   // workers per widening of the packed sums
     const uint32_t lane = threadIdx.x & (kWave - 1);
-    const size_t tile0 = wave_tile_index<THREADS, XCDK>() * TILE;
+    const size_t tile0 = wave_tile_index_tail_first<THREADS, XCDK>(n, TILE) * TILE;
     if (tile0 >= n) return;
 
     if (tile0 + TILE <= n) {
@@ -343,27 +343,52 @@ fixed_dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, int W, si
             epilogue_finish<EPI, NT>(epi, i, g, est[s]);
         }
     } else {
-#pragma unroll 1
+        // last, partial tile (see load_bytes_clamped in loco_kernels.h)
+        constexpr int QB = kQuad * BITS / 8;        // code bytes per quad: 2 or 4
+        const size_t last_quad = (n - 1) & ~(size_t)(kQuad - 1);
+        size_t at[SLOTS];
+        uint32_t have[SLOTS];
+        int total[SLOTS][4];
+#pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
-            if (i >= n) continue;
-            int total[4] = {0, 0, 0, 0};
-            for (int w = 0; w < W; ++w) {
-                const uint8_t* p = codes + (size_t)w * code_stride;
+            at[s] = i < n ? i : last_quad;
+            have[s] = code_bytes_present<BITS>(at[s], n, kQuad);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (i + j >= n) continue;
-                    if constexpr (BITS == 4) {
-                        const int nib = (p[(i + j) >> 1] >> (4 * ((i + j) & 1))) & 15;
-                        total[j] += (nib ^ 8) - 8;
+            for (int j = 0; j < 4; ++j) total[s][j] = 0;
+        }
+        for (int w0 = 0; w0 < W; w0 += kTailPayloads) {
+            uint32_t c[kTailPayloads][SLOTS];
+#pragma unroll
+            for (int u = 0; u < kTailPayloads; ++u) {
+                const size_t w = (size_t)(w0 + u < W ? w0 + u : W - 1);
+#pragma unroll
+                for (int s = 0; s < SLOTS; ++s) {
+                    uint32_t word[1] = {0u};
+                    if constexpr (QB == 4) {
+                        load_bytes_clamped<4>(codes + w * code_stride + at[s], have[s], word);
                     } else {
-                        total[j] += (int)(int8_t)p[i + j];
+                        const uint8_t* p = codes + w * code_stride + (at[s] >> 1);
+                        word[0] = (uint32_t)p[0] | ((uint32_t)p[have[s] - 1u] << 8);
                     }
+                    c[u][s] = word[0];
                 }
             }
 #pragma unroll
+            for (int u = 0; u < kTailPayloads; ++u)
+                if (w0 + u < W)
+#pragma unroll
+                    for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            total[s][j] += ((int)(c[u][s] << (32 - BITS * (j + 1)))) >> (32 - BITS);   // signed field j
+        }
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
+#pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (i + j < n) epilogue_element<EPI>(epi, i + j, ((float)total[j] * inv_s) * inv_w);
+                if (i + j < n) epilogue_element<EPI>(epi, i + j, ((float)total[s][j] * inv_s) * inv_w);
         }
     }
 }

@@ -112,6 +112,24 @@ __device__ __forceinline__ size_t wave_tile_index() {
     return b * (THREADS / kWave) + (size_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
 }
 
+// The same for the reduces, with the first and the last workgroup that has elements exchanged: the
+// last tile may be a partial one, whose wavefront takes the slow byte-wise path W payloads long; in the
+// workgroup that is dispatched first that time hides behind all the others, in the one dispatched
+// last it would be added to the kernel's (8 % at 128 payloads and 5e7 elements).
+template <int THREADS, int XCDK>
+__device__ __forceinline__ size_t wave_tile_index_tail_first(size_t n, size_t tile_elems) {
+    size_t b = blockIdx.x;
+    if constexpr (XCDK > 0) {
+        static_assert((XCDK & (XCDK - 1)) == 0, "XCDK must be a power of two");
+        const uint32_t in_run = blockIdx.x & (8u * XCDK - 1u);
+        b = (size_t)(blockIdx.x - in_run) + (in_run & 7u) * XCDK + (in_run >> 3);
+    }
+    const size_t last = ((n + tile_elems - 1) / tile_elems - 1) / (THREADS / kWave);   // n > 0
+    if (b == 0) b = last;
+    else if (b == last) b = 0;
+    return b * (THREADS / kWave) + (size_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+}
+
 // ---- gradient loads: one quad widened to fp32 ----
 template <typename G> struct Grad;
 template <> struct Grad<float> {
@@ -491,6 +509,29 @@ __device__ __forceinline__ uint32_t load_quad_codes(const uint8_t* p) {
     else return vload<NT>(reinterpret_cast<const uint32_t*>(p));
 }
 
+// ---- the last, partial tile of a reduce ----
+// A tile that n cuts short is summed with byte loads that never leave the payloads: a lane whose
+// elements do not exist works on the last group of elements that does, and a byte that does not exist
+// is replaced by the last one that does; what such duplicates decode to is never stored.  All loads
+// are unconditional, so the loads of kTailPayloads payloads are in flight together: a lane waits
+// W / kTailPayloads times, not once per payload and element (a ragged shard with 128 payloads spent
+// 0.15 - 0.45 ms in this path alone when it did).
+constexpr int kTailPayloads = 4;
+template <int BYTES>
+__device__ __forceinline__ void load_bytes_clamped(const uint8_t* p, uint32_t have, uint32_t (&out)[BYTES / 4]) {
+#pragma unroll
+    for (int k = 0; k < BYTES / 4; ++k) out[k] = 0u;
+#pragma unroll
+    for (int k = 0; k < BYTES; ++k) out[k / 4] |= (uint32_t)p[(uint32_t)k < have ? (uint32_t)k : have - 1u] << (8 * (k % 4));
+}
+// Bytes of codes that exist for a group of `group` elements starting at element i < n.
+template <int BITS>
+__device__ __forceinline__ uint32_t code_bytes_present(size_t i, size_t n, uint32_t group) {
+    const size_t left = n - i;
+    const uint32_t elems = left < group ? (uint32_t)left : group;
+    return (elems * BITS + 7u) / 8u;
+}
+
 constexpr uint32_t kBigStepBits = 0x7B800000u;  // 2^120 as a binary32 bit pattern
 
 // Same decomposition as cq_kernel; WU payloads are in flight per lane and slot.  Addresses
@@ -506,7 +547,7 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __rest
     constexpr bool UNIFORM_STEP = BLOCK >= kSlot;
     constexpr uint32_t SLOT_CODE_BYTES = kSlot * BITS / 8;
     const uint32_t lane = threadIdx.x & (kWave - 1);
-    const size_t wave = wave_tile_index<THREADS, XCDK>();
+    const size_t wave = wave_tile_index_tail_first<THREADS, XCDK>(n, TILE);
     const size_t tile0 = wave * TILE;
     if (tile0 >= n) return;
 
@@ -663,28 +704,51 @@ dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* __rest
             epilogue_finish<EPI, NT>(epi, i, g, est[s]);
         }
     } else {
-#pragma unroll 1
+        // last, partial tile (see load_bytes_clamped)
+        constexpr int QB = kQuad * BITS / 8;        // code bytes per quad: 2 or 4
+        const size_t last_quad = (n - 1) & ~(size_t)(kQuad - 1);
+        size_t at[SLOTS];
+        uint32_t have[SLOTS];
+        float acc[SLOTS][4];
+#pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
-            if (i >= n) continue;
-            float acc[4] = {0.f, 0.f, 0.f, 0.f};
-            for (int w = 0; w < W; ++w) {
-                const uint8_t* p = codes + (size_t)w * code_stride;
-                uint32_t c = 0;
-                if constexpr (BITS == 4) {
-                    c = p[i >> 1];
-                    if (i + 2 < n) c |= (uint32_t)p[(i >> 1) + 1] << 8;
-                } else {
+            at[s] = i < n ? i : last_quad;
+            have[s] = code_bytes_present<BITS>(at[s], n, kQuad);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (i + j < n) c |= (uint32_t)p[i + j] << (8 * j);
+            for (int j = 0; j < 4; ++j) acc[s][j] = 0.0f;
+        }
+        for (int w0 = 0; w0 < W; w0 += kTailPayloads) {
+            uint32_t c[kTailPayloads][SLOTS];
+            float D[kTailPayloads][SLOTS];
+#pragma unroll
+            for (int u = 0; u < kTailPayloads; ++u) {
+                const size_t w = (size_t)(w0 + u < W ? w0 + u : W - 1);
+#pragma unroll
+                for (int s = 0; s < SLOTS; ++s) {
+                    uint32_t word[1] = {0u};
+                    if constexpr (QB == 4) {
+                        load_bytes_clamped<4>(codes + w * code_stride + at[s], have[s], word);
+                    } else {
+                        const uint8_t* p = codes + w * code_stride + (at[s] >> 1);
+                        word[0] = (uint32_t)p[0] | ((uint32_t)p[have[s] - 1u] << 8);
+                    }
+                    c[u][s] = word[0];
+                    D[u][s] = step_from_storage(scales[w * scale_stride + at[s] / BLOCK]);
                 }
-                const float D = step_from_storage(scales[(size_t)w * scale_stride + i / BLOCK]);
-                dr_accumulate<BITS>(c, D, acc);
             }
 #pragma unroll
+            for (int u = 0; u < kTailPayloads; ++u)
+                if (w0 + u < W)
+#pragma unroll
+                    for (int s = 0; s < SLOTS; ++s) dr_accumulate<BITS>(c[u][s], D[u][s], acc[s]);
+        }
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            const size_t i = tile0 + (size_t)s * kSlot + (size_t)lane * kQuad;
+#pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (i + j < n) epilogue_element<EPI>(epi, i + j, acc[j] * inv_w);
+                if (i + j < n) epilogue_element<EPI>(epi, i + j, acc[s][j] * inv_w);
         }
     }
 }
@@ -756,7 +820,7 @@ dr_wide_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* _
     __shared__ f32x4 stage[THREADS / kWave][kWave * NQ];
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wv = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const size_t tile0 = wave_tile_index<THREADS, XCDK>() * UNIT;
+    const size_t tile0 = wave_tile_index_tail_first<THREADS, XCDK>(n, UNIT) * UNIT;
     if (tile0 >= n) return;
 
     if (tile0 + UNIT <= n) {
@@ -876,23 +940,31 @@ dr_wide_kernel(const uint8_t* __restrict__ codes, size_t code_stride, const S* _
             epilogue_finish<EPI, NT>(epi, tile0 + (size_t)k * kSlot + (size_t)lane * kQuad, g, est[k]);
         }
     } else {
-        // last, partial unit: element by element, never at or beyond n
-#pragma unroll 1
-        for (int j = 0; j < EL; ++j) {
-            const size_t i = tile0 + (size_t)lane * EL + j;
-            if (i >= n) break;
-            float acc = 0.0f;
-            for (int w = 0; w < W; ++w) {
-                const uint8_t* p = codes + (size_t)w * code_stride;
-                int q;
-                if constexpr (BITS == 4) q = (((int)(p[i >> 1] >> (4 * (i & 1))) & 15) ^ 8) - 8;
-                else q = (int)(int8_t)p[i];
-                const float D = step_from_storage(scales[(size_t)w * scale_stride + i / BLOCK]);
-                const float d = (float)q * D;
-                acc = acc + d;
+        // last, partial unit (see load_bytes_clamped); a lane's EL elements lie inside one block
+        const size_t mine = tile0 + (size_t)lane * EL;
+        const size_t first = mine < n ? mine : (n - 1) / EL * EL;
+        const uint32_t have = code_bytes_present<BITS>(first, n, EL);
+        float acc[EL];
+#pragma unroll
+        for (int j = 0; j < EL; ++j) acc[j] = 0.0f;
+        for (int w0 = 0; w0 < W; w0 += kTailPayloads) {
+            uint32_t c[kTailPayloads][DW];
+            float D[kTailPayloads];
+#pragma unroll
+            for (int u = 0; u < kTailPayloads; ++u) {
+                const size_t w = (size_t)(w0 + u < W ? w0 + u : W - 1);
+                load_bytes_clamped<CB>(codes + w * code_stride + first * BITS / 8, have, c[u]);
+                D[u] = step_from_storage(scales[w * scale_stride + first / BLOCK]);
             }
-            epilogue_element<EPI>(epi, i, acc * inv_w);
+#pragma unroll
+            for (int u = 0; u < kTailPayloads; ++u)
+                if (w0 + u < W)
+#pragma unroll
+                    for (int k = 0; k < DW; ++k) dr_accumulate_dword<BITS>(c[u][k], D[u], acc + k * PER_DW);
         }
+#pragma unroll
+        for (int j = 0; j < EL; ++j)
+            if (mine + j < n) epilogue_element<EPI>(epi, mine + j, acc[j] * inv_w);
     }
 }
 
