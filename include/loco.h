@@ -343,7 +343,8 @@ loco_status_t loco_compensate_quantize_resident(const void *grad, loco_dtype_t g
  *      3 is for 4-bit codes only) and the sums are transposed through LDS before the stores
  * A decomposition that does not exist for (bits, block_size) is LOCO_ERR_UNSUPPORTED.
  * loco_dequant_reduce_decomposition returns the library's own choice (1..5) for a worker
- * count, bit width and block size, or -1 for arguments outside the supported sets.
+ * count, bit width and block size and a shard of 2^22 elements or more (below that, 4-bit codes
+ * take 4 or 1 where this says 5), or -1 for arguments outside the supported sets.
  */
 loco_status_t loco_dequant_reduce_decomposed(const uint8_t *codes, size_t code_stride_bytes,
                                              const float *scales, size_t scale_stride_elems,

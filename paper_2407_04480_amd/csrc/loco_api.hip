@@ -238,7 +238,20 @@ using DrShapeFor = std::conditional_t<dr_updates_in_place(EPI), DrShape<8>, DrSh
 enum DrDecomposition { kDrAuto = 0, kDrQuad = 1, kDrQuadLaneSteps = 2, kDrWide4 = 3, kDrWide8 = 4, kDrWide16 = 5 };
 template <int CB> struct DrWideShape { static constexpr int kThreads = CB == 16 ? 128 : 256, kInFlight = 4; };
 
-int dr_auto_decomposition(int bits, int block, int W, Epilogue kind, bool scales_bf16) {
+int dr_auto_for_large_shards(int bits, int block, int W, Epilogue kind, bool scales_bf16);
+
+// Shards below 2^22 elements do not fill the machine with the 2048-element units of the 16-byte code
+// loads of 4-bit codes (2^20 elements, W = 128: 33 us against 20 us for the quad layout; equal from 2^22
+// on), so there the choice falls back to what it would be with fewer payloads.
+constexpr size_t kDrWide16MinElements = (size_t)1 << 22;
+int dr_auto_decomposition(int bits, int block, int W, Epilogue kind, bool scales_bf16, size_t n) {
+    const int how = dr_auto_for_large_shards(bits, block, W, kind, scales_bf16);
+    if (how == kDrWide16 && bits == 4 && n < kDrWide16MinElements && kind != Epilogue::kStoreBf16)
+        return block <= 128 ? kDrWide8 : kDrQuad;
+    return how;
+}
+
+int dr_auto_for_large_shards(int bits, int block, int W, Epilogue kind, bool scales_bf16) {
     if (scales_bf16) return kDrQuad;
     // bf16 output of 4-bit codes: half the bytes written per element leave the quad layout's 2-byte code
     // loads as the limit at any worker count (W = 8: 80 % of HBM peak against 74 %, W = 1: 77 % against 65 %)
@@ -441,7 +454,7 @@ loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const
     if (loco_status_t st = check_device_range(codes, code_span)) return st;
     if (loco_status_t st = check_device_range(scales, step_span)) return st;
     if (loco_status_t st = check_epilogue(kind, epi, n)) return st;
-    const int how = decomposition == kDrAuto ? dr_auto_decomposition(bits, block_size, num_workers, kind, scales_bf16)
+    const int how = decomposition == kDrAuto ? dr_auto_decomposition(bits, block_size, num_workers, kind, scales_bf16, n)
                                              : decomposition;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const DrArgs a{codes, code_stride_bytes, scales, scales_bf16, scale_stride_elems, num_workers, n};
@@ -770,7 +783,7 @@ loco_status_t loco_dequant_reduce_decomposed(const uint8_t* codes, size_t code_s
 
 int loco_dequant_reduce_decomposition(int num_workers, int bits, int block_size) {
     if ((bits != 4 && bits != 8) || !block_size_ok(block_size) || num_workers < 1) return -1;
-    return dr_auto_decomposition(bits, block_size, num_workers, Epilogue::kStore, false);
+    return dr_auto_for_large_shards(bits, block_size, num_workers, Epilogue::kStore, false);
 }
 
 loco_status_t loco_dequant_reduce_bf16(const uint8_t* codes, size_t code_stride_bytes, const float* scales,

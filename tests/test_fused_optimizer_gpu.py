@@ -62,6 +62,32 @@ def test_block_reduce_with_sgd_and_adam(bits, B, W, n):
     assert np.abs(th_adam_h - th0).max() > 1e-4
 
 
+def test_block_reduce_with_sgd_and_adam_large_shard_many_payloads():
+    """2^22 elements and more with 64 payloads and more: the 16-byte code loads in front of the optimizer steps."""
+    rs = np.random.default_rng(77)
+    bits, B, W, n = 4, 256, 64, (1 << 22) + 2048 + 3
+    th0 = rs.standard_normal(n).astype(np.float32)
+    th_sgd_h, th_adam_h = th0.copy(), th0.copy()
+    m_h, v_h = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    th_sgd, th_adam = torch.from_numpy(th0).to(DEV), torch.from_numpy(th0).to(DEV)
+    m_t, v_t = torch.zeros(n, device=DEV), torch.zeros(n, device=DEV)
+    cb, nb = oracle.code_bytes(n, bits), oracle.num_blocks(n, B)
+    cstride, sstride = (cb + 15) // 16 * 16, nb + 1
+    codes = rs.integers(0, 256, W * cstride, dtype=np.uint8)
+    scales = (rs.uniform(0.5, 2.0, W * sstride) * 1e-4).astype(np.float32)
+    c_t, s_t = torch.from_numpy(codes).to(DEV), torch.from_numpy(scales).to(DEV)
+    loco_dequant_reduce_sgd(c_t, cstride, s_t, sstride, W, n, bits, B, ETA, th_sgd)
+    loco_dequant_reduce_adam(c_t, cstride, s_t, sstride, W, n, bits, B, ETA, B1, B2, DL, m_t, v_t, th_adam)
+    torch.cuda.synchronize()
+    g_avg = oracle.dequant_reduce(codes, scales, W, n, bits, B, cstride, sstride, threads=8)
+    oracle.sgd_update(th_sgd_h, g_avg, ETA)
+    oracle.adam_update(th_adam_h, m_h, v_h, g_avg, ETA, B1, B2, DL)
+    same("sgd theta", th_sgd, th_sgd_h)
+    same("adam m", m_t, m_h)
+    same("adam v", v_t, v_h)
+    same("adam theta", th_adam, th_adam_h)
+
+
 @pytest.mark.parametrize("bits,W", [(4, 8), (8, 5), (4, 33)])
 def test_fixed_reduce_with_sgd_and_adam(bits, W):
     n, log2_s = 5 * 1024 + 301, 19

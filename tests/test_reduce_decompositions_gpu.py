@@ -80,6 +80,19 @@ def test_the_librarys_own_choice_matches_the_oracle(bits, B, W):
     assert 1 <= chosen <= 5 and exists(chosen, bits, B)
 
 
+def test_large_shard_with_many_payloads_through_the_librarys_choice():
+    """From 2^22 elements on 64 payloads of 4-bit codes take the 16-byte code loads; below, the quad layout."""
+    rs = np.random.default_rng(5)
+    bits, B, W = 4, 256, 64
+    for n in ((1 << 22) + 2048 * 3 + 5, (1 << 22) - 2048 - 1):
+        codes, scales, cs, ss = random_payloads(rs, W, n, bits, B)
+        out = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+        loco_dequant_reduce(torch.from_numpy(codes).to(DEV), cs, torch.from_numpy(scales).to(DEV), ss, W, n, bits, B, out)
+        torch.cuda.synchronize()
+        want = oracle.dequant_reduce(codes, scales, W, n, bits, B, cs, ss, threads=8)
+        assert np.array_equal(out.cpu().numpy(), want), f"n={n}"
+
+
 def test_many_workers_take_the_wide_loads():
     assert loco_dequant_reduce_decomposition(8, 4, 256) == QUAD
     assert loco_dequant_reduce_decomposition(16, 4, 256) == QUAD
