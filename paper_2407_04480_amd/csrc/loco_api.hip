@@ -22,8 +22,15 @@ using namespace loco;
 // Compensate-quantize: two slots per wavefront, at most 4 wavefronts resident per SIMD (see
 // kCqWavesPerSimd); with that, one-wavefront workgroups for 8-bit codes and two wavefronts for
 // 4-bit codes measured best (up to 2 points over the other choice, and over 4 slots or 256 threads).
+// Its tiles go to the XCDs in runs of 32768 consecutive elements (128 KB of state; see
+// wave_tile_index): with the residency above that measured 2-3.5 points of HBM peak faster than the
+// hardware's own round robin (bf16, 4-bit, B = 256: 83.2 % against 81.1 %; 8-bit, B = 64: 84.7 against
+// 81.2; 2.2e9 elements: 84.2 against 80.7), twice that 1 point less, four times nothing, and HALF of it
+// 6 points slower than no runs at all.  (At full residency the runs had measured no gain.)
+constexpr int kCqXcdRunElements = 32768;
 template <int BITS, int BLOCK = 256> struct CqShape {
     static constexpr int kSlots = 2, kThreads = BITS == 8 ? 64 : 128;
+    static constexpr int kXcdRun = kCqXcdRunElements / (kSlot * kSlots * (kThreads / kWave));
 };
 template <int BITS> struct DrShape;
 template <> struct DrShape<4> { static constexpr int kSlots = 2, kThreads = 128, kInFlight = 4; };
@@ -38,11 +45,9 @@ struct DrTwoOrThreeWorkersShape { static constexpr int kSlots = 4, kThreads = 25
 constexpr bool dr_few_workers(int bits, int W) { return bits == 4 ? W <= 4 : W <= 3; }
 constexpr int kDrFewPayloads8BitWaves = 6;
 constexpr bool kNonTemporal = true;
-// Consecutive workgroups' tiles per XCD (see wave_tile_index).  Measured: compensate-
-// quantize is fastest with the hardware's own round robin (0); dequant-reduce loses
-// nothing with runs of 32, which keeps each cache line of block steps in one L2 instead
-// of fetching it into all eight.
-constexpr int kCqXcdRun = 0;
+// Consecutive workgroups' tiles per XCD (see wave_tile_index): dequant-reduce loses nothing with
+// runs of 32, which keeps each cache line of block steps in one L2 instead of fetching it into all
+// eight (and is, for its two main shapes, again 32768 elements per run).
 constexpr int kDrXcdRun = 32;
 // The hardware's own round robin of workgroups over the XCDs instead of runs of tiles per XCD: when the
 // payloads together hold 2^33 bytes of codes or more (and there are at least 8 of them) it measured 2-6
@@ -157,34 +162,35 @@ template <typename G, int BITS, int BLOCK>
 loco_status_t launch_cq(hipStream_t s, const CqArgs& a) {
     const float one_minus_beta = 1.0f - a.beta;
     using Shape = CqShape<BITS, BLOCK>;
+    constexpr int kRun = Shape::kXcdRun;
     unsigned grid;
     if (loco_status_t st = grid_for(a.n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid,
-                                    kCqXcdRun ? 8 * kCqXcdRun : 1))
+                                    kRun ? 8 * kRun : 1))
         return st;
     if constexpr (BITS == 4) {
         if (a.stage_codes)
-            return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, float, true>,
+            return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kRun, false, float, true>,
                           grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
                           a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
     }
     if (a.waves == 6 || a.waves == 8) {
         if (a.waves == 6)
-            return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, float, false, 6>,
+            return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kRun, false, float, false, 6>,
                           grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
                           a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
-        return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, float, false, 8>,
+        return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kRun, false, float, false, 8>,
                       grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
                       a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
     }
     if (a.scales_bf16)   // offered without clipping only
-        return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, uint16_t>,
+        return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kRun, false, uint16_t>,
                       grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
                       a.reset_period, a.clip, a.codes, static_cast<uint16_t*>(a.scales));
     if (std::isinf(a.clip))
-        return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, false, float>,
+        return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kRun, false, float>,
                       grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
                       a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
-    return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kCqXcdRun, true, float>,
+    return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kRun, true, float>,
                   grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
                   a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
 }
@@ -384,8 +390,10 @@ EpilogueArgs make_epilogue(float* out, float* theta, float* m, float* v, float e
 }
 
 // Launch shapes of the fixed-scale kernels (units of 512 elements per wavefront).
-struct FixedCqShape { static constexpr int kUnits = 2, kThreads = 128; };
-struct FixedF32CqShape { static constexpr int kSlots = 2, kThreads = 64; };    // measured: 79 % of peak (128 threads: 77.7 %)
+// (tile runs per XCD: none for the 8-bit state, where every run length tried was 2-6 points slower; for the
+// fp32 state 32768 elements like cq_kernel: 83 % of HBM peak against 79-80 %)
+struct FixedCqShape { static constexpr int kUnits = 2, kThreads = 128, kXcdRun = 0; };
+struct FixedF32CqShape { static constexpr int kSlots = 2, kThreads = 64, kXcdRun = kCqXcdRunElements / (kSlot * 2); };    // measured: 79 % of peak (128 threads: 77.7 %)
 struct FixedDrShape { static constexpr int kSlots = 2, kThreads = 128, kInFlight = 4; };
 struct FixedDrWideShape { static constexpr int kSlots = 1, kThreads = 256, kInFlight = 4; };  // Adam, as DrShapeFor
 template <Epilogue EPI>
@@ -410,10 +418,10 @@ struct FixedCqArgs {
 template <typename G, int BITS, bool POW2>
 loco_status_t launch_fixed_cq(unsigned grid, hipStream_t s, const FixedCqArgs& a) {
     if (std::isinf(a.clip))
-        return launch(fixed_cq_kernel<G, BITS, POW2, FixedCqShape::kUnits, FixedCqShape::kThreads, kNonTemporal, false>,
+        return launch(fixed_cq_kernel<G, BITS, POW2, FixedCqShape::kUnits, FixedCqShape::kThreads, kNonTemporal, false, FixedCqShape::kXcdRun>,
                       grid, FixedCqShape::kThreads, s, a.grad, a.err8, a.n, a.k, a.reset, a.step_index, a.reset_period,
                       a.clip, a.codes);
-    return launch(fixed_cq_kernel<G, BITS, POW2, FixedCqShape::kUnits, FixedCqShape::kThreads, kNonTemporal, true>,
+    return launch(fixed_cq_kernel<G, BITS, POW2, FixedCqShape::kUnits, FixedCqShape::kThreads, kNonTemporal, true, FixedCqShape::kXcdRun>,
                   grid, FixedCqShape::kThreads, s, a.grad, a.err8, a.n, a.k, a.reset, a.step_index, a.reset_period,
                   a.clip, a.codes);
 }
@@ -607,7 +615,8 @@ loco_status_t compress_fixed(const void* grad, loco_dtype_t grad_dtype, float cl
     if (loco_status_t st = check_device_range(err_state8, n)) return st;
     if (loco_status_t st = check_device_range(codes_out, loco_code_bytes(n, bits))) return st;
     unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kUnit * FixedCqShape::kUnits * (FixedCqShape::kThreads / kWave), &grid))
+    if (loco_status_t st = grid_for(n, (size_t)kUnit * FixedCqShape::kUnits * (FixedCqShape::kThreads / kWave), &grid,
+                                    FixedCqShape::kXcdRun ? 8 * FixedCqShape::kXcdRun : 1))
         return st;
     FixedScales k;
     k.s = std::ldexp(1.0f, log2_s);
@@ -640,7 +649,9 @@ loco_status_t compress_fixed_f32state(const void* grad, loco_dtype_t grad_dtype,
     if (loco_status_t st = check_device_range(codes_out, loco_code_bytes(n, bits))) return st;
     using Shape = FixedF32CqShape;
     unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid)) return st;
+    if (loco_status_t st = grid_for(n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid,
+                                    Shape::kXcdRun ? 8 * Shape::kXcdRun : 1))
+        return st;
     FixedScales k{};
     k.s = std::ldexp(1.0f, log2_s);
     k.inv_s = std::ldexp(1.0f, -log2_s);
@@ -650,11 +661,11 @@ loco_status_t compress_fixed_f32state(const void* grad, loco_dtype_t grad_dtype,
     const long long* si = reinterpret_cast<const long long*>(step_index_dev);
     const long long period = (long long)reset_period;
     if (grad_dtype == LOCO_BF16) {
-        if (bits == 4) return launch(fixed_f32_cq_kernel<bf16_t, 4, Shape::kSlots, Shape::kThreads, kNonTemporal>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
-        return launch(fixed_f32_cq_kernel<bf16_t, 8, Shape::kSlots, Shape::kThreads, kNonTemporal>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
+        if (bits == 4) return launch(fixed_f32_cq_kernel<bf16_t, 4, Shape::kSlots, Shape::kThreads, kNonTemporal, Shape::kXcdRun>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
+        return launch(fixed_f32_cq_kernel<bf16_t, 8, Shape::kSlots, Shape::kThreads, kNonTemporal, Shape::kXcdRun>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
     }
-    if (bits == 4) return launch(fixed_f32_cq_kernel<float, 4, Shape::kSlots, Shape::kThreads, kNonTemporal>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
-    return launch(fixed_f32_cq_kernel<float, 8, Shape::kSlots, Shape::kThreads, kNonTemporal>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
+    if (bits == 4) return launch(fixed_f32_cq_kernel<float, 4, Shape::kSlots, Shape::kThreads, kNonTemporal, Shape::kXcdRun>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
+    return launch(fixed_f32_cq_kernel<float, 8, Shape::kSlots, Shape::kThreads, kNonTemporal, Shape::kXcdRun>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
 }
 
 template <StreamMode MODE, typename Shape>

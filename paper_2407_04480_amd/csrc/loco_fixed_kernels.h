@@ -102,14 +102,14 @@ constexpr int fixed_cq_waves_per_simd() { return (sizeof(G) == 2 && BITS == 4) ?
 
 // One wavefront per UNITS*512 elements, THREADS/64 wavefronts per workgroup;
 // grid = ceil(n / (UNITS*512*THREADS/64)).  The last wavefront may take the guarded path.
-template <typename G, int BITS, bool POW2, int UNITS, int THREADS, bool NT, bool CLIP>
+template <typename G, int BITS, bool POW2, int UNITS, int THREADS, bool NT, bool CLIP, int XCDK = 0>
 __global__ void __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, fixed_cq_waves_per_simd<G, BITS>())))
 fixed_cq_kernel(const void* __restrict__ grad, int8_t* __restrict__ err8, size_t n, FixedScales k,
                 int reset, const long long* __restrict__ step_index, long long reset_period, float clip,
                 uint8_t* __restrict__ codes) {
     constexpr size_t TILE = (size_t)kUnit * UNITS;
     const uint32_t lane = threadIdx.x & (kWave - 1);
-    const size_t tile0 = wave_tile_index<THREADS, 0>() * TILE;
+    const size_t tile0 = wave_tile_index<THREADS, XCDK>() * TILE;
     if (tile0 >= n) return;
     const bool rst = step_index ? reset_step_due(step_index, reset_period) : reset != 0;   // Eq. 7
 
@@ -188,14 +188,14 @@ __device__ __forceinline__ uint32_t fixed_f32_quad(const float (&h)[4], float (&
     return pk;
 }
 
-template <typename G, int BITS, int SLOTS, int THREADS, bool NT>
+template <typename G, int BITS, int SLOTS, int THREADS, bool NT, int XCDK = 0>
 __global__ void __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, kCqWavesPerSimd)))
 fixed_f32_cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, FixedScales k, int reset,
                     const long long* __restrict__ step_index, long long reset_period,
                     uint8_t* __restrict__ codes) {
     constexpr size_t TILE = (size_t)kSlot * SLOTS;
     const uint32_t lane = threadIdx.x & (kWave - 1);
-    const size_t tile0 = wave_tile_index<THREADS, 0>() * TILE;
+    const size_t tile0 = wave_tile_index<THREADS, XCDK>() * TILE;
     if (tile0 >= n) return;
     const bool rst = step_index ? reset_step_due(step_index, reset_period) : reset != 0;   // Eq. 7
 
