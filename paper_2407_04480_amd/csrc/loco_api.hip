@@ -26,7 +26,9 @@ using namespace loco;
 // wave_tile_index): with the residency above that measured 2-3.5 points of HBM peak faster than the
 // hardware's own round robin (bf16, 4-bit, B = 256: 83.2 % against 81.1 %; 8-bit, B = 64: 84.7 against
 // 81.2; 2.2e9 elements: 84.2 against 80.7), twice that 1 point less, four times nothing, and HALF of it
-// 6 points slower than no runs at all.  (At full residency the runs had measured no gain.)
+// 6 points slower than no runs at all; run lengths that are no powers of two (24576...49152 elements) 3-6
+// points slower than 32768; the same order for fp32 gradients.  (At full residency the runs had measured
+// no gain.)
 constexpr int kCqXcdRunElements = 32768;
 template <int BITS, int BLOCK = 256> struct CqShape {
     static constexpr int kSlots = 2, kThreads = BITS == 8 ? 64 : 128;
@@ -393,7 +395,7 @@ EpilogueArgs make_epilogue(float* out, float* theta, float* m, float* v, float e
 // (tile runs per XCD: none for the 8-bit state, where every run length tried was 2-6 points slower; for the
 // fp32 state 32768 elements like cq_kernel: 83 % of HBM peak against 79-80 %)
 struct FixedCqShape { static constexpr int kUnits = 2, kThreads = 128, kXcdRun = 0; };
-struct FixedF32CqShape { static constexpr int kSlots = 2, kThreads = 64, kXcdRun = kCqXcdRunElements / (kSlot * 2); };    // measured: 79 % of peak (128 threads: 77.7 %)
+struct FixedF32CqShape { static constexpr int kSlots = 2, kThreads = 64, kXcdRun = kCqXcdRunElements / (kSlot * 2); };    // 128 threads measured 1.5 points slower
 struct FixedDrShape { static constexpr int kSlots = 2, kThreads = 128, kInFlight = 4; };
 struct FixedDrWideShape { static constexpr int kSlots = 1, kThreads = 256, kInFlight = 4; };  // Adam, as DrShapeFor
 template <Epilogue EPI>
