@@ -1,0 +1,75 @@
+"""Compensate-quantize at lengths around the boundaries of its tile order.
+
+The compressor hands its tiles to the XCDs in runs of 32768 consecutive elements, eight runs
+(262144 elements) per round of workgroups, and rounds its grid up to whole rounds.  Alg. 1
+steps 1-2 do not care which workgroup takes which tile: every element must be produced exactly
+once, whatever part of the last round is empty.  Lengths just below, at and just above whole
+runs and whole rounds, for both workgroup sizes of the block form (4- and 8-bit codes) and for
+the fixed-scale form with the state in float32, against the oracle byte for byte.  With the
+canaries behind every output this also shows that the empty tiles of the last round write nothing.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2407_04480_amd import (loco_code_bytes, loco_compensate_quantize,
+                                  loco_compensate_quantize_fixed_f32state, loco_num_blocks, workloads)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+RUN, ROUND = 32768, 8 * 32768
+LENGTHS = [RUN - 1, RUN, RUN + 1, 3 * RUN + 1024 + 5, ROUND - 1, ROUND, ROUND + 1, ROUND + RUN + 1,
+           2 * ROUND + 5 * RUN - 3, 5 * ROUND - 2048]
+PAD = 64   # canary elements behind every output
+
+
+def gradient(n, dtype, seed):
+    rng = torch.Generator(device="cpu").manual_seed(seed)
+    g = torch.randn(n, generator=rng) * 1e-3
+    g[:: 4099] *= 50.0              # a few blocks with a large step
+    g[7 * 256: 9 * 256] = 0.0       # two dead blocks
+    return g.to(dtype)
+
+
+@pytest.mark.parametrize("bits,B", [(4, 256), (4, 32), (8, 64), (8, 512)])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_block_form_around_run_and_round_boundaries(bits, B, dtype):
+    for n in LENGTHS:
+        print(f"[tile order] block form bits={bits} B={B} {dtype} n={n}", flush=True)
+        cb, nb = loco_code_bytes(n, bits), loco_num_blocks(n, B)
+        e_host = np.zeros(n, np.float32)
+        e_t = torch.full((n + PAD,), 5.0, dtype=torch.float32, device=DEV)
+        e_t[:n] = 0.0
+        codes_t = torch.full((cb + PAD,), 0xAA, dtype=torch.uint8, device=DEV)
+        scales_t = torch.full((nb + PAD,), -1.0, dtype=torch.float32, device=DEV)
+        for step in range(2):
+            g = gradient(n, dtype, 31 * n + step)
+            loco_compensate_quantize(g.to(DEV), e_t[:n], bits, B, 0.25, False, codes_t[:cb], scales_t[:nb])
+            torch.cuda.synchronize()
+            c_ref, s_ref = oracle.compensate_quantize(workloads.as_numpy_grad(g), e_host, bits, B, 0.25, 0)
+            assert np.array_equal(codes_t[:cb].cpu().numpy(), c_ref), f"n={n} step={step}: code bytes differ"
+            assert np.array_equal(scales_t[:nb].cpu().numpy().view(np.uint32), s_ref.view(np.uint32)), f"n={n}: steps differ"
+            assert np.array_equal(e_t[:n].cpu().numpy(), e_host), f"n={n} step={step}: state differs"
+        assert bool((e_t[n:] == 5.0).all()) and bool((codes_t[cb:] == 0xAA).all()) and bool((scales_t[nb:] == -1.0).all()), \
+            f"n={n}: written past the end"
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_fixed_scale_form_with_fp32_state_around_run_and_round_boundaries(bits):
+    log2_s = 19 if bits == 4 else 17
+    for n in LENGTHS:
+        print(f"[tile order] fixed scale, fp32 state, bits={bits} n={n}", flush=True)
+        cb = loco_code_bytes(n, bits)
+        e_host = np.zeros(n, np.float32)
+        e_t = torch.full((n + PAD,), 5.0, dtype=torch.float32, device=DEV)
+        e_t[:n] = 0.0
+        codes_t = torch.full((cb + PAD,), 0xAA, dtype=torch.uint8, device=DEV)
+        for step in range(2):
+            g = (gradient(n, torch.bfloat16, 17 * n + step).float() * 1e-2).to(torch.bfloat16)
+            loco_compensate_quantize_fixed_f32state(g.to(DEV), e_t[:n], bits, log2_s, 0.25, False, codes_t[:cb])
+            torch.cuda.synchronize()
+            c_ref = oracle.fixed_compensate_quantize_f32state(workloads.as_numpy_grad(g), e_host, bits, log2_s, 0.25)
+            assert np.array_equal(codes_t[:cb].cpu().numpy(), c_ref), f"n={n} step={step}: code bytes differ"
+            assert np.array_equal(e_t[:n].cpu().numpy(), e_host), f"n={n} step={step}: state differs"
+        assert bool((e_t[n:] == 5.0).all()) and bool((codes_t[cb:] == 0xAA).all()), f"n={n}: written past the end"
