@@ -28,7 +28,8 @@ using namespace loco;
 // 81.2; 2.2e9 elements: 84.2 against 80.7), twice that 1 point less, four times nothing, and HALF of it
 // 6 points slower than no runs at all; run lengths that are no powers of two (24576...49152 elements) 3-6
 // points slower than 32768; the same order for fp32 gradients.  (At full residency the runs had measured
-// no gain.)
+// no gain.)  The runs are counted from a multiple of 128 KB of the state's address, not from its first
+// element (xcd_run_lead_tiles).
 constexpr int kCqXcdRunElements = 32768;
 template <int BITS, int BLOCK = 256> struct CqShape {
     static constexpr int kSlots = 2, kThreads = BITS == 8 ? 64 : 128;
@@ -165,36 +166,37 @@ loco_status_t launch_cq(hipStream_t s, const CqArgs& a) {
     const float one_minus_beta = 1.0f - a.beta;
     using Shape = CqShape<BITS, BLOCK>;
     constexpr int kRun = Shape::kXcdRun;
+    constexpr size_t kTile = (size_t)kSlot * Shape::kSlots;
+    const uint32_t lead = xcd_run_lead_tiles(a.err, kRun ? kCqXcdRunElements * sizeof(float) : 0, kTile * sizeof(float));
     unsigned grid;
-    if (loco_status_t st = grid_for(a.n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid,
-                                    kRun ? 8 * kRun : 1))
+    if (loco_status_t st = grid_for(a.n + lead * kTile, kTile * (Shape::kThreads / kWave), &grid, kRun ? 8 * kRun : 1))
         return st;
     if constexpr (BITS == 4) {
         if (a.stage_codes)
             return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kRun, false, float, true>,
                           grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
-                          a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
+                          a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales), lead);
     }
     if (a.waves == 6 || a.waves == 8) {
         if (a.waves == 6)
             return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kRun, false, float, false, 6>,
                           grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
-                          a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
+                          a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales), lead);
         return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kRun, false, float, false, 8>,
                       grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
-                      a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
+                      a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales), lead);
     }
     if (a.scales_bf16)   // offered without clipping only
         return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kRun, false, uint16_t>,
                       grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
-                      a.reset_period, a.clip, a.codes, static_cast<uint16_t*>(a.scales));
+                      a.reset_period, a.clip, a.codes, static_cast<uint16_t*>(a.scales), lead);
     if (std::isinf(a.clip))
         return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kRun, false, float>,
                       grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
-                      a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
+                      a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales), lead);
     return launch(cq_kernel<G, BITS, BLOCK, Shape::kSlots, Shape::kThreads, kNonTemporal, kRun, true, float>,
                   grid, Shape::kThreads, s, a.grad, a.err, a.n, a.beta, one_minus_beta, a.reset, a.step_index,
-                  a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales));
+                  a.reset_period, a.clip, a.codes, static_cast<float*>(a.scales), lead);
 }
 
 template <typename G, int BITS>
@@ -650,8 +652,10 @@ loco_status_t compress_fixed_f32state(const void* grad, loco_dtype_t grad_dtype,
     if (loco_status_t st = check_device_range(err_state, n * sizeof(float))) return st;
     if (loco_status_t st = check_device_range(codes_out, loco_code_bytes(n, bits))) return st;
     using Shape = FixedF32CqShape;
+    constexpr size_t kTile = (size_t)kSlot * Shape::kSlots;
+    const uint32_t lead = xcd_run_lead_tiles(err_state, Shape::kXcdRun ? kCqXcdRunElements * sizeof(float) : 0, kTile * sizeof(float));
     unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid,
+    if (loco_status_t st = grid_for(n + lead * kTile, kTile * (Shape::kThreads / kWave), &grid,
                                     Shape::kXcdRun ? 8 * Shape::kXcdRun : 1))
         return st;
     FixedScales k{};
@@ -663,11 +667,11 @@ loco_status_t compress_fixed_f32state(const void* grad, loco_dtype_t grad_dtype,
     const long long* si = reinterpret_cast<const long long*>(step_index_dev);
     const long long period = (long long)reset_period;
     if (grad_dtype == LOCO_BF16) {
-        if (bits == 4) return launch(fixed_f32_cq_kernel<bf16_t, 4, Shape::kSlots, Shape::kThreads, kNonTemporal, Shape::kXcdRun>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
-        return launch(fixed_f32_cq_kernel<bf16_t, 8, Shape::kSlots, Shape::kThreads, kNonTemporal, Shape::kXcdRun>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
+        if (bits == 4) return launch(fixed_f32_cq_kernel<bf16_t, 4, Shape::kSlots, Shape::kThreads, kNonTemporal, Shape::kXcdRun>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out, lead);
+        return launch(fixed_f32_cq_kernel<bf16_t, 8, Shape::kSlots, Shape::kThreads, kNonTemporal, Shape::kXcdRun>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out, lead);
     }
-    if (bits == 4) return launch(fixed_f32_cq_kernel<float, 4, Shape::kSlots, Shape::kThreads, kNonTemporal, Shape::kXcdRun>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
-    return launch(fixed_f32_cq_kernel<float, 8, Shape::kSlots, Shape::kThreads, kNonTemporal, Shape::kXcdRun>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out);
+    if (bits == 4) return launch(fixed_f32_cq_kernel<float, 4, Shape::kSlots, Shape::kThreads, kNonTemporal, Shape::kXcdRun>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out, lead);
+    return launch(fixed_f32_cq_kernel<float, 8, Shape::kSlots, Shape::kThreads, kNonTemporal, Shape::kXcdRun>, grid, Shape::kThreads, s, grad, err_state, n, k, reset, si, period, codes_out, lead);
 }
 
 template <StreamMode MODE, typename Shape>

@@ -192,10 +192,12 @@ template <typename G, int BITS, int SLOTS, int THREADS, bool NT, int XCDK = 0>
 __global__ void __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, kCqWavesPerSimd)))
 fixed_f32_cq_kernel(const void* __restrict__ grad, float* __restrict__ err, size_t n, FixedScales k, int reset,
                     const long long* __restrict__ step_index, long long reset_period,
-                    uint8_t* __restrict__ codes) {
+                    uint8_t* __restrict__ codes, uint32_t lead_tiles) {
     constexpr size_t TILE = (size_t)kSlot * SLOTS;
     const uint32_t lane = threadIdx.x & (kWave - 1);
-    const size_t tile0 = wave_tile_index<THREADS, XCDK>() * TILE;
+    const size_t wave = wave_tile_index<THREADS, XCDK>();
+    if (wave < lead_tiles) return;   // see xcd_run_lead_tiles
+    const size_t tile0 = (wave - lead_tiles) * TILE;
     if (tile0 >= n) return;
     const bool rst = step_index ? reset_step_due(step_index, reset_period) : reset != 0;   // Eq. 7
 

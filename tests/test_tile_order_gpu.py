@@ -7,6 +7,10 @@ once, whatever part of the last round is empty.  Lengths just below, at and just
 runs and whole rounds, for both workgroup sizes of the block form (4- and 8-bit codes) and for
 the fixed-scale form with the state in float32, against the oracle byte for byte.  With the
 canaries behind every output this also shows that the empty tiles of the last round write nothing.
+
+The runs are laid over the state's ADDRESSES (each starts at a multiple of 128 KB), so as many
+tile indices as the state's first byte lies behind such a multiple stay empty in front: the
+last test moves the state through offsets of 16 bytes to 128 KB within its allocation.
 """
 import numpy as np
 import pytest
@@ -73,3 +77,38 @@ def test_fixed_scale_form_with_fp32_state_around_run_and_round_boundaries(bits):
             assert np.array_equal(codes_t[:cb].cpu().numpy(), c_ref), f"n={n} step={step}: code bytes differ"
             assert np.array_equal(e_t[:n].cpu().numpy(), e_host), f"n={n} step={step}: state differs"
         assert bool((e_t[n:] == 5.0).all()) and bool((codes_t[cb:] == 0xAA).all()), f"n={n}: written past the end"
+
+
+# elements in front of the state inside its allocation (16-byte steps; a tile is 512 elements, a run 32768)
+STATE_OFFSETS = [4, 508, 512, 516, 3 * 512 + 8, 16384 + 4, 32768 - 4, 32768, 32768 + 512]
+
+
+@pytest.mark.parametrize("form,bits,B", [("block", 4, 256), ("block", 8, 64), ("block", 4, 32), ("fixed_f32", 4, 0), ("fixed_f32", 8, 0)])
+def test_state_at_any_16_byte_offset(form, bits, B):
+    for off in STATE_OFFSETS:
+        for n in (RUN - off % RUN + 5, ROUND + 3 * RUN - 2048 + 1, 2 * ROUND - off):
+            print(f"[tile order] {form} bits={bits} B={B} state offset {off} elements, n={n}", flush=True)
+            cb = loco_code_bytes(n, bits)
+            nb = loco_num_blocks(n, B) if form == "block" else 0
+            e_host = np.zeros(n, np.float32)
+            e_all = torch.full((off + n + PAD,), 5.0, dtype=torch.float32, device=DEV)
+            e_t = e_all[off:off + n]
+            e_t.zero_()
+            codes_t = torch.full((cb + PAD,), 0xAA, dtype=torch.uint8, device=DEV)
+            scales_t = torch.full((nb + PAD,), -1.0, dtype=torch.float32, device=DEV)
+            for step in range(2):
+                if form == "block":
+                    g = gradient(n, torch.bfloat16, 13 * n + off + step)
+                    loco_compensate_quantize(g.to(DEV), e_t, bits, B, 0.25, False, codes_t[:cb], scales_t[:nb])
+                    torch.cuda.synchronize()
+                    c_ref, s_ref = oracle.compensate_quantize(workloads.as_numpy_grad(g), e_host, bits, B, 0.25, 0)
+                    assert np.array_equal(scales_t[:nb].cpu().numpy().view(np.uint32), s_ref.view(np.uint32)), f"off={off} n={n}: steps differ"
+                else:
+                    g = (gradient(n, torch.bfloat16, 13 * n + off + step).float() * 1e-2).to(torch.bfloat16)
+                    loco_compensate_quantize_fixed_f32state(g.to(DEV), e_t, bits, 19 if bits == 4 else 17, 0.25, False, codes_t[:cb])
+                    torch.cuda.synchronize()
+                    c_ref = oracle.fixed_compensate_quantize_f32state(workloads.as_numpy_grad(g), e_host, bits, 19 if bits == 4 else 17, 0.25)
+                assert np.array_equal(codes_t[:cb].cpu().numpy(), c_ref), f"off={off} n={n} step={step}: code bytes differ"
+                assert np.array_equal(e_t.cpu().numpy(), e_host), f"off={off} n={n} step={step}: state differs"
+            assert bool((e_all[:off] == 5.0).all()) and bool((e_all[off + n:] == 5.0).all()), f"off={off} n={n}: state written outside"
+            assert bool((codes_t[cb:] == 0xAA).all()) and bool((scales_t[nb:] == -1.0).all()), f"off={off} n={n}: written past the end"
