@@ -124,7 +124,8 @@ loco_status_t loco_compensate_quantize(const void *grad, loco_dtype_t grad_dtype
  * payloads at once: when the strides are multiples of a large power of two (a shard of exactly 2^k
  * elements laid out back to back), those W reads meet in one memory channel and the call can lose up
  * to a quarter of its rate for W >= 32; padding each payload by a few hundred bytes avoids it.  A shard
- * length that is not a multiple of the tile costs nothing measurable.
+ * length that is not a multiple of the tile costs nothing measurable, and neither does a grad_out that
+ * is a slice of a larger buffer (the tile order follows its address).
  */
 loco_status_t loco_dequant_reduce(const uint8_t *codes, size_t code_stride_bytes,
                                   const float *scales, size_t scale_stride_elems,

@@ -276,30 +276,41 @@ int dr_auto_for_large_shards(int bits, int block, int W, Epilogue kind, bool sca
     return kind == Epilogue::kStore && block >= 256 && !dr_few_workers(bits, W) ? kDrQuadLaneSteps : kDrQuad;
 }
 
+// Empty tiles in front of a reduce's tile order, so that its runs of tiles start at multiples of their
+// own size in the ADDRESSES of the array the kernel writes or updates in place (see xcd_run_lead_tiles).
+template <Epilogue EPI>
+uint32_t dr_lead_tiles(const EpilogueArgs& epi, int xcd_run, size_t tile_elems, int waves_per_group) {
+    const void* base = (EPI == Epilogue::kStore || EPI == Epilogue::kStoreBf16) ? epi.out : epi.theta;
+    const size_t elem = EPI == Epilogue::kStoreBf16 ? 2 : 4;
+    return xcd_run_lead_tiles(base, (size_t)xcd_run * waves_per_group * tile_elems * elem, tile_elems * elem);
+}
+
 template <int BITS, int BLOCK, Epilogue EPI, typename Shape, typename S, bool LANE_STEPS, int XCD_RUN = kDrXcdRun>
 loco_status_t launch_dr_quad(hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
+    constexpr size_t kTile = (size_t)kSlot * Shape::kSlots;
+    const uint32_t lead = dr_lead_tiles<EPI>(epi, XCD_RUN, kTile, Shape::kThreads / kWave);
     unsigned grid;
-    if (loco_status_t st = grid_for(a.n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid,
-                                    XCD_RUN ? 8 * XCD_RUN : 1))
+    if (loco_status_t st = grid_for(a.n + lead * kTile, kTile * (Shape::kThreads / kWave), &grid, XCD_RUN ? 8 * XCD_RUN : 1))
         return st;
     constexpr int kWaves = (BITS == 8 && std::is_same_v<Shape, DrFewWorkersShape> && !dr_updates_in_place(EPI))
                                ? kDrFewPayloads8BitWaves : dr_waves_per_simd(EPI);
     return launch(dr_kernel<BITS, BLOCK, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, XCD_RUN, EPI, S,
                             LANE_STEPS, kWaves>,
                   grid, Shape::kThreads, s, a.codes, a.code_stride, static_cast<const S*>(a.scales), a.scale_stride, a.W,
-                  a.n, 1.0f / (float)a.W, epi);
+                  a.n, 1.0f / (float)a.W, epi, lead);
 }
 
 template <int BITS, int BLOCK, int CB, Epilogue EPI = Epilogue::kStore, int XCD_RUN = kDrXcdRun>
 loco_status_t launch_dr_wide(hipStream_t s, const DrArgs& a, const EpilogueArgs& epi) {
     using Shape = DrWideShape<CB>;
     constexpr size_t kUnitElems = (size_t)kWave * (CB * 8 / BITS);
+    const uint32_t lead = dr_lead_tiles<EPI>(epi, XCD_RUN, kUnitElems, Shape::kThreads / kWave);
     unsigned grid;
-    if (loco_status_t st = grid_for(a.n, kUnitElems * (Shape::kThreads / kWave), &grid, XCD_RUN ? 8 * XCD_RUN : 1))
+    if (loco_status_t st = grid_for(a.n + lead * kUnitElems, kUnitElems * (Shape::kThreads / kWave), &grid, XCD_RUN ? 8 * XCD_RUN : 1))
         return st;
     return launch(dr_wide_kernel<BITS, BLOCK, CB, Shape::kThreads, Shape::kInFlight, kNonTemporal, XCD_RUN, EPI, float>,
                   grid, Shape::kThreads, s, a.codes, a.code_stride, static_cast<const float*>(a.scales), a.scale_stride,
-                  a.W, a.n, 1.0f / (float)a.W, epi);
+                  a.W, a.n, 1.0f / (float)a.W, epi, lead);
 }
 
 template <int BITS, int BLOCK, Epilogue EPI>
@@ -483,50 +494,40 @@ loco_status_t reduce_block(const uint8_t* codes, size_t code_stride_bytes, const
 // fused optimizers of the fixed-scale reduce, and slower for the bf16 output.
 template <Epilogue EPI> constexpr int fixed_dr_xcd_run() { return EPI == Epilogue::kStoreBf16 ? 0 : 32; }
 
+// One launch of the fixed-scale reduce in a given shape, tile order and residency.
+template <int BITS, typename Shape, Epilogue EPI, int RUN, int WAVES = fixed_dr_waves_per_simd(EPI)>
+loco_status_t launch_fixed_dr_shape(hipStream_t s, const uint8_t* codes, size_t cs, int W, size_t n, float inv_s,
+                                    float inv_w, const EpilogueArgs& epi) {
+    constexpr size_t kTile = (size_t)kSlot * Shape::kSlots;
+    const uint32_t lead = dr_lead_tiles<EPI>(epi, RUN, kTile, Shape::kThreads / kWave);
+    unsigned grid;
+    if (loco_status_t st = grid_for(n + lead * kTile, kTile * (Shape::kThreads / kWave), &grid, RUN ? 8 * RUN : 1)) return st;
+    return launch(fixed_dr_kernel<BITS, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI, RUN, WAVES>, grid,
+                  Shape::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi, lead);
+}
+
 template <Epilogue EPI>
 loco_status_t launch_fixed_dr(int bits, hipStream_t s, const uint8_t* codes, size_t cs, int W,
                               size_t n, float inv_s, float inv_w, const EpilogueArgs& epi) {
     using Shape = FixedDrShapeFor<EPI>;
     constexpr int kRun = fixed_dr_xcd_run<EPI>();
-    unsigned grid;
-    if (loco_status_t st = grid_for(n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid, kRun ? 8 * kRun : 1))
-        return st;
     if constexpr (EPI == Epilogue::kStore) {
         // few payloads, as for the block form: 4 KB of output per wavefront for two or three payloads of
         // 4-bit codes (78 % of HBM peak against 69 %), 6 resident wavefronts for one payload of 8-bit codes
         // (82 % against 71 %)
-        using Few = DrTwoOrThreeWorkersShape;
-        if (bits == 4 && (W == 2 || W == 3)) {
-            if (loco_status_t st = grid_for(n, (size_t)kSlot * Few::kSlots * (Few::kThreads / kWave), &grid, kRun ? 8 * kRun : 1))
-                return st;
-            return launch(fixed_dr_kernel<4, Few::kSlots, Few::kThreads, Few::kInFlight, kNonTemporal, EPI, kRun>, grid,
-                          Few::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
-        }
-        using One = DrFewWorkersShape;
-        if (bits == 8 && W == 1) {
-            if (loco_status_t st = grid_for(n, (size_t)kSlot * One::kSlots * (One::kThreads / kWave), &grid, kRun ? 8 * kRun : 1))
-                return st;
-            return launch(fixed_dr_kernel<8, One::kSlots, One::kThreads, One::kInFlight, kNonTemporal, EPI, kRun,
-                                          kDrFewPayloads8BitWaves>,
-                          grid, One::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
-        }
-        if (bits == 4 && dr_natural_order(W, n, 4, cs, 0)) {   // see kDrNaturalOrderBytes
-            if (loco_status_t st = grid_for(n, (size_t)kSlot * Shape::kSlots * (Shape::kThreads / kWave), &grid)) return st;
-            return launch(fixed_dr_kernel<4, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI, 0>, grid,
-                          Shape::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
-        }
+        if (bits == 4 && (W == 2 || W == 3))
+            return launch_fixed_dr_shape<4, DrTwoOrThreeWorkersShape, EPI, kRun>(s, codes, cs, W, n, inv_s, inv_w, epi);
+        if (bits == 8 && W == 1)
+            return launch_fixed_dr_shape<8, DrFewWorkersShape, EPI, kRun, kDrFewPayloads8BitWaves>(s, codes, cs, W, n, inv_s, inv_w, epi);
+        if (bits == 4 && dr_natural_order(W, n, 4, cs, 0))   // see kDrNaturalOrderBytes
+            return launch_fixed_dr_shape<4, Shape, EPI, 0>(s, codes, cs, W, n, inv_s, inv_w, epi);
     }
-    if (bits == 4)
-        return launch(fixed_dr_kernel<4, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI, kRun>, grid,
-                      Shape::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
+    if (bits == 4) return launch_fixed_dr_shape<4, Shape, EPI, kRun>(s, codes, cs, W, n, inv_s, inv_w, epi);
     if constexpr (EPI == Epilogue::kStore) {
         if (W >= kFixedDr8ManyWorkers)
-            return launch(fixed_dr_kernel<8, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI, kRun,
-                                          kFixedDr8ManyWorkersWaves>,
-                          grid, Shape::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
+            return launch_fixed_dr_shape<8, Shape, EPI, kRun, kFixedDr8ManyWorkersWaves>(s, codes, cs, W, n, inv_s, inv_w, epi);
     }
-    return launch(fixed_dr_kernel<8, Shape::kSlots, Shape::kThreads, Shape::kInFlight, kNonTemporal, EPI, kRun>, grid,
-                  Shape::kThreads, s, codes, cs, W, n, inv_s, inv_w, epi);
+    return launch_fixed_dr_shape<8, Shape, EPI, kRun>(s, codes, cs, W, n, inv_s, inv_w, epi);
 }
 
 // The reduce kernel sums the integer codes and converts once; every partial sum must stay

@@ -265,12 +265,12 @@ template <int BITS, int SLOTS, int THREADS, int WU, bool NT, Epilogue EPI, int X
           int WAVES = fixed_dr_waves_per_simd(EPI)>
 __global__ void __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, WAVES)))
 fixed_dr_kernel(const uint8_t* __restrict__ codes, size_t code_stride, int W, size_t n, float inv_s,
-                float inv_w, EpilogueArgs epi) {
+                float inv_w, EpilogueArgs epi, uint32_t lead_tiles) {
     constexpr size_t TILE = (size_t)kSlot * SLOTS;
     constexpr uint32_t SLOT_CODE_BYTES = kSlot * BITS / 8;
     constexpr int FLUSH = BITS == 4 ? 16 : 256;   // workers per widening of the packed sums
     const uint32_t lane = threadIdx.x & (kWave - 1);
-    const size_t tile0 = wave_tile_index_tail_first<THREADS, XCDK>(n, TILE) * TILE;
+    const size_t tile0 = wave_tile_index_tail_first<THREADS, XCDK>(n, TILE, lead_tiles) * TILE;
     if (tile0 >= n) return;
 
     if (tile0 + TILE <= n) {
